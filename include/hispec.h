@@ -1,0 +1,182 @@
+/*
+ * hispec.h -- C ABI of the MI355X (gfx950) implementation of HiSpec's k-token
+ * verification path: hierarchical speculative decoding on an early-exit (EE)
+ * transformer (paper: "HiSpec: Hierarchical Speculative Decoding for LLMs").
+ *
+ * One EE model with L_f layers is cut into three contiguous layer groups by its
+ * draft exit L_d and its intermediate exit L_i (paper Sec. 3.1, "Early-Exit
+ * Model"):  G1 = layers 1..L_d,  G2 = L_d+1..L_i,  G3 = L_i+1..L_f.
+ * Every exit reads the hidden state through one shared final RMSNorm and one
+ * shared LM head and takes the arg max (greedy rule of Sec. 3.1; ties go to the
+ * lowest token id).
+ *
+ * Conventions
+ *  - Every call returns EE_OK (0) or a negative EE_ERR_* code; ee_last_error()
+ *    gives a message for the most recent failure on the calling thread.  A call
+ *    that fails leaves the session as it was.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host
+ *    memory.  The two arenas are allocated and owned by the caller and must stay
+ *    alive until the matching *_free call; the library carves them up and never
+ *    allocates device memory inside the draft / verify / rollback calls.
+ *  - `stream` is a hipStream_t passed as void*; all device work of an object is
+ *    enqueued on the stream given at creation.  Calls that return tokens or accept
+ *    lengths synchronise that stream once before returning, so host outputs are
+ *    valid on return.
+ *  - Token ids, lengths and counts are int32.  Positions are 0-based.
+ *  - Not thread safe per object; distinct sessions may be used from distinct threads.
+ *
+ * Per-sequence state (paper Algorithm 2 and Sec. 3.2).  C = committed tokens,
+ * V = tokens tentatively accepted by L_i, T = C||V.  The last token of T is
+ * "pending": it has no KV entry yet.  Between calls
+ *      len(G1) = len(G2) = |T|-1,   len(G3) = |C|-1,
+ * and the session buffers the L_i hidden rows of positions |C|-1 .. |T|-2 (H_i).
+ * KV entries past a group's length are dead: pruning only lowers the length.
+ */
+#ifndef HISPEC_H
+#define HISPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { EE_OK = 0, EE_ERR_ARG = -1, EE_ERR_STATE = -2, EE_ERR_CAPACITY = -3, EE_ERR_HIP = -4 };
+enum { EE_F32 = 0, EE_BF16 = 1 };
+
+/* tensor ids (also the stream ids of the synthetic weight generator) */
+enum {
+  EE_T_EMB = 0, EE_T_HEAD = 1, EE_T_GFINAL = 2, EE_T_G1 = 3, EE_T_WQ = 4, EE_T_WK = 5,
+  EE_T_WV = 6, EE_T_WO = 7, EE_T_G2 = 8, EE_T_WGATE = 9, EE_T_WUP = 10, EE_T_WDOWN = 11
+};
+
+typedef struct ee_config {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int32_t exit_draft;   /* L_d, 1 <= L_d < L_i                        (Sec. 3.1) */
+  int32_t exit_inter;   /* L_i, L_i < n_layers = L_f                             */
+  float rope_theta;     /* rotary base; half-split pairing (i, i + head_dim/2)   */
+  float rms_eps;
+  int32_t dtype;        /* EE_F32: fp32 weights/activations/KV.  EE_BF16: bf16 weights,
+                           bf16 matrix operands and KV, fp32 accumulation, fp32 residual */
+  int32_t bonus_inter;  /* 1: verify k+1 rows at L_i so a fully matching block also yields
+                           L_i's next token (LeadingSubstringVerify as printed); 0: k rows   */
+  int32_t bonus_full;   /* 1: before the L_f pass run the pending token through G1+G2 so a
+                           fully accepted V also yields L_f's next token; 0: |V| rows        */
+  float sigma;          /* std of the synthetic weights (used by seeded init only)           */
+  float gamma[3];       /* synthetic damping of the residual-writing matrices (Wo, Wdown) of
+                           G1, G2, G3; 1 = plain random init                                 */
+} ee_config;
+
+typedef struct ee_model ee_model;
+typedef struct ee_session ee_session;
+
+/* ---- model ------------------------------------------------------------------------------- */
+
+/* Bytes of device memory a model of this shape needs (weights in the library's own layout). */
+size_t ee_model_bytes(const ee_config* cfg);
+
+/* Build a model inside the caller's device arena (256-byte aligned, >= ee_model_bytes()).
+ * Weights are filled ON DEVICE from `seed` with the counter-based generator documented in
+ * ee_model_set_tensor's counterpart below (an EE checkpoint of the paper's kind would instead be
+ * streamed in tensor by tensor with ee_model_set_tensor).  Synchronises `stream`.
+ * Errors: EE_ERR_ARG (bad shape / null / misaligned), EE_ERR_CAPACITY (arena too small),
+ * EE_ERR_HIP. */
+int ee_model_load(const ee_config* cfg, void* dev_arena, size_t arena_bytes, uint64_t seed,
+                  void* stream, ee_model** out);
+
+/* Replace one tensor from host fp32 values in logical row-major [out_features, in_features]
+ * layout (1-D for gains).  `layer` is 0-based and ignored for EMB/HEAD/GFINAL.  Values are
+ * rounded to bf16 (nearest even) for EE_BF16 models.  Allocates a temporary staging buffer. */
+int ee_model_set_tensor(ee_model* m, int tensor_id, int layer, const float* host_values);
+
+/* Read rows [row0, row0+nrows) of a tensor back to host fp32 in logical layout (for gains:
+ * elements).  Used to check the device generator against the host generator bit for bit. */
+int ee_model_get_tensor_rows(ee_model* m, int tensor_id, int layer, int row0, int nrows,
+                             float* host_out);
+
+void ee_model_free(ee_model* m);   /* frees host bookkeeping only; the arena is the caller's */
+
+/* ---- session ----------------------------------------------------------------------------- */
+
+/* A session holds, for `batch` independent sequences: the paged KV cache shared by the three
+ * layer groups (Sec. 3.2; pages of 64 positions, one block table per sequence, as in the
+ * batched-inference section), the buffered exit hidden states H_d / H_i, the tentative buffer V
+ * and the work buffers of one forward pass.
+ *   max_ctx  : largest number of positions any one sequence may hold (incl. speculative rows)
+ *   max_rows : largest number of rows one sequence contributes to one call, also the capacity
+ *              of H_d / H_i / V per sequence (>= rounds_between_full_verifies*(k+1) + 1)
+ *   total_pages : size of the shared page pool, 0 = batch * ceil(max_ctx/64)               */
+size_t ee_session_bytes(const ee_model* m, int batch, int max_ctx, int max_rows, int total_pages);
+int ee_session_create(ee_model* m, int batch, int max_ctx, int max_rows, int total_pages,
+                      void* dev_arena, size_t arena_bytes, void* stream, ee_session** out);
+void ee_session_free(ee_session* s);
+
+/* Context build.  tokens: host, the prompts packed back to back; lens: host [batch], each >= 1.
+ * Runs all L_f layers over every prompt (in row chunks), leaves all three group lengths at
+ * lens[b], and commits first_token[b] = arg max at L_f of the last prompt position
+ * (the "Vanilla generation" step of Sec. 3.1).  first_token: host [batch]. */
+int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* lens, int32_t* first_token);
+
+/* Generate(L_d, x||V, k) of Algorithm 2: k sequential single-row passes through G1 + exit head +
+ * arg max per sequence, each appending one KV row per G1 layer and one H_d row (Sec. 3.2,
+ * "expanding during draft generation").  With bonus_inter one more G1-only row is run for the
+ * last draft token.  draft: host [batch, k] out.  Errors: EE_ERR_STATE if a draft block is
+ * already pending, EE_ERR_CAPACITY if positions or rows would overflow. */
+int ee_draft(ee_session* s, int k, int32_t* draft);
+
+/* Same state transition for an externally supplied draft block (host [batch, k]): G1 runs
+ * block-parallel on the rows [pending token, S_1 .. S_k] (k+1 rows, k without bonus_inter). */
+int ee_draft_inject(ee_session* s, int k, const int32_t* draft);
+
+/* LeadingSubstringVerify(S, L_i, x||V) of Algorithm 2 for every sequence with a pending draft
+ * block: the buffered H_d rows run through G2 block-causally against the shared KV cache, the
+ * exit head + arg max gives v_1..v_rows, a = number of leading draft tokens equal to v.  Appends
+ * [S_1..S_a, v_{a+1}] to V (only S when all k matched and no bonus row exists), keeps the L_i
+ * hidden rows of the surviving positions in H_i, prunes G1/G2 KV to the surviving length, drops
+ * H_d.  n_accept: host [batch] (0..k); next_token: host [batch] (v_{a+1}, or -1 if none). */
+int ee_verify_intermediate(ee_session* s, int32_t* n_accept, int32_t* next_token);
+
+/* LeadingSubstringVerify(V, L_f, x) of Algorithm 2 for every sequence with active[b] != 0
+ * (null = all) and a non-empty V: the buffered H_i rows (after the pending token's catch-up
+ * through G1+G2 when bonus_full) run through G3, exit head + arg max, f = leading matches with V.
+ * Commits [V_1..V_f, w_{f+1}] (only V when all matched and no bonus row), prunes all three
+ * groups to |C|-1 and empties V and H_i (Sec. 3.2, last sentence).
+ * n_accept, next_token, n_committed: host [batch]; committed: host [batch, max_rows+1], the newly
+ * committed tokens of each sequence.  Inactive sequences report n_accept = -1, n_committed = 0. */
+int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
+                   int32_t* committed, int32_t* n_committed);
+
+/* In-place KV length rollback of one sequence (Sec. 3.2 "pruning"): keep `new_len` positions.
+ * group_mask bit0 = G1, bit1 = G2, bit2 = G3.  G1 and G2 move together: T is cut to new_len+1
+ * tokens (the last becomes pending), V / H_i follow; if the cut reaches committed tokens V is
+ * emptied and bit2 must be set (G3 is cut to new_len as well).  A pending draft block is dropped.
+ * Only integers and the block-table tail change; no KV bytes move.  Shrink only:
+ * EE_ERR_ARG if new_len exceeds the current length or the mask is inconsistent. */
+int kv_rollback(ee_session* s, int seq, int group_mask, int new_len);
+
+/* ---- introspection (parity tests; not part of the timed path) ---------------------------- */
+int ee_get_lengths(const ee_session* s, int32_t* len_3_by_batch);           /* host [batch,3]      */
+int ee_get_counts(const ee_session* s, int32_t* n_committed, int32_t* n_tentative); /* [batch] each */
+int ee_get_tokens(const ee_session* s, int seq, int32_t* out, int cap, int32_t* n_out); /* T = C||V */
+/* When enabled, every exit-head call also stores full fp32 logits for its rows. */
+int ee_debug_enable_logits(ee_session* s, int on);
+int ee_debug_last_logits(ee_session* s, float* host_out, int max_rows, int32_t* n_rows);  /* [rows, vocab] */
+int ee_debug_last_hidden(ee_session* s, float* host_out, int max_rows, int32_t* n_rows);  /* [rows, d]     */
+/* K and V of `n` positions from pos0 of one layer, logical layout [n, n_kv_heads, head_dim]. */
+int ee_debug_read_kv(ee_session* s, int seq, int layer, int pos0, int n, float* k_out, float* v_out);
+/* Overwrite every dead KV entry (position >= the group's length, in owned pages) of a sequence
+ * with NaN: a test that pruned entries can never leak into a later result. */
+int ee_debug_poison_dead_kv(ee_session* s, int seq);
+/* Per-kernel launch accounting of the most recent draft/verify call: number of kernel launches
+ * and, when enabled with ee_debug_time_kernels, HIP-event time (ms) per kernel family.        */
+int ee_debug_time_kernels(ee_session* s, int on);
+int ee_debug_kernel_times(ee_session* s, int32_t* n_families, const char** names /*[16]*/,
+                          float* ms /*[16]*/, int32_t* launches /*[16]*/);
+
+const char* ee_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HISPEC_H */

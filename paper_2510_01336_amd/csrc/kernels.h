@@ -1,0 +1,50 @@
+// Launchers of the HIP kernels (internal).  All work is enqueued on `st`; nothing synchronises.
+#pragma once
+#include "common.h"
+
+// ---- dtype-independent ---------------------------------------------------------------------
+// X[r][:] = float(emb[tok[r]][:])
+void k_embed(hipStream_t st, bool bf16, const void* emb, const int* tok, float* X, int M, int d);
+// dst[dst_idx[r]][:] = src[src_idx[r]][:]   (null index = identity)
+void k_copy_rows(hipStream_t st, float* dst, const int* dst_idx, int dst_add, const float* src, const int* src_idx, int M, int d);
+// per sequence: a = number of leading j < n_cand[b] with cand[b][j] == v[row0[b]+j];
+// next = v[row0+a] if a < m[b] else -1.  Sequences with m[b] == 0 report (-1, -1).
+void k_accept(hipStream_t st, const int* v, const CallMeta& meta, int cand_stride, int B, int* n_accept, int* next_tok);
+// sequential drafting, one row per sequence: tok_next[r] = v[r]; draft_out[row_seq[r]*stride + j] = v[r]
+void k_take_token(hipStream_t st, const int* v, const int* row_seq, int M, int* tok_next, int* draft_out, int stride, int j);
+// cos/sin table for the rows of this call: cs[r][i] = (cos, sin)(pos_r * inv_freq[i]), evaluated in double
+void k_rope_table(hipStream_t st, const int* row_pos, int pos_add, const double* inv_freq, float2* cs, int M, int half);
+void k_fill_nan_dead_kv(hipStream_t st, bool bf16, void* kv, const int* pages, int n_owned_pages, int len,
+                        int layer0, int layer1, int n_pages, int n_kv, int D);
+void k_read_kv(hipStream_t st, bool bf16, const void* kv, const int* pages, int layer, int pos0, int n,
+               int n_pages, int n_kv, int D, float* k_out, float* v_out);
+
+// ---- fp32 reference-precision path (EE_F32 models) -----------------------------------------
+void f32_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, float* out, int M, int d);
+// Y[m][n] (+)= sum_k A[m][k] W[n][k];  A row-major lda, W row-major [N][K], Y row-major ldy
+void f32_gemm(hipStream_t st, const float* A, int lda, const float* W, float* Y, int ldy, int M, int N, int K, bool add);
+void f32_rope_append(hipStream_t st, const float* QKV, int ldq, const float2* cs, const CallMeta& meta, int pos_add, int M,
+                     int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq, float* Q, float* kv);
+void f32_attention(hipStream_t st, const float* Q, const float* kv, const CallMeta& meta, int pos_add, int M, int Hq, int Hkv,
+                   int D, int layer, int n_pages, int pages_per_seq, int max_ctx, float* out);
+void f32_silu_mul(hipStream_t st, const float* GU, int ldg, float* H, int M, int F);
+void f32_argmax(hipStream_t st, const float* logits, int M, int V, int* v);
+
+// ---- bf16 MFMA path (EE_BF16 models) ---------------------------------------------------------
+enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2, EPI_ARGMAX = 3 };
+struct GemmOut {
+  float* Y = nullptr; int ldy = 0;        // EPI_STORE / EPI_ADD target (row-major fp32); EPI_ARGMAX: optional logits
+  bf16_t* H = nullptr; int h_ktiles = 0;  // EPI_SWIGLU target (fragment layout)
+  float* pmax = nullptr; int* pidx = nullptr; int pstride = 0;   // EPI_ARGMAX partials [ntiles][pstride]
+};
+// Y^T tile = W tile (A operand) x X^T (B operand); W, A in fragment layout; M <= 64 rows per launch
+void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out);
+void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf16_t* out, int ktiles, int M, int d);
+void bf16_rope_append(hipStream_t st, const float* QKV, int ldq, const float2* cs, const CallMeta& meta, int pos_add, int M,
+                      int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq, int total_qt,
+                      bf16_t* Q, bf16_t* kv);
+struct AttnScratch { float* part_o; float* part_ml; int max_splits; };
+void bf16_attention(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,
+                    int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
+                    const AttnScratch& scr, bf16_t* out, int out_ktiles);
+void bf16_argmax_reduce(hipStream_t st, const float* pmax, const int* pidx, int ntiles, int pstride, int M, int* v);

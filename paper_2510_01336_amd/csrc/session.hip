@@ -1,0 +1,800 @@
+// Session state machine and C ABI of the draft / verify / rollback calls (Algorithm 2 of the paper
+// with the KV-cache and hidden-state reuse of its Sec. 3.2).  Host code only decides shapes and
+// keeps the integer bookkeeping; every arithmetic step runs in the kernels of kernels_*.hip.
+#include "kernels.h"
+#include <algorithm>
+#include <cstring>
+
+struct SeqState {
+  std::vector<int> C, V, S;   // committed, tentative, pending draft block
+  int len[3] = {0, 0, 0};     // KV length per layer group
+  int n_hd = 0;               // buffered L_d hidden rows (pending draft block incl. bonus row)
+  std::vector<int> pages;     // block table
+  bool started = false;
+};
+
+struct MetaSlot {             // one upload region: host (pinned) + device copy, same layout
+  int* h = nullptr;
+  int* d = nullptr;
+  hipEvent_t copied = nullptr;
+  bool in_flight = false;
+};
+
+struct KTimer { int fam; hipEvent_t a, b; };
+
+struct ee_session {
+  ee_model* m = nullptr;
+  hipStream_t st = nullptr;
+  int B = 0, max_ctx = 0, max_rows = 0, pps = 0, n_pages = 0, maxM = 0, Mp = 0, maxQT = 0, chunk = 0;
+  char* base = nullptr;
+  size_t bytes = 0;
+  // device buffers (inside the caller's arena)
+  void* kv = nullptr;
+  float *X = nullptr, *QKV = nullptr, *GU = nullptr, *LOGITS = nullptr, *Hd = nullptr, *Hi = nullptr;
+  void *XN = nullptr, *Qb = nullptr, *AO = nullptr, *H = nullptr;
+  float2* cs = nullptr;
+  int *vtok = nullptr, *tok_next = nullptr, *draft_dev = nullptr, *out_dev = nullptr, *page_scratch = nullptr;
+  float *part_o = nullptr, *part_ml = nullptr, *pmax = nullptr;
+  int* pidx = nullptr;
+  int max_splits = 64;
+  // host side
+  MetaSlot slot[2];
+  size_t meta_ints = 0;
+  int* out_host = nullptr;    // pinned: n_accept[B], next[B], draft [B*max_rows]
+  std::vector<SeqState> seq;
+  std::vector<int> free_pages;
+  bool debug_logits = false, time_kernels = false;
+  int last_rows = 0;
+  std::vector<KTimer> timers;
+  int launches[KF_COUNT] = {0};
+  // meta layout (offsets in ints)
+  size_t o_row_seq, o_row_pos, o_row_tok, o_row_src, o_row_dst, o_seq_row0, o_seq_m, o_seq_p0, o_seq_qt0, o_qt_seq,
+      o_qt_local, o_cand, o_n_cand, o_bt;
+  int cand_stride = 0;
+};
+
+static const char* kFamName[KF_COUNT] = {"embed", "rmsnorm", "gemm_qkv", "rope_append", "attention", "attn_combine", "gemm_o",
+                                         "gemm_gate_up", "gemm_down", "gemm_head", "argmax", "accept", "copy_rows", "misc"};
+
+// ---------------------------------------------------------------------------------------------
+// arena carving
+// ---------------------------------------------------------------------------------------------
+struct Carver {
+  char* base; size_t cur = 0;
+  template <class T> T* take(size_t n) {
+    cur = align_up(cur, 256);
+    T* p = base ? (T*)(base + cur) : nullptr;
+    cur += n * sizeof(T);
+    return p;
+  }
+};
+
+static void layout_meta(ee_session* s) {
+  size_t o = 0;
+  auto take = [&](size_t n) { size_t r = o; o += (n + 3) / 4 * 4; return r; };
+  s->cand_stride = s->max_rows + 1;
+  s->o_row_seq = take(s->maxM); s->o_row_pos = take(s->maxM); s->o_row_tok = take(s->maxM);
+  s->o_row_src = take(s->maxM); s->o_row_dst = take(s->maxM);
+  s->o_seq_row0 = take(s->B); s->o_seq_m = take(s->B); s->o_seq_p0 = take(s->B); s->o_seq_qt0 = take(s->B);
+  s->o_qt_seq = take(s->maxQT); s->o_qt_local = take(s->maxQT);
+  s->o_cand = take((size_t)s->B * s->cand_stride); s->o_n_cand = take(s->B);
+  s->o_bt = take((size_t)s->B * s->pps);
+  s->meta_ints = o;
+}
+
+static size_t carve(ee_session* s, char* base) {
+  const ee_model* m = s->m;
+  const ee_config& c = m->cfg;
+  const bool bf = m->bf16;
+  const int d = c.d_model, D = c.head_dim, Hq = c.n_q_heads, Hkv = c.n_kv_heads;
+  const int rep = Hq / Hkv;
+  Carver cv{base};
+  const size_t es = bf ? 2 : 4;
+  const int Mp = s->Mp;
+  s->kv = cv.take<char>((size_t)c.n_layers * s->n_pages * Hkv * 2 * EE_PAGE * D * es);
+  s->X = cv.take<float>((size_t)s->maxM * d);
+  s->XN = bf ? (void*)cv.take<bf16_t>((size_t)Mp * ceil_div(d, 32) * 32) : (void*)cv.take<float>((size_t)s->maxM * d);
+  const int nqkv = (Hq + 2 * Hkv) * D, nqkv_p = bf ? ceil_div(nqkv, 16) * 16 : nqkv;
+  s->QKV = cv.take<float>((size_t)s->maxM * nqkv_p);
+  s->Qb = bf ? (void*)cv.take<bf16_t>((size_t)Hkv * s->maxQT * 16 * D) : (void*)cv.take<float>((size_t)s->maxM * Hq * D);
+  s->AO = bf ? (void*)cv.take<bf16_t>((size_t)Mp * ceil_div(Hq * D, 32) * 32) : (void*)cv.take<float>((size_t)s->maxM * Hq * D);
+  s->GU = bf ? nullptr : cv.take<float>((size_t)s->maxM * 2 * m->Fp);
+  s->H = bf ? (void*)cv.take<bf16_t>((size_t)Mp * ceil_div(c.d_ffn, 32) * 32) : (void*)cv.take<float>((size_t)s->maxM * c.d_ffn);
+  s->LOGITS = cv.take<float>((size_t)s->maxM * c.vocab);
+  s->Hd = cv.take<float>((size_t)s->B * s->max_rows * d);
+  s->Hi = cv.take<float>((size_t)s->B * s->max_rows * d);
+  s->cs = cv.take<float2>((size_t)s->maxM * (D / 2));
+  s->vtok = cv.take<int>(s->maxM);
+  s->tok_next = cv.take<int>(s->maxM);
+  s->draft_dev = cv.take<int>((size_t)s->B * s->max_rows);
+  s->out_dev = cv.take<int>(2 * (size_t)s->B);
+  s->page_scratch = cv.take<int>(s->pps);
+  if (bf) {
+    s->part_o = cv.take<float>((size_t)s->maxQT * Hkv * s->max_splits * 16 * D);
+    s->part_ml = cv.take<float>((size_t)s->maxQT * Hkv * s->max_splits * 32);
+    s->pmax = cv.take<float>((size_t)m->head.ntiles() * Mp);
+    s->pidx = cv.take<int>((size_t)m->head.ntiles() * Mp);
+  }
+  s->slot[0].d = cv.take<int>(s->meta_ints);
+  s->slot[1].d = cv.take<int>(s->meta_ints);
+  (void)rep;
+  return align_up(cv.cur, 256);
+}
+
+static int shape_session(ee_session* s, const ee_model* m, int batch, int max_ctx, int max_rows, int total_pages) {
+  if (!m || batch < 1 || max_ctx < 2 || max_rows < 2) { ee_set_error("bad session shape"); return EE_ERR_ARG; }
+  if (!m->bf16 && max_ctx > 8192) { ee_set_error("EE_F32 sessions support max_ctx <= 8192"); return EE_ERR_ARG; }
+  const int rep = m->cfg.n_q_heads / m->cfg.n_kv_heads;
+  s->m = const_cast<ee_model*>(m);
+  s->B = batch; s->max_ctx = max_ctx; s->max_rows = max_rows;
+  s->pps = ceil_div(max_ctx, EE_PAGE);
+  s->n_pages = total_pages > 0 ? total_pages : batch * s->pps;
+  s->chunk = 64;                                        // prefill rows per pass
+  s->maxM = std::max(batch * max_rows, s->chunk);
+  s->Mp = ceil_div(s->maxM, 64) * 64;                   // activation rows padded to whole 64-row GEMM passes
+  s->maxQT = ceil_div(s->maxM * rep, 16) + batch;
+  layout_meta(s);
+  return EE_OK;
+}
+
+extern "C" size_t ee_session_bytes(const ee_model* m, int batch, int max_ctx, int max_rows, int total_pages) {
+  ee_session tmp;
+  if (shape_session(&tmp, m, batch, max_ctx, max_rows, total_pages) != EE_OK) return 0;
+  return carve(&tmp, nullptr);
+}
+
+extern "C" int ee_session_create(ee_model* m, int batch, int max_ctx, int max_rows, int total_pages, void* dev_arena,
+                                 size_t arena_bytes, void* stream, ee_session** out) {
+  if (!out || !dev_arena || ((uintptr_t)dev_arena & 255)) { ee_set_error("arena must be non-null and 256-byte aligned"); return EE_ERR_ARG; }
+  ee_session* s = new ee_session();
+  int rc = shape_session(s, m, batch, max_ctx, max_rows, total_pages);
+  if (rc != EE_OK) { delete s; return rc; }
+  s->st = (hipStream_t)stream;
+  s->base = (char*)dev_arena;
+  s->bytes = carve(s, s->base);
+  if (arena_bytes < s->bytes) {
+    ee_set_error("session arena too small: %zu < %zu", arena_bytes, s->bytes);
+    delete s; return EE_ERR_CAPACITY;
+  }
+  hipError_t e = hipMemsetAsync(s->base, 0, s->bytes, s->st);
+  for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+    e = hipHostMalloc((void**)&s->slot[i].h, s->meta_ints * sizeof(int), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->slot[i].copied, hipEventDisableTiming);
+  }
+  if (e == hipSuccess) e = hipHostMalloc((void**)&s->out_host, (2 * (size_t)batch + (size_t)batch * max_rows) * sizeof(int), hipHostMallocDefault);
+  if (e == hipSuccess) e = hipStreamSynchronize(s->st);
+  if (e != hipSuccess) { ee_set_error("session create: %s", hipGetErrorString(e)); ee_session_free(s); return EE_ERR_HIP; }
+  s->seq.resize(batch);
+  s->free_pages.resize(s->n_pages);
+  for (int i = 0; i < s->n_pages; ++i) s->free_pages[i] = s->n_pages - 1 - i;   // pop_back hands out 0, 1, 2, ...
+  *out = s;
+  return EE_OK;
+}
+
+extern "C" void ee_session_free(ee_session* s) {
+  if (!s) return;
+  if (s->st) (void)hipStreamSynchronize(s->st);
+  for (auto& t : s->timers) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
+  for (int i = 0; i < 2; ++i) {
+    if (s->slot[i].h) (void)hipHostFree(s->slot[i].h);
+    if (s->slot[i].copied) (void)hipEventDestroy(s->slot[i].copied);
+  }
+  if (s->out_host) (void)hipHostFree(s->out_host);
+  delete s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// pages
+// ---------------------------------------------------------------------------------------------
+static int pages_needed_total(const ee_session* s, const std::vector<int>& want_positions) {
+  int need = 0;
+  for (int b = 0; b < s->B; ++b) {
+    int have = (int)s->seq[b].pages.size(), want = ceil_div(want_positions[b], EE_PAGE);
+    if (want > have) need += want - have;
+  }
+  return need;
+}
+// make sure sequence b owns pages for positions [0, n)
+static int grow_pages(ee_session* s, int b, int n) {
+  SeqState& q = s->seq[b];
+  while ((int)q.pages.size() * EE_PAGE < n) {
+    if (s->free_pages.empty() || (int)q.pages.size() >= s->pps) { ee_set_error("KV page pool exhausted"); return EE_ERR_CAPACITY; }
+    q.pages.push_back(s->free_pages.back());
+    s->free_pages.pop_back();
+  }
+  return EE_OK;
+}
+// give back pages no group needs any more (Sec. 3.2 pruning: only the table tail changes)
+static void trim_pages(ee_session* s, int b) {
+  SeqState& q = s->seq[b];
+  int keep = ceil_div(std::max(q.len[0], std::max(q.len[1], q.len[2])) + 1, EE_PAGE);
+  while ((int)q.pages.size() > keep) { s->free_pages.push_back(q.pages.back()); q.pages.pop_back(); }
+}
+static int check_capacity(ee_session* s, const std::vector<int>& want_positions) {
+  for (int b = 0; b < s->B; ++b)
+    if (want_positions[b] > s->max_ctx) { ee_set_error("sequence %d would need %d positions (max_ctx %d)", b, want_positions[b], s->max_ctx); return EE_ERR_CAPACITY; }
+  if (pages_needed_total(s, want_positions) > (int)s->free_pages.size()) { ee_set_error("KV page pool exhausted"); return EE_ERR_CAPACITY; }
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-call metadata
+// ---------------------------------------------------------------------------------------------
+struct CallPlan {
+  int M = 0, n_active = 0, max_m = 0, total_qt = 0, max_kv_end = 0;
+  std::vector<int> m, p0;        // per sequence rows and first position (m = 0: not taking part)
+};
+
+static CallMeta meta_ptrs(const ee_session* s, const int* d) {
+  CallMeta c;
+  c.row_seq = d + s->o_row_seq; c.row_pos = d + s->o_row_pos; c.row_tok = d + s->o_row_tok;
+  c.row_src = d + s->o_row_src; c.row_dst = d + s->o_row_dst;
+  c.seq_row0 = d + s->o_seq_row0; c.seq_m = d + s->o_seq_m; c.seq_p0 = d + s->o_seq_p0; c.seq_qt0 = d + s->o_seq_qt0;
+  c.qt_seq = d + s->o_qt_seq; c.qt_local = d + s->o_qt_local; c.cand = d + s->o_cand; c.n_cand = d + s->o_n_cand;
+  c.block_table = d + s->o_bt;
+  return c;
+}
+
+// Fill slot `si` from the plan: rows are packed sequence by sequence.  The callbacks give the
+// per-row token / gather source / scatter destination; candidates are filled by the caller.
+template <class RowFn>
+static int build_meta(ee_session* s, int si, CallPlan& p, RowFn row_fn) {
+  MetaSlot& sl = s->slot[si];
+  if (sl.in_flight) { HIP_TRY(hipEventSynchronize(sl.copied)); sl.in_flight = false; }
+  int* h = sl.h;
+  const int rep = s->m->cfg.n_q_heads / s->m->cfg.n_kv_heads;
+  int row = 0, qt = 0;
+  p.M = 0; p.n_active = 0; p.max_m = 0; p.max_kv_end = 0;
+  for (int b = 0; b < s->B; ++b) {
+    int m = p.m[b];
+    h[s->o_seq_row0 + b] = row; h[s->o_seq_m + b] = m; h[s->o_seq_p0 + b] = p.p0[b]; h[s->o_seq_qt0 + b] = qt;
+    h[s->o_n_cand + b] = 0;
+    if (m == 0) continue;
+    p.n_active++; p.max_m = std::max(p.max_m, m); p.max_kv_end = std::max(p.max_kv_end, p.p0[b] + m);
+    for (int r = 0; r < m; ++r, ++row) {
+      h[s->o_row_seq + row] = b; h[s->o_row_pos + row] = p.p0[b] + r;
+      int tok = 0, src = 0, dst = 0;
+      row_fn(b, r, tok, src, dst);
+      h[s->o_row_tok + row] = tok; h[s->o_row_src + row] = src; h[s->o_row_dst + row] = dst;
+    }
+    int nqt = ceil_div(m * rep, 16);
+    for (int t = 0; t < nqt; ++t, ++qt) { h[s->o_qt_seq + qt] = b; h[s->o_qt_local + qt] = t; }
+  }
+  p.M = row; p.total_qt = qt;
+  if (row > s->maxM || qt > s->maxQT) { ee_set_error("internal: call exceeds work buffers (%d rows)", row); return EE_ERR_CAPACITY; }
+  for (int b = 0; b < s->B; ++b) {
+    const SeqState& q = s->seq[b];
+    for (size_t i = 0; i < q.pages.size(); ++i) h[s->o_bt + (size_t)b * s->pps + i] = q.pages[i];
+  }
+  return EE_OK;
+}
+static int upload_meta(ee_session* s, int si) {
+  MetaSlot& sl = s->slot[si];
+  HIP_TRY(hipMemcpyAsync(sl.d, sl.h, s->meta_ints * sizeof(int), hipMemcpyHostToDevice, s->st));
+  HIP_TRY(hipEventRecord(sl.copied, s->st));
+  sl.in_flight = true;
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// launch accounting
+// ---------------------------------------------------------------------------------------------
+struct Scope {
+  ee_session* s; int fam; hipEvent_t a = nullptr, b = nullptr;
+  Scope(ee_session* s_, int f) : s(s_), fam(f) {
+    s->launches[fam]++;
+    if (s->time_kernels) {
+      (void)hipEventCreate(&a); (void)hipEventCreate(&b); (void)hipEventRecord(a, s->st);
+    }
+  }
+  ~Scope() {
+    if (a) { (void)hipEventRecord(b, s->st); s->timers.push_back({fam, a, b}); }
+  }
+};
+#define KF(fam, call) do { Scope sc_(s, fam); call; } while (0)
+
+static void reset_accounting(ee_session* s) {
+  for (auto& t : s->timers) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
+  s->timers.clear();
+  memset(s->launches, 0, sizeof(s->launches));
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward pass pieces
+// ---------------------------------------------------------------------------------------------
+static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const CallMeta& mt, int pos_add) {
+  const ee_model* m = s->m;
+  const ee_config& c = m->cfg;
+  const int d = c.d_model, D = c.head_dim, Hq = c.n_q_heads, Hkv = c.n_kv_heads, M = p.M;
+  hipStream_t st = s->st;
+  KF(KF_ROPE, k_rope_table(st, mt.row_pos, pos_add, m->inv_freq, s->cs, M, D / 2));
+  for (int l = l0; l < l1; ++l) {
+    const LayerLoc& L = m->L[l];
+    const float* g1 = (const float*)(m->base + L.g1);
+    const float* g2 = (const float*)(m->base + L.g2);
+    if (m->bf16) {
+      const bf16_t* Wqkv = (const bf16_t*)(m->base + L.qkv.off);
+      const bf16_t* Wo = (const bf16_t*)(m->base + L.o.off);
+      const bf16_t* Wgu = (const bf16_t*)(m->base + L.gu.off);
+      const bf16_t* Wd = (const bf16_t*)(m->base + L.down.off);
+      GemmOut o;
+      KF(KF_NORM, bf16_rmsnorm(st, s->X, g1, c.rms_eps, (bf16_t*)s->XN, L.qkv.ktiles(), M, d));
+      o = GemmOut(); o.Y = s->QKV; o.ldy = L.qkv.Np;
+      KF(KF_GEMM_QKV, bf16_gemm(st, EPI_STORE, Wqkv, L.qkv.ntiles(), L.qkv.ktiles(), (const bf16_t*)s->XN, M, L.qkv.N, o));
+      KF(KF_ROPE, bf16_rope_append(st, s->QKV, L.qkv.Np, s->cs, mt, pos_add, M, Hq, Hkv, D, l, s->n_pages, s->pps, p.total_qt,
+                                   (bf16_t*)s->Qb, (bf16_t*)s->kv));
+      AttnScratch scr{s->part_o, s->part_ml, s->max_splits};
+      KF(KF_ATTN, bf16_attention(st, (const bf16_t*)s->Qb, (const bf16_t*)s->kv, mt, pos_add, s->B, p.max_m, p.total_qt,
+                                 p.max_kv_end + pos_add, Hq, Hkv, D, l, s->n_pages, s->pps, scr, (bf16_t*)s->AO, L.o.ktiles()));
+      o = GemmOut(); o.Y = s->X; o.ldy = d;
+      KF(KF_GEMM_O, bf16_gemm(st, EPI_ADD, Wo, L.o.ntiles(), L.o.ktiles(), (const bf16_t*)s->AO, M, L.o.N, o));
+      KF(KF_NORM, bf16_rmsnorm(st, s->X, g2, c.rms_eps, (bf16_t*)s->XN, L.gu.ktiles(), M, d));
+      o = GemmOut(); o.H = (bf16_t*)s->H; o.h_ktiles = L.down.ktiles();
+      KF(KF_GEMM_GU, bf16_gemm(st, EPI_SWIGLU, Wgu, L.gu.ntiles(), L.gu.ktiles(), (const bf16_t*)s->XN, M, L.gu.N, o));
+      o = GemmOut(); o.Y = s->X; o.ldy = d;
+      KF(KF_GEMM_DOWN, bf16_gemm(st, EPI_ADD, Wd, L.down.ntiles(), L.down.ktiles(), (const bf16_t*)s->H, M, L.down.N, o));
+    } else {
+      const float* Wqkv = (const float*)(m->base + L.qkv.off);
+      const float* Wo = (const float*)(m->base + L.o.off);
+      const float* Wgu = (const float*)(m->base + L.gu.off);
+      const float* Wd = (const float*)(m->base + L.down.off);
+      KF(KF_NORM, f32_rmsnorm(st, s->X, g1, c.rms_eps, (float*)s->XN, M, d));
+      KF(KF_GEMM_QKV, f32_gemm(st, (const float*)s->XN, d, Wqkv, s->QKV, L.qkv.N, M, L.qkv.N, d, false));
+      KF(KF_ROPE, f32_rope_append(st, s->QKV, L.qkv.N, s->cs, mt, pos_add, M, Hq, Hkv, D, l, s->n_pages, s->pps, (float*)s->Qb, (float*)s->kv));
+      KF(KF_ATTN, f32_attention(st, (const float*)s->Qb, (const float*)s->kv, mt, pos_add, M, Hq, Hkv, D, l, s->n_pages, s->pps,
+                                s->max_ctx, (float*)s->AO));
+      KF(KF_GEMM_O, f32_gemm(st, (const float*)s->AO, Hq * D, Wo, s->X, d, M, d, Hq * D, true));
+      KF(KF_NORM, f32_rmsnorm(st, s->X, g2, c.rms_eps, (float*)s->XN, M, d));
+      KF(KF_GEMM_GU, f32_gemm(st, (const float*)s->XN, d, Wgu, s->GU, 2 * m->Fp, M, 2 * m->Fp, d, false));
+      KF(KF_GEMM_GU, f32_silu_mul(st, s->GU, 2 * m->Fp, (float*)s->H, M, c.d_ffn));
+      KF(KF_GEMM_DOWN, f32_gemm(st, (const float*)s->H, c.d_ffn, Wd, s->X, d, M, d, c.d_ffn, true));
+    }
+  }
+}
+
+// shared final RMSNorm + shared LM head + arg max for rows 0..M-1 of X -> vtok
+static void exit_head(ee_session* s, int M) {
+  const ee_model* m = s->m;
+  const ee_config& c = m->cfg;
+  hipStream_t st = s->st;
+  const float* gf = (const float*)(m->base + m->gfinal);
+  if (m->bf16) {
+    KF(KF_NORM, bf16_rmsnorm(st, s->X, gf, c.rms_eps, (bf16_t*)s->XN, m->head.ktiles(), M, c.d_model));
+    GemmOut o;
+    const int Mp = s->Mp;
+    o.pmax = s->pmax; o.pidx = s->pidx; o.pstride = Mp;
+    if (s->debug_logits) { o.Y = s->LOGITS; o.ldy = c.vocab; }
+    KF(KF_GEMM_HEAD, bf16_gemm(st, EPI_ARGMAX, (const bf16_t*)(m->base + m->head.off), m->head.ntiles(), m->head.ktiles(),
+                               (const bf16_t*)s->XN, M, c.vocab, o));
+    KF(KF_ARGMAX, bf16_argmax_reduce(st, s->pmax, s->pidx, m->head.ntiles(), Mp, M, s->vtok));
+  } else {
+    KF(KF_NORM, f32_rmsnorm(st, s->X, gf, c.rms_eps, (float*)s->XN, M, c.d_model));
+    KF(KF_GEMM_HEAD, f32_gemm(st, (const float*)s->XN, c.d_model, (const float*)(m->base + m->head.off), s->LOGITS, c.vocab, M,
+                              c.vocab, c.d_model, false));
+    KF(KF_ARGMAX, f32_argmax(st, s->LOGITS, M, c.vocab, s->vtok));
+  }
+  s->last_rows = M;
+}
+
+static int finish(ee_session* s) {
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(s->st));
+  for (int i = 0; i < 2; ++i) s->slot[i].in_flight = false;
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI: prefill
+// ---------------------------------------------------------------------------------------------
+extern "C" int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* lens, int32_t* first_token) {
+  if (!s || !tokens || !lens || !first_token) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  const ee_config& c = s->m->cfg;
+  std::vector<int> want(s->B);
+  size_t total = 0;
+  for (int b = 0; b < s->B; ++b) {
+    if (lens[b] < 1) { ee_set_error("prompt %d is empty", b); return EE_ERR_ARG; }
+    want[b] = lens[b] + 1;
+    total += lens[b];
+  }
+  for (size_t i = 0; i < total; ++i)
+    if (tokens[i] < 0 || tokens[i] >= c.vocab) { ee_set_error("token id out of range"); return EE_ERR_ARG; }
+  // restart every sequence from scratch
+  for (int b = 0; b < s->B; ++b) {
+    SeqState& q = s->seq[b];
+    for (int pg : q.pages) s->free_pages.push_back(pg);
+    q = SeqState();
+  }
+  EE_TRY(check_capacity(s, want));
+  reset_accounting(s);
+  size_t off = 0;
+  for (int b = 0; b < s->B; ++b) {
+    EE_TRY(grow_pages(s, b, want[b]));
+    const int n = lens[b];
+    for (int r0 = 0, ci = 0; r0 < n; r0 += s->chunk, ++ci) {
+      const int si = ci & 1;      // alternate upload slots so the host runs one chunk ahead
+      CallPlan p;
+      p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
+      p.m[b] = std::min(s->chunk, n - r0); p.p0[b] = r0;
+      const int32_t* tk = tokens + off + r0;
+      EE_TRY(build_meta(s, si, p, [&](int, int r, int& tok, int&, int&) { tok = tk[r]; }));
+      EE_TRY(upload_meta(s, si));
+      CallMeta mt = meta_ptrs(s, s->slot[si].d);
+      KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
+      run_layers(s, 0, c.n_layers, p, mt, 0);
+      if (r0 + s->chunk >= n) {
+        exit_head(s, p.M);
+        HIP_TRY(hipMemcpyAsync(s->out_host + b, s->vtok + (p.M - 1), sizeof(int), hipMemcpyDeviceToHost, s->st));
+      }
+    }
+    off += n;
+  }
+  EE_TRY(finish(s));
+  off = 0;
+  for (int b = 0; b < s->B; ++b) {
+    SeqState& q = s->seq[b];
+    q.C.assign(tokens + off, tokens + off + lens[b]);
+    q.C.push_back(s->out_host[b]);
+    q.len[0] = q.len[1] = q.len[2] = lens[b];
+    q.started = true;
+    first_token[b] = s->out_host[b];
+    off += lens[b];
+  }
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI: drafting at exit L_d
+// ---------------------------------------------------------------------------------------------
+static int draft_precheck(ee_session* s, int k, int rows) {
+  if (k < 1 || rows > s->max_rows) { ee_set_error("draft length %d does not fit max_rows %d", k, s->max_rows); return EE_ERR_ARG; }
+  std::vector<int> want(s->B);
+  for (int b = 0; b < s->B; ++b) {
+    const SeqState& q = s->seq[b];
+    if (!q.started) { ee_set_error("sequence %d has no context (call ee_prefill)", b); return EE_ERR_STATE; }
+    if (q.n_hd) { ee_set_error("sequence %d already has an unverified draft block", b); return EE_ERR_STATE; }
+    int nT = (int)(q.C.size() + q.V.size());
+    if ((int)q.V.size() + rows + 1 > s->max_rows) { ee_set_error("tentative buffer of sequence %d would overflow max_rows", b); return EE_ERR_CAPACITY; }
+    want[b] = nT - 1 + rows + 1;   // one spare position for the pending token's later catch-up
+  }
+  return check_capacity(s, want);
+}
+
+extern "C" int ee_draft(ee_session* s, int k, int32_t* draft) {
+  if (!s || !draft) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  const ee_config& c = s->m->cfg;
+  const int rows = k + (c.bonus_inter ? 1 : 0);
+  EE_TRY(draft_precheck(s, k, rows));
+  reset_accounting(s);
+  CallPlan p;
+  p.m.assign(s->B, 1); p.p0.resize(s->B);
+  for (int b = 0; b < s->B; ++b) {
+    const SeqState& q = s->seq[b];
+    p.p0[b] = (int)(q.C.size() + q.V.size()) - 1;
+    EE_TRY(grow_pages(s, b, p.p0[b] + rows + 1));
+  }
+  EE_TRY(build_meta(s, 0, p, [&](int b, int, int& tok, int&, int& dst) {
+    const SeqState& q = s->seq[b];
+    tok = q.V.empty() ? q.C.back() : q.V.back();
+    dst = b * s->max_rows;
+  }));
+  EE_TRY(upload_meta(s, 0));
+  CallMeta mt = meta_ptrs(s, s->slot[0].d);
+  for (int j = 0; j < rows; ++j) {
+    KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, j == 0 ? mt.row_tok : s->tok_next, s->X, p.M, c.d_model));
+    run_layers(s, 0, c.exit_draft, p, mt, j);
+    KF(KF_COPY, k_copy_rows(s->st, s->Hd, mt.row_dst, j, s->X, nullptr, p.M, c.d_model));
+    if (j < k) {
+      exit_head(s, p.M);
+      KF(KF_MISC, k_take_token(s->st, s->vtok, mt.row_seq, p.M, s->tok_next, s->draft_dev, s->max_rows, j));
+    }
+  }
+  int* dh = s->out_host + 2 * s->B;
+  HIP_TRY(hipMemcpyAsync(dh, s->draft_dev, (size_t)s->B * s->max_rows * sizeof(int), hipMemcpyDeviceToHost, s->st));
+  EE_TRY(finish(s));
+  for (int b = 0; b < s->B; ++b) {
+    SeqState& q = s->seq[b];
+    q.S.assign(dh + b * s->max_rows, dh + b * s->max_rows + k);
+    q.n_hd = rows;
+    q.len[0] = p.p0[b] + rows;
+    for (int j = 0; j < k; ++j) draft[b * k + j] = q.S[j];
+  }
+  return EE_OK;
+}
+
+extern "C" int ee_draft_inject(ee_session* s, int k, const int32_t* draft) {
+  if (!s || !draft) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  const ee_config& c = s->m->cfg;
+  const int rows = k + (c.bonus_inter ? 1 : 0);
+  EE_TRY(draft_precheck(s, k, rows));
+  for (int i = 0; i < s->B * k; ++i)
+    if (draft[i] < 0 || draft[i] >= c.vocab) { ee_set_error("draft token out of range"); return EE_ERR_ARG; }
+  reset_accounting(s);
+  CallPlan p;
+  p.m.assign(s->B, rows); p.p0.resize(s->B);
+  for (int b = 0; b < s->B; ++b) {
+    const SeqState& q = s->seq[b];
+    p.p0[b] = (int)(q.C.size() + q.V.size()) - 1;
+    EE_TRY(grow_pages(s, b, p.p0[b] + rows + 1));
+  }
+  EE_TRY(build_meta(s, 0, p, [&](int b, int r, int& tok, int&, int& dst) {
+    const SeqState& q = s->seq[b];
+    tok = r == 0 ? (q.V.empty() ? q.C.back() : q.V.back()) : draft[b * k + r - 1];
+    dst = b * s->max_rows + r;
+  }));
+  EE_TRY(upload_meta(s, 0));
+  CallMeta mt = meta_ptrs(s, s->slot[0].d);
+  KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
+  run_layers(s, 0, c.exit_draft, p, mt, 0);
+  KF(KF_COPY, k_copy_rows(s->st, s->Hd, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));
+  HIP_TRY(hipGetLastError());
+  for (int b = 0; b < s->B; ++b) {
+    SeqState& q = s->seq[b];
+    q.S.assign(draft + b * k, draft + b * k + k);
+    q.n_hd = rows;
+    q.len[0] = p.p0[b] + rows;
+  }
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI: intermediate verification at exit L_i
+// ---------------------------------------------------------------------------------------------
+extern "C" int ee_verify_intermediate(ee_session* s, int32_t* n_accept, int32_t* next_token) {
+  if (!s || !n_accept || !next_token) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  const ee_config& c = s->m->cfg;
+  CallPlan p;
+  p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
+  int any = 0;
+  for (int b = 0; b < s->B; ++b) {
+    const SeqState& q = s->seq[b];
+    if (!q.n_hd) continue;
+    p.m[b] = q.n_hd; p.p0[b] = (int)(q.C.size() + q.V.size()) - 1;
+    any++;
+  }
+  if (!any) { ee_set_error("no draft block is pending"); return EE_ERR_STATE; }
+  reset_accounting(s);
+  EE_TRY(build_meta(s, 0, p, [&](int b, int r, int&, int& src, int& dst) {
+    src = b * s->max_rows + r;                               // H_d row
+    dst = b * s->max_rows + (int)s->seq[b].V.size() + r;     // H_i row
+  }));
+  int* h = s->slot[0].h;
+  for (int b = 0; b < s->B; ++b) {
+    const SeqState& q = s->seq[b];
+    if (!p.m[b]) continue;
+    h[s->o_n_cand + b] = (int)q.S.size();
+    for (size_t j = 0; j < q.S.size(); ++j) h[s->o_cand + (size_t)b * s->cand_stride + j] = q.S[j];
+  }
+  EE_TRY(upload_meta(s, 0));
+  CallMeta mt = meta_ptrs(s, s->slot[0].d);
+  KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, s->Hd, mt.row_src, p.M, c.d_model));       // a1: consume buffered H_d
+  run_layers(s, c.exit_draft, c.exit_inter, p, mt, 0);
+  exit_head(s, p.M);
+  KF(KF_COPY, k_copy_rows(s->st, s->Hi, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));       // keep L_i hidden rows
+  KF(KF_ACCEPT, k_accept(s->st, s->vtok, mt, s->cand_stride, s->B, s->out_dev, s->out_dev + s->B));
+  HIP_TRY(hipMemcpyAsync(s->out_host, s->out_dev, 2 * (size_t)s->B * sizeof(int), hipMemcpyDeviceToHost, s->st));
+  EE_TRY(finish(s));
+  for (int b = 0; b < s->B; ++b) {
+    SeqState& q = s->seq[b];
+    n_accept[b] = s->out_host[b]; next_token[b] = s->out_host[s->B + b];
+    if (!p.m[b]) continue;
+    const int a = n_accept[b];
+    q.V.insert(q.V.end(), q.S.begin(), q.S.begin() + a);
+    int keep = a;
+    if (a < p.m[b]) { q.V.push_back(next_token[b]); keep = a + 1; }
+    q.len[0] = q.len[1] = p.p0[b] + keep;                    // prune rejected rows (lengths only)
+    q.n_hd = 0; q.S.clear();
+    trim_pages(s, b);
+  }
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI: full verification at L_f
+// ---------------------------------------------------------------------------------------------
+extern "C" int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
+                              int32_t* committed, int32_t* n_committed) {
+  if (!s || !n_accept || !next_token || !committed || !n_committed) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  const ee_config& c = s->m->cfg;
+  const int bonus = c.bonus_full ? 1 : 0;
+  std::vector<int> act(s->B, 0);
+  int any = 0;
+  for (int b = 0; b < s->B; ++b) {
+    const SeqState& q = s->seq[b];
+    if (active && !active[b]) continue;
+    if (q.V.empty()) continue;
+    if (q.n_hd) { ee_set_error("sequence %d still has an unverified draft block", b); return EE_ERR_STATE; }
+    act[b] = 1; any++;
+  }
+  if (!any) { ee_set_error("no sequence has tentative tokens to verify"); return EE_ERR_STATE; }
+  reset_accounting(s);
+  if (bonus) {
+    // the pending token V[-1] owns no hidden state yet: one row per sequence through G1 and G2
+    CallPlan p;
+    p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
+    for (int b = 0; b < s->B; ++b) {
+      if (!act[b]) continue;
+      const SeqState& q = s->seq[b];
+      p.m[b] = 1; p.p0[b] = (int)(q.C.size() + q.V.size()) - 1;
+      EE_TRY(grow_pages(s, b, p.p0[b] + 1));
+    }
+    EE_TRY(build_meta(s, 1, p, [&](int b, int, int& tok, int&, int& dst) {
+      tok = s->seq[b].V.back();
+      dst = b * s->max_rows + (int)s->seq[b].V.size();
+    }));
+    EE_TRY(upload_meta(s, 1));
+    CallMeta mt = meta_ptrs(s, s->slot[1].d);
+    KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
+    run_layers(s, 0, c.exit_inter, p, mt, 0);
+    KF(KF_COPY, k_copy_rows(s->st, s->Hi, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));
+  }
+  CallPlan p;
+  p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
+  for (int b = 0; b < s->B; ++b) {
+    if (!act[b]) continue;
+    const SeqState& q = s->seq[b];
+    p.m[b] = (int)q.V.size() + bonus; p.p0[b] = (int)q.C.size() - 1;
+  }
+  EE_TRY(build_meta(s, 0, p, [&](int b, int r, int&, int& src, int&) { src = b * s->max_rows + r; }));
+  int* h = s->slot[0].h;
+  for (int b = 0; b < s->B; ++b) {
+    if (!act[b]) continue;
+    const SeqState& q = s->seq[b];
+    h[s->o_n_cand + b] = (int)q.V.size();
+    for (size_t j = 0; j < q.V.size(); ++j) h[s->o_cand + (size_t)b * s->cand_stride + j] = q.V[j];
+  }
+  EE_TRY(upload_meta(s, 0));
+  CallMeta mt = meta_ptrs(s, s->slot[0].d);
+  KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, s->Hi, mt.row_src, p.M, c.d_model));       // consume buffered H_i
+  run_layers(s, c.exit_inter, c.n_layers, p, mt, 0);
+  exit_head(s, p.M);
+  KF(KF_ACCEPT, k_accept(s->st, s->vtok, mt, s->cand_stride, s->B, s->out_dev, s->out_dev + s->B));
+  HIP_TRY(hipMemcpyAsync(s->out_host, s->out_dev, 2 * (size_t)s->B * sizeof(int), hipMemcpyDeviceToHost, s->st));
+  EE_TRY(finish(s));
+  for (int b = 0; b < s->B; ++b) {
+    SeqState& q = s->seq[b];
+    n_accept[b] = s->out_host[b]; next_token[b] = s->out_host[s->B + b];
+    n_committed[b] = 0;
+    if (!act[b]) continue;
+    const int f = n_accept[b];
+    int32_t* out = committed + (size_t)b * (s->max_rows + 1);
+    int n = 0;
+    for (int j = 0; j < f; ++j) out[n++] = q.V[j];
+    if (f < p.m[b]) out[n++] = next_token[b];
+    n_committed[b] = n;
+    q.C.insert(q.C.end(), out, out + n);
+    q.V.clear();
+    q.len[0] = q.len[1] = q.len[2] = (int)q.C.size() - 1;
+    trim_pages(s, b);
+  }
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI: rollback
+// ---------------------------------------------------------------------------------------------
+extern "C" int kv_rollback(ee_session* s, int seq, int group_mask, int new_len) {
+  if (!s || seq < 0 || seq >= s->B) { ee_set_error("bad sequence index"); return EE_ERR_ARG; }
+  SeqState& q = s->seq[seq];
+  if (!q.started) { ee_set_error("sequence %d has no context", seq); return EE_ERR_STATE; }
+  const int m12 = group_mask & 3;
+  if (m12 != 0 && m12 != 3) { ee_set_error("G1 and G2 roll back together"); return EE_ERR_ARG; }
+  if (group_mask & ~7) { ee_set_error("bad group mask"); return EE_ERR_ARG; }
+  if (m12 == 0) {
+    if ((group_mask & 4) && new_len != q.len[2]) { ee_set_error("G3 cannot roll back alone"); return EE_ERR_ARG; }
+    q.n_hd = 0; q.S.clear(); q.len[0] = q.len[1];
+    trim_pages(s, seq);
+    return EE_OK;
+  }
+  if (new_len < 0 || new_len > q.len[1]) { ee_set_error("rollback can only shrink (len %d -> %d)", q.len[1], new_len); return EE_ERR_ARG; }
+  const int nT = new_len + 1;
+  if (nT <= (int)q.C.size()) {
+    if (new_len < q.len[2] && !(group_mask & 4)) { ee_set_error("cut reaches committed tokens: G3 must roll back too"); return EE_ERR_ARG; }
+    q.C.resize(nT); q.V.clear();
+    q.len[2] = new_len;
+  } else {
+    q.V.resize(nT - q.C.size());
+  }
+  q.n_hd = 0; q.S.clear();
+  q.len[0] = q.len[1] = new_len;
+  trim_pages(s, seq);
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI: introspection
+// ---------------------------------------------------------------------------------------------
+extern "C" int ee_get_lengths(const ee_session* s, int32_t* out) {
+  if (!s || !out) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  for (int b = 0; b < s->B; ++b) for (int g = 0; g < 3; ++g) out[b * 3 + g] = s->seq[b].len[g];
+  return EE_OK;
+}
+extern "C" int ee_get_counts(const ee_session* s, int32_t* nc, int32_t* nv) {
+  if (!s || !nc || !nv) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  for (int b = 0; b < s->B; ++b) { nc[b] = (int)s->seq[b].C.size(); nv[b] = (int)s->seq[b].V.size(); }
+  return EE_OK;
+}
+extern "C" int ee_get_tokens(const ee_session* s, int seq, int32_t* out, int cap, int32_t* n_out) {
+  if (!s || !out || !n_out || seq < 0 || seq >= s->B) { ee_set_error("bad argument"); return EE_ERR_ARG; }
+  const SeqState& q = s->seq[seq];
+  int n = (int)(q.C.size() + q.V.size());
+  if (n > cap) { ee_set_error("buffer too small: %d tokens", n); return EE_ERR_CAPACITY; }
+  std::copy(q.C.begin(), q.C.end(), out);
+  std::copy(q.V.begin(), q.V.end(), out + q.C.size());
+  *n_out = n;
+  return EE_OK;
+}
+extern "C" int ee_debug_enable_logits(ee_session* s, int on) {
+  if (!s) { ee_set_error("null session"); return EE_ERR_ARG; }
+  s->debug_logits = on != 0;
+  return EE_OK;
+}
+extern "C" int ee_debug_last_logits(ee_session* s, float* host_out, int max_rows, int32_t* n_rows) {
+  if (!s || !host_out || !n_rows) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  if (s->m->bf16 && !s->debug_logits) { ee_set_error("logits were not kept: call ee_debug_enable_logits first"); return EE_ERR_STATE; }
+  int n = std::min(max_rows, s->last_rows);
+  HIP_TRY(hipMemcpy(host_out, s->LOGITS, (size_t)n * s->m->cfg.vocab * sizeof(float), hipMemcpyDeviceToHost));
+  *n_rows = n;
+  return EE_OK;
+}
+extern "C" int ee_debug_last_hidden(ee_session* s, float* host_out, int max_rows, int32_t* n_rows) {
+  if (!s || !host_out || !n_rows) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  int n = std::min(max_rows, s->last_rows);
+  HIP_TRY(hipMemcpy(host_out, s->X, (size_t)n * s->m->cfg.d_model * sizeof(float), hipMemcpyDeviceToHost));
+  *n_rows = n;
+  return EE_OK;
+}
+static int upload_pages(ee_session* s, int seq) {
+  const SeqState& q = s->seq[seq];
+  if (q.pages.empty()) return EE_OK;
+  HIP_TRY(hipMemcpy(s->page_scratch, q.pages.data(), q.pages.size() * sizeof(int), hipMemcpyHostToDevice));
+  return EE_OK;
+}
+extern "C" int ee_debug_read_kv(ee_session* s, int seq, int layer, int pos0, int n, float* k_out, float* v_out) {
+  if (!s || !k_out || !v_out || seq < 0 || seq >= s->B) { ee_set_error("bad argument"); return EE_ERR_ARG; }
+  const ee_config& c = s->m->cfg;
+  const SeqState& q = s->seq[seq];
+  if (layer < 0 || layer >= c.n_layers || pos0 < 0 || n < 0 || pos0 + n > (int)q.pages.size() * EE_PAGE) { ee_set_error("KV range not owned by the sequence"); return EE_ERR_ARG; }
+  if (!n) return EE_OK;
+  size_t cnt = (size_t)n * c.n_kv_heads * c.head_dim;
+  float* stage = nullptr;
+  HIP_TRY(hipMalloc(&stage, 2 * cnt * sizeof(float)));
+  int rc = upload_pages(s, seq);
+  if (rc == EE_OK) {
+    k_read_kv(s->st, s->m->bf16, s->kv, s->page_scratch, layer, pos0, n, s->n_pages, c.n_kv_heads, c.head_dim, stage, stage + cnt);
+    hipError_t e = hipStreamSynchronize(s->st);
+    if (e == hipSuccess) e = hipMemcpy(k_out, stage, cnt * sizeof(float), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(v_out, stage + cnt, cnt * sizeof(float), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) { ee_set_error("read_kv: %s", hipGetErrorString(e)); rc = EE_ERR_HIP; }
+  }
+  (void)hipFree(stage);
+  return rc;
+}
+extern "C" int ee_debug_poison_dead_kv(ee_session* s, int seq) {
+  if (!s || seq < 0 || seq >= s->B) { ee_set_error("bad argument"); return EE_ERR_ARG; }
+  const ee_config& c = s->m->cfg;
+  const SeqState& q = s->seq[seq];
+  EE_TRY(upload_pages(s, seq));
+  const int bounds[4] = {0, c.exit_draft, c.exit_inter, c.n_layers};
+  for (int g = 0; g < 3; ++g)
+    k_fill_nan_dead_kv(s->st, s->m->bf16, s->kv, s->page_scratch, (int)q.pages.size(), q.len[g], bounds[g], bounds[g + 1],
+                       s->n_pages, c.n_kv_heads, c.head_dim);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(s->st));
+  return EE_OK;
+}
+extern "C" int ee_debug_time_kernels(ee_session* s, int on) {
+  if (!s) { ee_set_error("null session"); return EE_ERR_ARG; }
+  s->time_kernels = on != 0;
+  return EE_OK;
+}
+extern "C" int ee_debug_kernel_times(ee_session* s, int32_t* n_families, const char** names, float* ms, int32_t* launches) {
+  if (!s || !n_families || !names || !ms || !launches) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  HIP_TRY(hipStreamSynchronize(s->st));
+  for (int f = 0; f < KF_COUNT; ++f) { names[f] = kFamName[f]; ms[f] = 0.f; launches[f] = s->launches[f]; }
+  for (auto& t : s->timers) {
+    float x = 0.f;
+    if (hipEventElapsedTime(&x, t.a, t.b) == hipSuccess) ms[t.fam] += x;
+  }
+  *n_families = KF_COUNT;
+  return EE_OK;
+}

@@ -1,0 +1,406 @@
+"""GPU parity: the HIP path behind the C ABI against the CPU oracle, on the same seeded inputs.
+
+Accept lengths and token ids must be bit-exact on inputs whose compared rows clear a
+top-1/top-2 logit margin of 1e-2 in the oracle; logits and hidden states must agree within
+max|gpu-ref|/max|ref| <= 1e-4 (fp32 models) or 2e-2 (bf16 models).
+"""
+import copy
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import ee_oracle as eo
+from hs_common import MARGIN, TOL, OracleSide, bf16_d128, bf16_small, gpu_side, max_rel
+
+pytestmark = pytest.mark.gpu
+
+
+# ------------------------------------------------------------------------------------------------
+# inputs: device generator == host generator, bit for bit
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg", [synth.tiny_config(), bf16_small(), bf16_d128(gamma=(1.0, 0.5, 0.25))],
+                         ids=["tiny_f32", "bf16_small", "bf16_d128"])
+def test_device_weights_equal_host_generator(cfg):
+    import paper_2510_01336_amd as hs
+    model = hs.Model(cfg, 4242)
+    for name in synth.model.GLOBAL_TENSORS + synth.model.LAYER_TENSORS:
+        shape = synth.tensor_shape(cfg, name)
+        for layer in ([0] if name in synth.model.GLOBAL_TENSORS else [0, cfg.n_layers - 1]):
+            want = synth.gen_tensor(cfg, 4242, name, layer)
+            rows, cols = shape[0], (shape[1] if len(shape) == 2 else 1)
+            got = model.tensor_rows(name, layer, 0, rows, cols).reshape(want.shape)
+            nbad = int(np.count_nonzero(got.view(np.uint32) != want.view(np.uint32)))
+            assert nbad == 0, (name, layer, nbad)
+    model.close()
+
+
+def test_set_tensor_roundtrip():
+    import paper_2510_01336_amd as hs
+    cfg = bf16_small()
+    model = hs.Model(cfg, 1)
+    rng = np.random.default_rng(0)
+    for name in ("wup", "wk", "g2", "emb"):
+        shape = synth.tensor_shape(cfg, name)
+        vals = rng.normal(size=shape).astype(np.float32)
+        model.set_tensor(name, 1, vals)
+        want = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(vals))
+        got = model.tensor_rows(name, 1, 0, shape[0], shape[1] if len(shape) == 2 else 1).reshape(shape)
+        assert np.array_equal(got, want), name
+    # neighbours in the fused / interleaved matrices are untouched
+    assert np.array_equal(model.tensor_rows("wgate", 1, 0, 688, 256), synth.gen_tensor(cfg, 1, "wgate", 1))
+    assert np.array_equal(model.tensor_rows("wq", 1, 0, 512, 256), synth.gen_tensor(cfg, 1, "wq", 1))
+    model.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# helpers: one HiSpec round on both sides with margin-filtered inputs
+# ------------------------------------------------------------------------------------------------
+def _trial_round(O, seqs, drafts, do_full):
+    """Run the round on deep copies of the oracle sequences; return the smallest margin among the
+    rows whose arg max decides an output (rows 0..a of each verify)."""
+    worst = np.inf
+    for s0, S in zip(seqs, drafts):
+        s = copy.deepcopy(s0)
+        O.o.draft_inject(s, S)
+        a, _ = O.o.verify_intermediate(s)
+        m = eo.top2_margin(O.o.last_logits)
+        worst = min(worst, m[:min(a + 1, len(m))].min())
+        if do_full:
+            f, _, _ = O.o.verify_full(s)
+            m = eo.top2_margin(O.o.last_logits)
+            worst = min(worst, m[:min(f + 1, len(m))].min())
+    return worst
+
+
+def _nudge(O, sess, b):
+    """Drop the last token of sequence b on both sides (it becomes pending again one position
+    earlier): a different row 0, hence a fresh draw of its margin."""
+    s = O.seqs[b]
+    sess.rollback(b, 0b111, s.len[0] - 1)
+    O.o.rollback(s, 0b111, s.len[0] - 1)
+
+
+def _pick_drafts(O, sess, k, p, rng, do_full, first_mismatch=None, tries=25):
+    """Teacher-forced draft blocks (agreement p with the L_i verifier) whose every decisive row
+    clears the margin in the oracle.  The drawn first-mismatch index is lowered until the rows up
+    to it are clear; if even row 0 is not, the context is nudged and the draw repeated."""
+    for _ in range(tries):
+        drafts = []
+        for b, s in enumerate(O.seqs):
+            greedy = O.greedy(s, k, O.cfg.exit_inter)
+            a0 = synth.draw_first_mismatch(k, p, rng) if first_mismatch is None else first_mismatch
+            lowest = -1 if first_mismatch is None else first_mismatch - 1
+            found = None
+            for a_star in range(a0, lowest, -1):
+                S = synth.make_draft_block(greedy, k, p, O.cfg.vocab, rng, first_mismatch=a_star)
+                if _trial_round(O, [s], [S], do_full) > MARGIN:
+                    found = S
+                    break
+            if found is None:
+                _nudge(O, sess, b)
+                break
+            drafts.append(found)
+        else:
+            return np.stack(drafts)
+    pytest.fail("no draft block cleared the margin filter")
+
+
+def _round(O, sess, k, p, rng, do_full, tol):
+    B = len(O.seqs)
+    drafts = _pick_drafts(O, sess, k, p, rng, do_full)
+    sess.draft_inject(drafts)
+    ga, gn = sess.verify_intermediate()
+    glog, ghid = sess.last_logits(), sess.last_hidden()
+    r0 = 0
+    for b, s in enumerate(O.seqs):
+        O.o.draft_inject(s, drafts[b])
+        a, nxt = O.o.verify_intermediate(s)
+        n = len(O.o.last_logits)
+        assert (int(ga[b]), int(gn[b])) == (a, nxt), f"seq {b}: gpu ({ga[b]},{gn[b]}) oracle ({a},{nxt})"
+        assert max_rel(glog[r0:r0 + n], O.o.last_logits) <= tol
+        assert max_rel(ghid[r0:r0 + n], O.o.last_hidden) <= tol
+        r0 += n
+    _check_state(O, sess)
+    if not do_full:
+        return
+    gf, gn, gcom = sess.verify_full()
+    glog, ghid = sess.last_logits(), sess.last_hidden()
+    r0 = 0
+    for b, s in enumerate(O.seqs):
+        f, nxt, F = O.o.verify_full(s)
+        n = len(O.o.last_logits)
+        assert (int(gf[b]), int(gn[b]), gcom[b]) == (f, nxt, F)
+        assert max_rel(glog[r0:r0 + n], O.o.last_logits) <= tol
+        assert max_rel(ghid[r0:r0 + n], O.o.last_hidden) <= tol
+        r0 += n
+    _check_state(O, sess)
+
+
+def _check_state(O, sess):
+    lens = sess.lengths()
+    nc, nv = sess.counts()
+    for b, s in enumerate(O.seqs):
+        assert list(lens[b]) == s.len
+        assert (nc[b], nv[b]) == (len(s.C), len(s.V))
+        assert sess.tokens(b).tolist() == s.T
+
+
+def _setup(cfg, seed, ctx_lens, max_rows, bonus=(True, True), prompt_seed=100):
+    B = len(ctx_lens)
+    max_ctx = int(max(ctx_lens)) + 8 * max_rows
+    O = OracleSide(cfg, seed, *bonus)
+    model, sess = gpu_side(cfg, seed, B, max_ctx, max_rows, *bonus)
+    sess.enable_logits(True)
+    for attempt in range(20):
+        prompts = [synth.gen_prompt(cfg.vocab, int(n), prompt_seed + 1000 * attempt + b) for b, n in enumerate(ctx_lens)]
+        first, margins = O.prefill(prompts, max_ctx)
+        if min(margins) > MARGIN:      # the committed first token must be decided clearly
+            break
+    else:
+        pytest.fail("no prompt cleared the margin filter")
+    gfirst = sess.prefill(prompts)
+    return O, model, sess, first, gfirst
+
+
+# ------------------------------------------------------------------------------------------------
+# verify-step parity
+# ------------------------------------------------------------------------------------------------
+CASES = [
+    # cfg, ctx lengths (ragged; > 64 spans KV pages), k, bonus modes
+    ("tiny_f32", synth.tiny_config(gamma=(1.0, 0.3, 0.3)), [32], 4, (True, True)),
+    ("tiny_f32_batch", synth.tiny_config(gamma=(1.0, 0.3, 0.3)), [40, 7, 129], 4, (True, False)),
+    ("bf16_small", bf16_small(), [150], 8, (True, True)),
+    ("bf16_small_batch", bf16_small(), [70, 5, 200, 64], 8, (True, True)),
+    ("bf16_small_nobonus", bf16_small(), [33, 130], 5, (False, False)),
+    ("bf16_d128", bf16_d128(), [100, 260], 8, (True, True)),
+    ("bf16_d128_k16", bf16_d128(), [300], 16, (True, True)),
+]
+
+
+@pytest.mark.parametrize("name,cfg,ctx,k,bonus", CASES, ids=[c[0] for c in CASES])
+def test_verify_rounds_match_oracle(name, cfg, ctx, k, bonus):
+    tol = TOL[cfg.dtype]
+    max_rows = 3 * (k + 1) + 2
+    O, model, sess, first, gfirst = _setup(cfg, 777, ctx, max_rows, bonus)
+    assert gfirst.tolist() == first.tolist()
+    # the last prefill pass covered the last sequence: its final row is the oracle's last hidden row
+    assert max_rel(sess.last_hidden()[-1:], O.o.last_hidden) <= tol
+    assert max_rel(sess.last_logits()[-1:], O.o.last_logits) <= tol
+    rng = np.random.default_rng(5)
+    # round 1: intermediate only; round 2: intermediate then full; round 3: both again
+    _round(O, sess, k, 0.8, rng, False, tol)
+    _round(O, sess, k, 0.8, rng, True, tol)
+    _round(O, sess, k, 0.6, rng, True, tol)
+    sess.close(); model.close()
+
+
+def test_all_correct_and_wrong_first_blocks():
+    cfg = bf16_small()
+    k = 8
+    O, model, sess, first, gfirst = _setup(cfg, 31, [90], 3 * (k + 1) + 2)
+    rng = np.random.default_rng(9)
+    s = O.seqs[0]
+    for first_mismatch, want_a in ((k, k), (0, 0), (3, 3)):
+        S = _pick_drafts(O, sess, k, 0.5, rng, False, first_mismatch=first_mismatch)[0]
+        greedy = O.greedy(s, k + 1, cfg.exit_inter)
+        sess.draft_inject(S[None])
+        ga, gn = sess.verify_intermediate()
+        O.o.draft_inject(s, S)
+        a, nxt = O.o.verify_intermediate(s)
+        assert (int(ga[0]), int(gn[0])) == (a, nxt) == (want_a, greedy[want_a])
+    _check_state(O, sess)
+    sess.close(); model.close()
+
+
+def test_self_drafting_matches_oracle():
+    """ee_draft (k sequential shallow passes on the device) against the oracle's Generate(L_d, ., k)."""
+    for cfg in (synth.tiny_config(gamma=(1.0, 0.3, 0.3)), bf16_small()):
+        k = 4
+        O, model, sess, first, gfirst = _setup(cfg, 99, [50, 20], 3 * (k + 1) + 2)
+        assert gfirst.tolist() == first.tolist()
+        compared = 0
+        for rnd in range(6):
+            trial = [copy.deepcopy(s) for s in O.seqs]
+            clear = True
+            for t in trial:
+                O.o.draft(t, k)
+                clear &= eo.top2_margin(O.o.last_logits).min() > MARGIN
+                a, _ = O.o.verify_intermediate(t)
+                m = eo.top2_margin(O.o.last_logits)
+                clear &= m[:min(a + 1, len(m))].min() > MARGIN
+            if clear:
+                gS = sess.draft(k)
+                for b, s in enumerate(O.seqs):
+                    assert gS[b].tolist() == O.o.draft(s, k)
+                compared += 1
+            else:   # keep both sides moving with a teacher-forced block instead
+                drafts = _pick_drafts(O, sess, k, 0.7, np.random.default_rng(rnd), False)
+                sess.draft_inject(drafts)
+                for b, s in enumerate(O.seqs):
+                    O.o.draft_inject(s, drafts[b])
+            ga, gn = sess.verify_intermediate()
+            for b, s in enumerate(O.seqs):
+                assert (int(ga[b]), int(gn[b])) == O.o.verify_intermediate(s)
+            if rnd % 2 == 1:
+                full_clear = True
+                trial = [copy.deepcopy(s) for s in O.seqs]
+                for t in trial:
+                    f, _, _ = O.o.verify_full(t)
+                    m = eo.top2_margin(O.o.last_logits)
+                    full_clear &= m[:min(f + 1, len(m))].min() > MARGIN
+                if not full_clear:
+                    break
+                gf, gn, gcom = sess.verify_full()
+                for b, s in enumerate(O.seqs):
+                    f, nxt, F = O.o.verify_full(s)
+                    assert (int(gf[b]), int(gn[b]), gcom[b]) == (f, nxt, F)
+            _check_state(O, sess)
+        assert compared >= 1
+        sess.close(); model.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# cache alignment, rollback, batching
+# ------------------------------------------------------------------------------------------------
+def test_kv_cache_matches_oracle_and_dead_entries_never_leak():
+    cfg = bf16_small()
+    k = 8
+    O, model, sess, _, _ = _setup(cfg, 55, [100, 30], 3 * (k + 1) + 2)
+    rng = np.random.default_rng(2)
+    tol = TOL["bf16"]
+    for rnd in range(4):
+        for b in range(2):
+            sess.poison_dead_kv(b)          # NaN in every pruned / never-written slot
+        _round(O, sess, k, 0.7, rng, rnd % 2 == 1, tol)
+        assert np.isfinite(sess.last_logits()).all()
+    for b, s in enumerate(O.seqs):
+        for g in range(3):
+            for l in cfg.group_layers(g):
+                n = s.len[g]
+                gk, gv = sess.read_kv(b, l, 0, n)
+                assert max_rel(gk, s.cache.K[l, :n]) <= tol and max_rel(gv, s.cache.V[l, :n]) <= tol
+    sess.close(); model.close()
+
+
+def test_explicit_rollback_restores_prefix_and_continues():
+    cfg = bf16_small()
+    k = 6
+    O, model, sess, _, _ = _setup(cfg, 56, [80], 3 * (k + 1) + 2)
+    rng = np.random.default_rng(3)
+    tol = TOL["bf16"]
+    s = O.seqs[0]
+    before = sess.read_kv(0, 0, 0, 80)
+    _round(O, sess, k, 0.9, rng, True, tol)
+    _round(O, sess, k, 0.9, rng, True, tol)
+    assert len(s.C) > 82
+    sess.rollback(0, 0b111, 81)
+    O.o.rollback(s, 0b111, 81)
+    _check_state(O, sess)
+    after = sess.read_kv(0, 0, 0, 80)
+    assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])   # no KV bytes moved
+    sess.poison_dead_kv(0)
+    _round(O, sess, k, 0.8, rng, True, tol)
+    # tentative-only cut
+    _round(O, sess, k, 1.0, rng, False, tol)
+    cut = s.len[0] - 2
+    sess.rollback(0, 0b011, cut)
+    O.o.rollback(s, 0b011, cut)
+    _check_state(O, sess)
+    _round(O, sess, k, 0.8, rng, True, tol)
+    sess.close(); model.close()
+
+
+def test_batched_equals_solo():
+    """Per-sequence acceptance: each sequence of a ragged batch behaves exactly as when run alone."""
+    cfg = bf16_small()
+    k = 8
+    ctx = [70, 5, 200]
+    O, model, sess, _, _ = _setup(cfg, 57, ctx, 3 * (k + 1) + 2)
+    prompts = [np.array(s.C[:-1], np.int32) for s in O.seqs]
+    rng = np.random.default_rng(4)
+    drafts = _pick_drafts(O, sess, k, 0.7, rng, True)
+    prompts = [np.array(s.C[:-1], np.int32) for s in O.seqs]     # (a nudge may have shortened a context)
+    sess.draft_inject(drafts)
+    ga, gn = sess.verify_intermediate()
+    blog = sess.last_logits().copy()
+    gf, gfn, gcom = sess.verify_full()
+    r0 = 0
+    import paper_2510_01336_amd as hs
+    for b in range(3):
+        solo = hs.Session(model, 1, sess.max_ctx, sess.max_rows)
+        solo.enable_logits(True)
+        solo.prefill([prompts[b]])
+        solo.draft_inject(drafts[b:b + 1])
+        a, n = solo.verify_intermediate()
+        assert (a[0], n[0]) == (ga[b], gn[b])
+        sl = solo.last_logits()
+        assert np.array_equal(sl, blog[r0:r0 + len(sl)])     # same kernels, same order: bit-identical
+        r0 += len(sl)
+        f, fn, com = solo.verify_full()
+        assert (f[0], fn[0], com[0]) == (gf[b], gfn[b], gcom[b])
+        solo.close()
+    sess.close(); model.close()
+
+
+def test_rerun_is_bit_identical():
+    cfg = bf16_d128()
+    k = 8
+    O, model, sess, _, _ = _setup(cfg, 58, [200], 3 * (k + 1) + 2)
+    drafts = _pick_drafts(O, sess, k, 0.8, np.random.default_rng(6), False)
+    n0 = O.seqs[0].len[0]
+    outs = []
+    for _ in range(3):
+        sess.draft_inject(drafts)
+        a, n = sess.verify_intermediate()
+        outs.append((a.copy(), n.copy(), sess.last_logits().copy()))
+        sess.rollback(0, 0b011, n0)
+    for o in outs[1:]:
+        assert np.array_equal(o[0], outs[0][0]) and np.array_equal(o[1], outs[0][1]) and np.array_equal(o[2], outs[0][2])
+    sess.close(); model.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# error behaviour
+# ------------------------------------------------------------------------------------------------
+def test_error_codes_leave_state_untouched():
+    import paper_2510_01336_amd as hs
+    cfg = synth.tiny_config()
+    model, sess = gpu_side(cfg, 1, 1, 128, 12)
+    with pytest.raises(hs.EEError) as e:
+        sess.draft(2)
+    assert e.value.code == -2                       # no context yet
+    sess.prefill([synth.gen_prompt(cfg.vocab, 20, 1)])
+    with pytest.raises(hs.EEError) as e:
+        sess.verify_intermediate()
+    assert e.value.code == -2                       # nothing drafted
+    with pytest.raises(hs.EEError) as e:
+        sess.verify_full()
+    assert e.value.code == -2                       # nothing tentative
+    with pytest.raises(hs.EEError) as e:
+        sess.draft(40)
+    assert e.value.code == -1                       # more rows than max_rows
+    with pytest.raises(hs.EEError) as e:
+        sess.rollback(0, 0b111, 25)
+    assert e.value.code == -1                       # growing is not a rollback
+    with pytest.raises(hs.EEError) as e:
+        sess.rollback(0, 0b001, 5)
+    assert e.value.code == -1
+    with pytest.raises(hs.EEError) as e:
+        sess.draft_inject(np.array([[cfg.vocab]]))
+    assert e.value.code == -1
+    assert sess.lengths().tolist() == [[20, 20, 20]]
+    sess.draft(3)
+    with pytest.raises(hs.EEError) as e:
+        sess.draft(3)
+    assert e.value.code == -2                       # a block is already pending
+    sess.verify_intermediate()
+    # capacity: a context that cannot grow any further
+    small = hs.Session(model, 1, 24, 12)
+    small.prefill([synth.gen_prompt(cfg.vocab, 20, 1)])
+    with pytest.raises(hs.EEError) as e:
+        small.draft(4)
+    assert e.value.code == -3
+    with pytest.raises(hs.EEError) as e:
+        hs.Session(model, 1, 100000, 12)            # fp32 sessions are limited to 8192 positions
+    small.close(); sess.close(); model.close()
