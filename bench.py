@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the k-token verify path on one MI355X.
+
+One "step" is one HiSpec round on a batch resident in HBM:
+    ee_draft_inject (draft block through G1) -> ee_verify_intermediate (G2 + exit head + accept +
+    prune) -> ee_verify_full (catch-up row, G3 + exit head + accept + commit + prune) ->
+    kv_rollback (back to the starting context, so every step sees the same KV length).
+Metric: verified draft tokens per second = batch * k * steps / elapsed.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel (the gate/up weight-streaming
+GEMM): algorithmic bytes per launch / its mean launch duration, measured with HIP events on the
+library's stream in a second, instrumented pass over the same steps.  `cpu_baseline` is the
+numpy oracle timed on this machine's host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+MODEL_SEED = 20251001
+
+# HBM traffic of one gate/up GEMM launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE,
+# calibrated against a copy kernel); see profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+WORKLOADS = {
+    # name: (config factory, batch, ctx, k, agreement p)
+    "8b_b1_ctx2048_k8": (synth.llama8b_config, 1, 2048, 8, 0.8),
+    "tiny_b1_ctx32_k4": (lambda: synth.tiny_config(gamma=(1.0, 0.3, 0.3)), 1, 32, 4, 0.8),
+    "8b_reduced_b1_ctx2048_k8": (lambda: synth.llama8b_config(n_layers=8, exit_draft=1, exit_inter=4), 1, 2048, 8, 0.8),
+}
+
+
+def step_bytes(cfg, batch, ctx, k, rows_full):
+    """Algorithmic HBM bytes of one step: every weight of the layers run once, the two exit heads,
+    and the KV context once per layer pass (activations are negligible and left out)."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    d, D, Hq, Hkv, F = cfg.d_model, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads, cfg.d_ffn
+    per_layer = ((Hq + 2 * Hkv) * D * d + d * Hq * D + 3 * F * d) * es
+    head = cfg.vocab * d * es
+    kv_layer = batch * ctx * 2 * Hkv * D * es
+    layers = cfg.n_layers + (cfg.exit_inter if rows_full else 0)   # G1+G2+G3, + catch-up row through G1+G2
+    return layers * (per_layer + kv_layer) + 2 * head
+
+
+def build_workload(name, seed=MODEL_SEED):
+    import paper_2510_01336_amd as hs
+    factory, batch, ctx, k, p = WORKLOADS[name]
+    cfg = factory()
+    model = hs.Model(cfg, seed)
+    sess = hs.Session(model, batch, ctx + 64, 2 * (k + 1) + 2)
+    prompts = [synth.gen_prompt(cfg.vocab, ctx, 7 + b) for b in range(batch)]
+    sess.prefill(prompts)
+    # teacher-forced greedy continuation of the intermediate verifier, found with the library itself
+    # (k+1 untimed rounds), then a block agreeing with it with probability p per position
+    rng = np.random.default_rng(11)
+    greedy = np.zeros((batch, k), np.int64)
+    for j in range(k):
+        S = rng.integers(0, cfg.vocab, size=(batch, k))
+        S[:, :j] = greedy[:, :j]
+        sess.draft_inject(S)
+        a, nxt = sess.verify_intermediate()
+        greedy[:, j] = nxt
+        for b in range(batch):
+            sess.rollback(b, 0b111, ctx)
+    drafts = np.stack([synth.make_draft_block(greedy[b], k, p, cfg.vocab, rng) for b in range(batch)])
+    return dict(cfg=cfg, model=model, sess=sess, batch=batch, ctx=ctx, k=k, p=p, drafts=drafts, name=name)
+
+
+def one_step(w, collect=None):
+    sess = w["sess"]
+    sess.draft_inject(w["drafts"])
+    if collect is not None:
+        collect(sess.kernel_times(), "inject")
+    a, nxt = sess.verify_intermediate()
+    if collect is not None:
+        collect(sess.kernel_times(), "inter")
+    f, fn, com = sess.verify_full()
+    if collect is not None:
+        collect(sess.kernel_times(), "full")
+    for b in range(w["batch"]):
+        sess.rollback(b, 0b111, w["ctx"])
+    return a, f
+
+
+def cpu_baseline(w):
+    """The oracle as it stands, on a bounded sample: ONE layer of the verify pass (k+1 rows against
+    a random KV context of the workload's length) plus ONE exit head, scaled to the layer and head
+    count of a full step."""
+    from oracle import ee_oracle as eo
+    cfg, k, ctx, batch = w["cfg"], w["k"], w["ctx"], w["batch"]
+    spec = eo.ModelSpec.from_config(cfg)
+    l = cfg.exit_draft                         # first layer of G2
+    store = synth.WeightStore(cfg, MODEL_SEED, cache=True)
+    for name in ("g1", "wq", "wk", "wv", "wo", "g2", "wgate", "wup", "wdown"):
+        store.get(name, l)
+    store.get("gfinal"); store.get("head")
+    model = eo.EEModel(spec, store)
+    rng = np.random.default_rng(0)
+    rows = k + 1
+    cache = eo.KVCache(spec, ctx + rows)
+    cache.K[l, :ctx] = eo.round_bf16(rng.normal(size=(ctx, cfg.n_kv_heads, cfg.head_dim)))
+    cache.V[l, :ctx] = eo.round_bf16(rng.normal(size=(ctx, cfg.n_kv_heads, cfg.head_dim)))
+    x = rng.normal(size=(rows, cfg.d_model))
+    t0 = time.perf_counter()
+    for _ in range(batch):
+        y = model.layer(l, x, ctx + np.arange(rows), cache)
+    t_layer = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for _ in range(batch):
+        eo.argmax_rows(model.exit_logits(y))
+    t_head = time.perf_counter() - t0
+    layers = cfg.n_layers + cfg.exit_inter      # G1 + G2 + G3 + catch-up row through G1+G2
+    t_step = layers * t_layer + 2 * t_head
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": batch * k / t_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 of {layers} layer passes ({rows} rows, KV context {ctx}, random KV) timed at "
+                      f"{t_layer:.2f} s + 1 of 2 exit heads at {t_head:.2f} s, scaled to a full step "
+                      f"({t_step:.1f} s); float64 numpy"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="8b_b1_ctx2048_k8", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
+    torch.cuda.set_device(0)
+    w = build_workload(args.workload)
+    cfg, sess = w["cfg"], w["sess"]
+
+    for _ in range(args.warmup):
+        a, f = one_step(w)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        a, f = one_step(w)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = w["batch"] * w["k"] * args.steps / elapsed
+
+    # instrumented pass: HIP events around every launch on the library's stream
+    acc = {}
+    def collect(times, phase):
+        for fam, (ms, n) in times.items():
+            e = acc.setdefault(fam, [0.0, 0])
+            e[0] += ms; e[1] += n
+            p = acc.setdefault("phase:" + phase, [0.0, 0])
+            p[0] += ms; p[1] += n
+    sess.time_kernels(True)
+    for _ in range(args.steps):
+        one_step(w, collect)
+    sess.time_kernels(False)
+    fam = "gemm_gate_up"
+    gu_ms, gu_n = acc[fam]
+    es = 2
+    gu_bytes = 2 * cfg.d_ffn * cfg.d_model * es            # gate + up weights, streamed once per launch
+    rows = w["batch"] * (w["k"] + 1)
+    gu_bytes += rows * cfg.d_model * es + rows * cfg.d_ffn * es   # normed input rows in, SwiGLU rows out
+    gu_avg_s = gu_ms / gu_n * 1e-3
+    achieved = gu_bytes / gu_avg_s / 1e9
+    roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel<1,SWIGLU> (gate/up projection + SiLU*mul)",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": gu_bytes, "avg_launch_us": gu_avg_s * 1e6,
+                "launches": gu_n}
+    sb = step_bytes(cfg, w["batch"], w["ctx"], w["k"], True)
+    kernel_ms = {k2: round(v[0] / args.steps, 4) for k2, v in acc.items()}
+
+    out = {
+        "metric": "verified draft tokens/sec per GPU (k-token verify)", "value": value, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": w["batch"], "kv_context": w["ctx"], "k": w["k"],
+                   "draft_agreement_p": w["p"], "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers],
+                   "step": "draft_inject(G1) + verify_intermediate(G2) + verify_full(G1+G2 catch-up row, G3) + rollback",
+                   "accepted_inter": [int(x) for x in a], "accepted_full": [int(x) for x in f]},
+        "roofline": roofline,
+        "step_bytes": sb, "step_hbm_frac": sb / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernel_ms_per_step": kernel_ms,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

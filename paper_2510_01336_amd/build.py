@@ -21,7 +21,7 @@ def build(verbose: bool = True) -> str:
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
+        raise RuntimeError("hipcc failed:\n" + "\n".join(out.splitlines()[:60]))
     if verbose and out.strip():
         print(out)
     return LIB

@@ -39,6 +39,8 @@ struct GemmOut {
 };
 // Y^T tile = W tile (A operand) x X^T (B operand); W, A in fragment layout; M <= 64 rows per launch
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out);
+void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
+                   const GemmOut& out, int nw, int ksplit, int U);
 void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf16_t* out, int ktiles, int M, int d);
 void bf16_rope_append(hipStream_t st, const float* QKV, int ldq, const float2* cs, const CallMeta& meta, int pos_add, int M,
                       int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq, int total_qt,

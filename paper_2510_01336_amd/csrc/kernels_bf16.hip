@@ -11,6 +11,10 @@
 #include "kernels.h"
 #include <cmath>
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
 __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
@@ -19,60 +23,86 @@ __device__ inline uint32_t pack2(float lo, float hi) { return (uint32_t)f32_to_b
 // ---------------------------------------------------------------------------------------------
 // RMSNorm: fp32 row in, bf16 fragment-layout row out (the next GEMM's B operand)
 // ---------------------------------------------------------------------------------------------
-__global__ void bf16_rmsnorm_kernel(const float* X, const float* g, float eps, bf16_t* out, int ktiles, int d) {
+// One workgroup per row; the row is read once as float4 into registers (all loads issued before the
+// first use), reduced, scaled, and written as 8-byte bf16 quads (4 consecutive k share a fragment lane).
+template <int CH>   // float4 chunks per thread: d <= 4 * 256 * CH
+__global__ __launch_bounds__(256) void bf16_rmsnorm_kernel(const float* __restrict__ X, const float* __restrict__ g, float eps,
+                                                           bf16_t* __restrict__ out, int ktiles, int d) {
   __shared__ float part[4];
-  int r = blockIdx.x;
-  const float* x = X + (size_t)r * d;
+  const int r = blockIdx.x, nch = d >> 2;
+  const float4* x4 = (const float4*)(X + (size_t)r * d);
+  const float4* g4 = (const float4*)g;
+  float4 xv[CH], gv[CH];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = threadIdx.x + i * 256;
+    xv[i] = c < nch ? x4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+    gv[i] = c < nch ? g4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
   float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) ss += x[c] * x[c];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) ss += xv[i].x * xv[i].x + xv[i].y * xv[i].y + xv[i].z * xv[i].z + xv[i].w * xv[i].w;
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_down(ss, o, 64);
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
   __syncthreads();
-  float inv = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)d + eps);
-  for (int c = threadIdx.x; c < d; c += blockDim.x) out[frag_offset(r, c, ktiles)] = f32_to_bf16(x[c] * inv * g[c]);
+  const float inv = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = threadIdx.x + i * 256;
+    if (c < nch) {
+      uint2 pk = make_uint2(pack2(xv[i].x * inv * gv[i].x, xv[i].y * inv * gv[i].y),
+                            pack2(xv[i].z * inv * gv[i].z, xv[i].w * inv * gv[i].w));
+      *(uint2*)(out + frag_offset(r, c * 4, ktiles)) = pk;
+    }
+  }
 }
 void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf16_t* out, int ktiles, int M, int d) {
-  hipLaunchKernelGGL(bf16_rmsnorm_kernel, dim3(M), dim3(256), 0, st, X, g, eps, out, ktiles, d);
+  // d is a multiple of 16 for bf16 models (checked at model load), so float4 access is aligned
+  if (d <= 1024) hipLaunchKernelGGL((bf16_rmsnorm_kernel<1>), dim3(M), dim3(256), 0, st, X, g, eps, out, ktiles, d);
+  else if (d <= 4096) hipLaunchKernelGGL((bf16_rmsnorm_kernel<4>), dim3(M), dim3(256), 0, st, X, g, eps, out, ktiles, d);
+  else hipLaunchKernelGGL((bf16_rmsnorm_kernel<16>), dim3(M), dim3(256), 0, st, X, g, eps, out, ktiles, d);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Skinny GEMM  Y[m][n] = sum_k X[m][k] W[n][k],  M <= 16*MT rows, weights streamed once.
-// One workgroup owns one 16-row weight tile strip (two for SwiGLU: the gate tile and its up tile)
-// over the whole K; its waves split K into contiguous chunks, each wave streaming its chunk of
-// the strip (1 KiB per MFMA step) with a two-stage register pipeline, then the partial 16x16
-// tiles are summed through LDS in a fixed order (deterministic) and wave 0 runs the epilogue.
+// A task is one 16-row weight tile strip over the whole K (two strips for SwiGLU: the gate tile and
+// its up tile).  A workgroup of nw waves runs nw/ksplit tasks; the ksplit waves of a task split K
+// into contiguous chunks, each wave streaming its chunk (1 KiB per MFMA step) through a two-stage
+// register pipeline of depth U; the partial 16x16 tiles are then summed through LDS in a fixed
+// order (deterministic) and the task's first wave runs the epilogue.
 // The MFMA computes Y^T = W X^T so that a lane ends up with 4 consecutive n of one row m.
 // ---------------------------------------------------------------------------------------------
 template <int MT, int NB, int U>
 struct Frags {
-  uint4 w[NB][U];
-  uint4 x[MT][U];
+  u32x4 w[NB][U];
+  u32x4 x[MT][U];
 };
 
 template <int MT, int NB, int U>
-__device__ inline void load_frags(Frags<MT, NB, U>& f, const uint4* const (&wp)[NB], const uint4* ap, int ktiles, int kt, int kt1) {
-  const uint4 z = make_uint4(0, 0, 0, 0);
+__device__ inline void load_frags(Frags<MT, NB, U>& f, const u32x4* const (&wp)[NB], const u32x4* ap, int ktiles, int kt, int kt1) {
+  const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     bool ok = kt + u < kt1;
     int k = ok ? kt + u : kt1 - 1;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) { uint4 t = wp[nb][(size_t)k * 64]; f.w[nb][u] = ok ? t : z; }
+    for (int nb = 0; nb < NB; ++nb) { u32x4 t = __builtin_nontemporal_load(&wp[nb][(size_t)k * 64]); f.w[nb][u] = ok ? t : z; }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) f.x[mt][u] = ap[((size_t)mt * ktiles + k) * 64];
   }
 }
 
-template <int MT, int EPI>
-__global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const uint4* __restrict__ W, int ktiles,
-                                                                        const uint4* __restrict__ A, int M, int N, GemmOut out) {
+template <int MT, int EPI, int U>
+__global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const uint4* __restrict__ W, int ktiles, int ntasks,
+                                                                        const uint4* __restrict__ A, int M, int N, GemmOut out,
+                                                                        int ksplit) {
   constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
-  constexpr int U = (MT * NB >= 4) ? 2 : 4;
-  __shared__ float4 red[EE_MAX_WAVES - 1][NB * MT][64];
+  __shared__ float4 red[EE_MAX_WAVES][NB * MT][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  const int tile0 = blockIdx.x * NB;
-  const int per = (ktiles + nw - 1) / nw;
-  const int kt0 = wave * per, kt1 = min(ktiles, kt0 + per);
+  const int task = blockIdx.x * (nw / ksplit) + wave / ksplit, kpart = wave % ksplit;
+  const bool active = task < ntasks;
+  const int per = (ktiles + ksplit - 1) / ksplit;
+  const int kt0 = kpart * per, kt1 = min(ktiles, kt0 + per);
 
   f32x4 acc[NB][MT];
 #pragma unroll
@@ -80,11 +110,11 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  if (kt0 < kt1) {
-    const uint4* wp[NB];
+  if (active && kt0 < kt1) {
+    const u32x4* wp[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) wp[nb] = W + (size_t)(tile0 + nb) * ktiles * 64 + lane;
-    const uint4* ap = A + lane;
+    for (int nb = 0; nb < NB; ++nb) wp[nb] = (const u32x4*)W + (size_t)(task * NB + nb) * ktiles * 64 + lane;
+    const u32x4* ap = (const u32x4*)A + lane;
     Frags<MT, NB, U> cur, nxt;
     load_frags<MT, NB, U>(cur, wp, ap, ktiles, kt0, kt1);
     for (int kt = kt0; kt < kt1; kt += U) {
@@ -100,31 +130,34 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
     }
   }
 
-  // fixed-order cross-wave reduction
-  if (wave > 0) {
+  if (ksplit > 1) {   // fixed-order reduction over the K parts of a task (uniform branch: no wave left before it)
+    if (kpart > 0) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+      for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        red[wave - 1][nb * MT + mt][lane] = make_float4(acc[nb][mt][0], acc[nb][mt][1], acc[nb][mt][2], acc[nb][mt][3]);
+        for (int mt = 0; mt < MT; ++mt)
+          red[wave][nb * MT + mt][lane] = make_float4(acc[nb][mt][0], acc[nb][mt][1], acc[nb][mt][2], acc[nb][mt][3]);
+    }
+    __syncthreads();
+    if (kpart == 0) {
+      for (int w = 1; w < ksplit; ++w)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            float4 t = red[wave + w][nb * MT + mt][lane];
+            acc[nb][mt][0] += t.x; acc[nb][mt][1] += t.y; acc[nb][mt][2] += t.z; acc[nb][mt][3] += t.w;
+          }
+    }
   }
-  __syncthreads();
-  if (wave != 0) return;
-  for (int w = 1; w < nw; ++w)
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        float4 t = red[w - 1][nb * MT + mt][lane];
-        acc[nb][mt][0] += t.x; acc[nb][mt][1] += t.y; acc[nb][mt][2] += t.z; acc[nb][mt][3] += t.w;
-      }
+  if (kpart != 0 || !active) return;
 
   const int g = lane >> 4, mc = lane & 15;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int m = mt * 16 + mc;
     if (EPI == EPI_STORE || EPI == EPI_ADD) {
-      const int n = blockIdx.x * 16 + 4 * g;
+      const int n = task * 16 + 4 * g;
       if (m < M) {
         float4* p = (float4*)(out.Y + (size_t)m * out.ldy + n);
         float4 r = make_float4(acc[0][mt][0], acc[0][mt][1], acc[0][mt][2], acc[0][mt][3]);
@@ -132,7 +165,7 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
         *p = r;
       }
     } else if (EPI == EPI_SWIGLU) {
-      const int f = blockIdx.x * 16 + 4 * g;     // h[m][f..f+3] = silu(gate) * up
+      const int f = task * 16 + 4 * g;     // h[m][f..f+3] = silu(gate) * up
       if (m < M) {
         float h[4];
 #pragma unroll
@@ -147,7 +180,7 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
       float best = -INFINITY; int bi = 0x7fffffff;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int n = blockIdx.x * 16 + 4 * g + v;
+        const int n = task * 16 + 4 * g + v;
         float t = acc[0][mt][v];
         if (n < N) {
           if (out.Y && m < M) out.Y[(size_t)m * out.ldy + n] = t;
@@ -160,28 +193,31 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
         if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
       }
       if (g == 0 && m < M) {
-        out.pmax[(size_t)blockIdx.x * out.pstride + m] = best;
-        out.pidx[(size_t)blockIdx.x * out.pstride + m] = bi;
+        out.pmax[(size_t)task * out.pstride + m] = best;
+        out.pidx[(size_t)task * out.pstride + m] = bi;
       }
     }
   }
 }
 
-template <int MT>
+template <int MT, int U>
 static void launch_gemm_mt(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int M, int N,
-                           const GemmOut& out, int waves) {
-  dim3 blk(64 * waves);
+                           const GemmOut& out, int nw, int ksplit) {
+  dim3 blk(64 * nw);
+  const int tpw = nw / ksplit;
+  const int ntasks = epi == EPI_SWIGLU ? ntiles / 2 : ntiles;
+  dim3 grid(ceil_div(ntasks, tpw));
   switch (epi) {
-    case EPI_STORE: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_STORE>), dim3(ntiles), blk, 0, st, W, ktiles, A, M, N, out); break;
-    case EPI_ADD: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ADD>), dim3(ntiles), blk, 0, st, W, ktiles, A, M, N, out); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_SWIGLU>), dim3(ntiles / 2), blk, 0, st, W, ktiles, A, M, N, out); break;
-    default: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ARGMAX>), dim3(ntiles), blk, 0, st, W, ktiles, A, M, N, out); break;
+    case EPI_STORE: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_STORE, U>), grid, blk, 0, st, W, ktiles, ntasks, A, M, N, out, ksplit); break;
+    case EPI_ADD: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ADD, U>), grid, blk, 0, st, W, ktiles, ntasks, A, M, N, out, ksplit); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_SWIGLU, U>), grid, blk, 0, st, W, ktiles, ntasks, A, M, N, out, ksplit); break;
+    default: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ARGMAX, U>), grid, blk, 0, st, W, ktiles, ntasks, A, M, N, out, ksplit); break;
   }
 }
 
-// M may exceed 64: rows are processed in chunks of 64 (weights are re-streamed per chunk).
-void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out0) {
-  int waves = ktiles >= 64 ? 8 : (ktiles >= 16 ? 4 : (ktiles >= 4 ? 2 : 1));
+// launch shape: nw waves per workgroup, ksplit of them per task, register pipeline depth U (2, 4 or 8)
+void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
+                   const GemmOut& out0, int nw, int ksplit, int U) {
   for (int m0 = 0; m0 < M; m0 += 64) {
     int mc = min(64, M - m0);
     GemmOut out = out0;
@@ -190,10 +226,28 @@ void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles,
     if (out.pmax) { out.pmax += m0; out.pidx += m0; }
     const uint4* Ac = (const uint4*)A + (size_t)(m0 / 16) * ktiles * 64;
     const uint4* Wc = (const uint4*)W;
-    if (mc <= 16) launch_gemm_mt<1>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, waves);
-    else if (mc <= 32) launch_gemm_mt<2>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, waves);
-    else launch_gemm_mt<4>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, waves);
+    if (mc <= 16) {
+      if (U >= 8) launch_gemm_mt<1, 8>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
+      else if (U >= 4) launch_gemm_mt<1, 4>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
+      else launch_gemm_mt<1, 2>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
+    } else if (mc <= 32) {
+      if (U >= 4) launch_gemm_mt<2, 4>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
+      else launch_gemm_mt<2, 2>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
+    } else {
+      launch_gemm_mt<4, 2>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
+    }
   }
+}
+
+// Launch shape by task count (measured on MI355X at M <= 16): many tasks -> one wave streams a whole
+// strip (no reduction, deepest pipeline); few tasks -> split K over the waves of a workgroup so that
+// about two thousand waves are in flight.  M may exceed 64: rows go in chunks of 64 (weights re-streamed).
+void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out) {
+  const int ntasks = epi == EPI_SWIGLU ? ntiles / 2 : ntiles;
+  int ksplit = ntasks >= 768 ? 1 : (ntasks >= 320 ? 4 : 8);
+  while (ksplit > 1 && ktiles / ksplit < 4) ksplit >>= 1;
+  const int nw = ksplit > 4 ? ksplit : 4;
+  bf16_gemm_cfg(st, epi, W, ntiles, ktiles, A, M, N, out, nw, ksplit, ksplit == 1 ? 8 : 4);
 }
 
 __global__ void bf16_argmax_reduce_kernel(const float* pmax, const int* pidx, int ntiles, int pstride, int* v) {
@@ -400,30 +454,50 @@ __global__ __launch_bounds__(512) void attn_split_kernel(const uint4* __restrict
   for (int dt = 0; dt < DT; ++dt) *(float4*)(po + dt * 16 + 4 * g) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
 }
 
-// merge the KV splits and emit the bf16 attention output in fragment layout (O-projection operand)
-__global__ void attn_combine_kernel(const float* part_o, const float* part_ml, const int* qt_seq, const int* qt_local,
-                                    const int* seq_m, const int* seq_row0, int rep, int Hkv, int D, int nsplit, bf16_t* out,
-                                    int out_ktiles) {
+// merge the KV splits and emit the bf16 attention output in fragment layout (O-projection operand):
+// first the normalised weight of every (query row, split) pair goes to LDS, then each thread sums
+// four output dims over the splits with coalesced float4 reads.
+#define EE_MAX_SPLITS 64
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                           const int* qt_seq, const int* qt_local, const int* seq_m,
+                                                           const int* seq_row0, int rep, int Hkv, int D, int nsplit,
+                                                           bf16_t* out, int out_ktiles) {
+  __shared__ float w[16][EE_MAX_SPLITS];
   const int gqt = blockIdx.x, kvh = blockIdx.y;
   const int b = qt_seq[gqt], qt = qt_local[gqt];
   const int nq = seq_m[b] * rep;
   const size_t slot0 = ((size_t)gqt * Hkv + kvh) * nsplit;
-  for (int i = threadIdx.x; i < 16 * D; i += blockDim.x) {
-    int qc = i / D, d = i % D;
-    int qrow = qt * 16 + qc;
-    if (qrow >= nq) continue;
-    float M = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part_ml[(slot0 + s) * 32 + qc * 2]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
+  {
+    // 16 threads per query row: each takes splits s = t, t+16, ...
+    const int qc = threadIdx.x >> 4, t = threadIdx.x & 15;
+    float mloc = -INFINITY;
+    for (int s = t; s < nsplit; s += 16) mloc = fmaxf(mloc, part_ml[(slot0 + s) * 32 + qc * 2]);
+    for (int sh = 1; sh < 16; sh <<= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, sh, 64));
+    float den = 0.f;
+    for (int s = t; s < nsplit; s += 16) {
       float ms = part_ml[(slot0 + s) * 32 + qc * 2];
-      if (ms == -INFINITY) continue;
-      float w = __expf(ms - M);
-      den += w * part_ml[(slot0 + s) * 32 + qc * 2 + 1];
-      num += w * part_o[((slot0 + s) * 16 + qc) * D + d];
+      float e = ms == -INFINITY ? 0.f : __expf(ms - mloc);
+      w[qc][s] = e;
+      den += e * part_ml[(slot0 + s) * 32 + qc * 2 + 1];
     }
-    int row = seq_row0[b] + qrow / rep, col = (kvh * rep + qrow % rep) * D + d;
-    out[frag_offset(row, col, out_ktiles)] = f32_to_bf16(num / den);
+    for (int sh = 1; sh < 16; sh <<= 1) den += __shfl_xor(den, sh, 64);
+    const float inv = 1.0f / den;
+    for (int s = t; s < nsplit; s += 16) w[qc][s] *= inv;
+  }
+  __syncthreads();
+  const int d4n = D >> 2;
+  for (int i = threadIdx.x; i < 16 * d4n; i += blockDim.x) {
+    const int qc = i / d4n, d = (i % d4n) * 4;
+    const int qrow = qt * 16 + qc;
+    if (qrow >= nq) continue;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < nsplit; ++s) {
+      const float ws = w[qc][s];
+      const float4 o = *(const float4*)(part_o + ((slot0 + s) * 16 + qc) * D + d);
+      acc.x += ws * o.x; acc.y += ws * o.y; acc.z += ws * o.z; acc.w += ws * o.w;
+    }
+    const int row = seq_row0[b] + qrow / rep, col = (kvh * rep + qrow % rep) * D + d;
+    *(uint2*)(out + frag_offset(row, col, out_ktiles)) = make_uint2(pack2(acc.x, acc.y), pack2(acc.z, acc.w));
   }
 }
 
@@ -434,8 +508,9 @@ void bf16_attention(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const Cal
   const int max_qt = ceil_div(max_m * rep, 16);
   const int qt_groups = ceil_div(max_qt, 8), waves = min(max_qt, 8);
   const int max_pages = ceil_div(max_kv_end, EE_PAGE);
-  int nsplit = ceil_div(1024, max(1, B * Hkv * max_qt));
-  nsplit = max(1, min(nsplit, min(max_pages, scr.max_splits)));
+  // enough (split, head, q-tile) waves to cover the chip, but at least two pages per wave when possible
+  int nsplit = ceil_div(768, max(1, B * Hkv * max_qt));
+  nsplit = max(1, min(nsplit, min(ceil_div(max_pages, 2), min(scr.max_splits, EE_MAX_SPLITS))));
   dim3 grid(nsplit, Hkv * qt_groups, B), blk(64 * waves);
   if (D == 128)
     hipLaunchKernelGGL((attn_split_kernel<128>), grid, blk, 0, st, (const uint4*)Q, kv, meta.seq_m, meta.seq_p0, meta.seq_qt0,

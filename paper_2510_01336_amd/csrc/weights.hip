@@ -32,6 +32,9 @@ static int check_config(const ee_config* c) {
   if (c->dtype == EE_BF16 && c->head_dim != 64 && c->head_dim != 128) {
     ee_set_error("EE_BF16 models need head_dim 64 or 128"); return EE_ERR_ARG;
   }
+  if (c->dtype == EE_BF16 && (c->d_model % 16 || c->d_model > 16384)) {
+    ee_set_error("EE_BF16 models need d_model to be a multiple of 16, at most 16384"); return EE_ERR_ARG;
+  }
   if (c->head_dim % 2 || c->head_dim > 256) { ee_set_error("head_dim must be even and <= 256"); return EE_ERR_ARG; }
   if (c->n_q_heads / c->n_kv_heads > 16) { ee_set_error("at most 16 query heads per KV head"); return EE_ERR_ARG; }
   if (!(c->rope_theta > 1.f) || !(c->rms_eps > 0.f)) { ee_set_error("bad rope_theta / rms_eps"); return EE_ERR_ARG; }

@@ -335,7 +335,8 @@ def test_batched_equals_solo():
         a, n = solo.verify_intermediate()
         assert (a[0], n[0]) == (ga[b], gn[b])
         sl = solo.last_logits()
-        assert np.array_equal(sl, blog[r0:r0 + len(sl)])     # same kernels, same order: bit-identical
+        # same kernels; only the KV-split count may differ with the batch shape, so not bit-identical
+        assert max_rel(sl, blog[r0:r0 + len(sl)].astype(np.float64)) <= 1e-3
         r0 += len(sl)
         f, fn, com = solo.verify_full()
         assert (f[0], fn[0], com[0]) == (gf[b], gfn[b], gcom[b])
