@@ -335,8 +335,9 @@ def test_batched_equals_solo():
         a, n = solo.verify_intermediate()
         assert (a[0], n[0]) == (ga[b], gn[b])
         sl = solo.last_logits()
-        # same kernels; only the KV-split count may differ with the batch shape, so not bit-identical
-        assert max_rel(sl, blog[r0:r0 + len(sl)].astype(np.float64)) <= 1e-3
+        # same kernels, but the KV-split count follows the batch shape: a last-bit difference in an fp32
+        # sum can flip the bf16 rounding of an activation, so the two runs agree to bf16 accuracy only
+        assert max_rel(sl, blog[r0:r0 + len(sl)].astype(np.float64)) <= TOL["bf16"]
         r0 += len(sl)
         f, fn, com = solo.verify_full()
         assert (f[0], fn[0], com[0]) == (gf[b], gfn[b], gcom[b])
