@@ -119,15 +119,25 @@ struct TensorMap {
   int rows, cols;
   size_t off;      // byte offset of matrix / vector / embedding
   int row_off;     // first physical row (fused QKV)
-  int interleave;  // 0 none, 1 gate (tiles 2j), 2 up (tiles 2j+1)
+  int interleave;  // 0 none, 1 gate (tiles 2j), 2 up (tiles 2j+1), 3 rotary halves of a head (see phys_row)
   int Kp;          // padded K of the matrix
+  int hd;          // head_dim (interleave 3 only)
 };
 int ee_tensor_map(const ee_model* m, int tensor_id, int layer, TensorMap* out);
 int ee_layout_model(ee_model* m);   // fills offsets, returns total bytes in m->bytes
 
-// physical row of logical row n
-__host__ __device__ inline int phys_row(int n, int row_off, int interleave) {
+// physical row of logical row n.
+// interleave 1/2: gate and up tiles alternate, so one GEMM task (two adjacent 16-row tiles) holds gate and
+// up of the same 16 features.  interleave 3 (fused QKV of bf16 models): inside every head the 16-row tiles
+// of the two rotary halves alternate -- tile 2j holds features 16j..16j+15, tile 2j+1 their partners
+// D/2 + 16j.. -- so one GEMM task holds both elements of 16 rotary pairs.
+__host__ __device__ inline int phys_row(int n, int row_off, int interleave, int hd) {
   if (interleave == 0) return row_off + n;
+  if (interleave == 3) {
+    const int r = row_off + n, h = r / hd, f = r % hd, half = hd >> 1;
+    const int hi = f >= half ? 1 : 0, fj = (f - hi * half) >> 4;
+    return h * hd + ((2 * fj + hi) << 4) + (f & 15);
+  }
   return (((n >> 4) * 2 + (interleave - 1)) << 4) | (n & 15);
 }
 

@@ -31,22 +31,46 @@ void f32_silu_mul(hipStream_t st, const float* GU, int ldg, float* H, int M, int
 void f32_argmax(hipStream_t st, const float* logits, int M, int V, int* v);
 
 // ---- bf16 MFMA path (EE_BF16 models) ---------------------------------------------------------
-enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2, EPI_ARGMAX = 3 };
+enum { EPI_ADD = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_ROPE = 3 };
+// Deferred RMSNorm of a GEMM's activation operand: the rows hold bf16(x * gain) and the per-row factor
+// rsqrt(mean(x^2) + eps) is applied to the fp32 accumulators in the epilogue (it commutes with the
+// product).  ssq holds partial sums of squares [n_part][stride] left by the GEMM that produced x;
+// null = the operand is already fully normalised.
+struct NormIn {
+  const float* ssq = nullptr; int n_part = 0, stride = 0; float inv_d = 0.f, eps = 0.f;
+};
+// EPI_ADD extra output: the updated residual rows as the next GEMM's operand, bf16(x * g) in fragment
+// layout, plus this tile's partial sums of squares ssq[tile][row].
+struct NormOut {
+  const float* g = nullptr; bf16_t* xn = nullptr; int ktiles = 0; float* ssq = nullptr; int stride = 0;
+};
+// EPI_ROPE (fused QKV projection): rotate Q and K, write Q tiles for the attention kernel and K/V into
+// their cache pages.
+struct RopeOut {
+  const float2* cs = nullptr;   // [rows][D/2] (cos, sin) of every row's position
+  const int *row_seq = nullptr, *row_pos = nullptr, *seq_row0 = nullptr, *seq_qt0 = nullptr, *block_table = nullptr;
+  int pos_add = 0, Hq = 0, Hkv = 0, D = 0, layer = 0, n_pages = 0, pps = 0, total_qt = 0;
+  bf16_t *Q = nullptr, *kv = nullptr;
+};
 struct GemmOut {
-  float* Y = nullptr; int ldy = 0;        // EPI_STORE / EPI_ADD target (row-major fp32); EPI_ARGMAX: optional logits
+  float* Y = nullptr; int ldy = 0;        // EPI_ADD: residual stream, Y += product (row-major fp32); EPI_ARGMAX: optional logits
   bf16_t* H = nullptr; int h_ktiles = 0;  // EPI_SWIGLU target (fragment layout)
   float* pmax = nullptr; int* pidx = nullptr; int pstride = 0;   // EPI_ARGMAX partials [ntiles][pstride]
+  NormIn nin;
+  NormOut nout;
+  RopeOut rope;
 };
-// Y^T tile = W tile (A operand) x X^T (B operand); W, A in fragment layout; M <= 64 rows per launch
+// Y^T tile = W tile (A operand) x X^T (B operand); W, A in fragment layout.  Rows go in passes of 64.
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out);
 void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                    const GemmOut& out, int nw, int ksplit, int U);
 void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf16_t* out, int ktiles, int M, int d);
-void bf16_rope_append(hipStream_t st, const float* QKV, int ldq, const float2* cs, const CallMeta& meta, int pos_add, int M,
-                      int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq, int total_qt,
-                      bf16_t* Q, bf16_t* kv);
 struct AttnScratch { float* part_o; float* part_ml; int max_splits; };
 void bf16_attention(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,
                     int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
                     const AttnScratch& scr, bf16_t* out, int out_ktiles);
+// same with an explicit number of KV splits (<= 0: chosen from the shape; must not exceed scr.max_splits)
+void bf16_attention_cfg(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,
+                        int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
+                        const AttnScratch& scr, bf16_t* out, int out_ktiles, int nsplit);
 void bf16_argmax_reduce(hipStream_t st, const float* pmax, const int* pidx, int ntiles, int pstride, int M, int* v);

@@ -10,6 +10,7 @@
 // LDS staging or transposition is needed anywhere on the streaming path.
 #include "kernels.h"
 #include <cmath>
+#include <type_traits>
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 __device__ inline f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
@@ -18,7 +19,13 @@ __device__ inline f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
 __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
-__device__ inline uint32_t pack2(float lo, float hi) { return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16); }
+// two fp32 -> packed bf16 pair (lo in bits 0..15), round to nearest even: one v_cvt_pk_bf16_f32
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pack2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 // ---------------------------------------------------------------------------------------------
 // RMSNorm: fp32 row in, bf16 fragment-layout row out (the next GEMM's B operand)
@@ -64,13 +71,22 @@ void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf1
 }
 
 // ---------------------------------------------------------------------------------------------
-// Skinny GEMM  Y[m][n] = sum_k X[m][k] W[n][k],  M <= 16*MT rows, weights streamed once.
-// A task is one 16-row weight tile strip over the whole K (two strips for SwiGLU: the gate tile and
-// its up tile).  A workgroup of nw waves runs nw/ksplit tasks; the ksplit waves of a task split K
+// Skinny GEMM  Y[m][n] = sum_k X[m][k] W[n][k],  M <= 16*MT rows per launch, weights streamed once.
+// A task is one 16-row weight tile strip over the whole K, or two adjacent strips (NB = 2) when the
+// epilogue needs both at once: gate and up of the same features (SwiGLU), or the two rotary halves of
+// a head (RoPE).  A workgroup of nw waves runs nw/ksplit tasks; the ksplit waves of a task split K
 // into contiguous chunks, each wave streaming its chunk (1 KiB per MFMA step) through a two-stage
 // register pipeline of depth U; the partial 16x16 tiles are then summed through LDS in a fixed
 // order (deterministic) and the task's first wave runs the epilogue.
 // The MFMA computes Y^T = W X^T so that a lane ends up with 4 consecutive n of one row m.
+//
+// Epilogues (everything between two projections is fused here, so a layer is five launches):
+//   EPI_ADD     residual add into the fp32 stream; optionally emits the next projection's operand
+//               bf16(x_new * gain) and this tile's partial sum of squares per row (deferred RMSNorm)
+//   EPI_SWIGLU  silu(gate) * up  -> bf16 operand of the down projection
+//   EPI_ROPE    rotary embedding of Q and K; Q tiles for the attention kernel; K, V into cache pages
+//   EPI_ARGMAX  per-row (max, arg max) of the tile (+ optional fp32 logits)
+// Every epilogue first applies the operand's deferred RMSNorm factor (NormIn).
 // ---------------------------------------------------------------------------------------------
 template <int MT, int NB, int U>
 struct Frags {
@@ -94,10 +110,11 @@ __device__ inline void load_frags(Frags<MT, NB, U>& f, const u32x4* const (&wp)[
 
 template <int MT, int EPI, int U>
 __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const uint4* __restrict__ W, int ktiles, int ntasks,
-                                                                        const uint4* __restrict__ A, int M, int N, GemmOut out,
-                                                                        int ksplit) {
-  constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
-  __shared__ float4 red[EE_MAX_WAVES][NB * MT][64];
+                                                                        const uint4* __restrict__ A, int row0, int M, int N,
+                                                                        GemmOut out, int ksplit) {
+  constexpr int NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
+  __shared__ float4 red[EE_MAX_WAVES - 1][NB * MT][64];
+  __shared__ float ssq_red[EE_MAX_WAVES][MT * 16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int task = blockIdx.x * (nw / ksplit) + wave / ksplit, kpart = wave % ksplit;
   const bool active = task < ntasks;
@@ -110,13 +127,54 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  if (active && kt0 < kt1) {
-    const u32x4* wp[NB];
+  const bool stream = active && kt0 < kt1;
+  const u32x4* wp[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) wp[nb] = (const u32x4*)W + (size_t)(task * NB + nb) * ktiles * 64 + lane;
-    const u32x4* ap = (const u32x4*)A + lane;
-    Frags<MT, NB, U> cur, nxt;
+  for (int nb = 0; nb < NB; ++nb) wp[nb] = (const u32x4*)W + (size_t)(task * NB + nb) * ktiles * 64 + lane;
+  const u32x4* ap = (const u32x4*)A + (size_t)(row0 >> 4) * ktiles * 64 + lane;
+  Frags<MT, NB, U> cur, nxt;
+
+  // Deferred RMSNorm: sum of squares of row mt*16 + lane%16 from the producer's per-tile partials, in a
+  // fixed order.  The ksplit waves of a task each sum a contiguous share of the partials (lane group g
+  // takes every 4th); the first batch is requested before the first weight fragments and added once
+  // those are in flight, so its (L2) latency hides under the first HBM fetch.
+  constexpr int SB = 16;   // partials per lane, m-tile and batch
+  const bool normed = out.nin.ssq != nullptr && active;
+  float ssl[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) ssl[mt] = 0.f;
+  if (normed) {
+    const int np = out.nin.n_part, cp = (np + ksplit - 1) / ksplit;
+    const int c0 = kpart * cp + (lane >> 4), c1 = min(np, (kpart + 1) * cp);
+    const float* p = out.nin.ssq + row0 + (lane & 15);
+    float t[MT][SB];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < SB; ++j) { const int i = c0 + 4 * j; t[mt][j] = i < c1 ? p[(size_t)i * out.nin.stride + mt * 16] : 0.f; }
+    if (stream) load_frags<MT, NB, U>(cur, wp, ap, ktiles, kt0, kt1);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < SB; ++j) ssl[mt] += t[mt][j];
+    for (int b0 = c0 + 4 * SB; b0 < c1; b0 += 4 * SB)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int j = 0; j < SB; ++j) { const int i = b0 + 4 * j; t[mt][j] = i < c1 ? p[(size_t)i * out.nin.stride + mt * 16] : 0.f; }
+#pragma unroll
+        for (int j = 0; j < SB; ++j) ssl[mt] += t[mt][j];
+      }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      ssl[mt] += __shfl_xor(ssl[mt], 16, 64);
+      ssl[mt] += __shfl_xor(ssl[mt], 32, 64);
+    }
+  } else if (stream) {
     load_frags<MT, NB, U>(cur, wp, ap, ktiles, kt0, kt1);
+  }
+
+  if (stream) {
     for (int kt = kt0; kt < kt1; kt += U) {
       const bool more = kt + U < kt1;
       if (more) load_frags<MT, NB, U>(nxt, wp, ap, ktiles, kt + U, kt1);
@@ -130,60 +188,126 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
     }
   }
 
-  if (ksplit > 1) {   // fixed-order reduction over the K parts of a task (uniform branch: no wave left before it)
+  // fixed-order reduction over the K parts of a task (every wave reaches the barrier)
+  if (ksplit > 1) {   // uniform branch
+    if (normed && lane < 16) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) ssq_red[wave][mt * 16 + lane] = ssl[mt];
+    }
     if (kpart > 0) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          red[wave][nb * MT + mt][lane] = make_float4(acc[nb][mt][0], acc[nb][mt][1], acc[nb][mt][2], acc[nb][mt][3]);
+          red[wave - 1][nb * MT + mt][lane] = make_float4(acc[nb][mt][0], acc[nb][mt][1], acc[nb][mt][2], acc[nb][mt][3]);
     }
     __syncthreads();
-    if (kpart == 0) {
-      for (int w = 1; w < ksplit; ++w)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            float4 t = red[wave + w][nb * MT + mt][lane];
-            acc[nb][mt][0] += t.x; acc[nb][mt][1] += t.y; acc[nb][mt][2] += t.z; acc[nb][mt][3] += t.w;
-          }
-    }
   }
   if (kpart != 0 || !active) return;
+  for (int w = 1; w < ksplit; ++w)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        float4 t = red[wave + w - 1][nb * MT + mt][lane];
+        acc[nb][mt][0] += t.x; acc[nb][mt][1] += t.y; acc[nb][mt][2] += t.z; acc[nb][mt][3] += t.w;
+      }
 
   const int g = lane >> 4, mc = lane & 15;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int m = mt * 16 + mc;
-    if (EPI == EPI_STORE || EPI == EPI_ADD) {
+    const int m = mt * 16 + mc, row = row0 + m;
+    const bool ok = m < M;
+    float sc = 1.0f;
+    if (normed) {
+      float ss = ssl[mt];
+      for (int w = 1; w < ksplit; ++w) ss += ssq_red[wave + w][m];
+      sc = 1.0f / sqrtf(ss * out.nin.inv_d + out.nin.eps);
+    }
+    if (EPI == EPI_ADD) {
       const int n = task * 16 + 4 * g;
-      if (m < M) {
-        float4* p = (float4*)(out.Y + (size_t)m * out.ldy + n);
-        float4 r = make_float4(acc[0][mt][0], acc[0][mt][1], acc[0][mt][2], acc[0][mt][3]);
-        if (EPI == EPI_ADD) { float4 o = *p; r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w; }
+      float4 r = make_float4(acc[0][mt][0] * sc, acc[0][mt][1] * sc, acc[0][mt][2] * sc, acc[0][mt][3] * sc);
+      if (ok) {
+        float4* p = (float4*)(out.Y + (size_t)row * out.ldy + n);
+        const float4 o = *p;
+        r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w;
         *p = r;
+      }
+      if (out.nout.xn) {
+        const float4 gn = *(const float4*)(out.nout.g + n);
+        if (ok) *(uint2*)(out.nout.xn + frag_offset(row, n, out.nout.ktiles)) = make_uint2(pack2(r.x * gn.x, r.y * gn.y), pack2(r.z * gn.z, r.w * gn.w));
+        float ss = ok ? (r.x * r.x + r.y * r.y) + (r.z * r.z + r.w * r.w) : 0.f;
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (g == 0) out.nout.ssq[(size_t)task * out.nout.stride + row] = ss;
       }
     } else if (EPI == EPI_SWIGLU) {
       const int f = task * 16 + 4 * g;     // h[m][f..f+3] = silu(gate) * up
-      if (m < M) {
+      if (ok) {
         float h[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          float gt = acc[0][mt][v], up = acc[NB - 1][mt][v];
+          float gt = acc[0][mt][v] * sc, up = acc[NB - 1][mt][v] * sc;
           h[v] = gt / (1.0f + __expf(-gt)) * up;
         }
-        uint2 pk = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
-        *(uint2*)(out.H + frag_offset(m, f, out.h_ktiles)) = pk;
+        *(uint2*)(out.H + frag_offset(row, f, out.h_ktiles)) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
+      }
+    } else if (EPI == EPI_ROPE) {
+      // task = (head h, 16 rotary pairs f0..f0+15): acc[0] holds features f, acc[1] their partners f + D/2
+      const RopeOut& R = out.rope;
+      const int D = R.D, half = D >> 1, tph = D >> 5;
+      const int h = task / tph, f = (task % tph) * 16 + 4 * g;
+      if (ok) {
+        float lo[4], hi[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) { lo[v] = acc[0][mt][v] * sc; hi[v] = acc[NB - 1][mt][v] * sc; }
+        const int sq = R.row_seq[row];
+        if (h < R.Hq + R.Hkv) {
+          const float4* c4 = (const float4*)(R.cs + (size_t)row * half + f);
+          const float4 c01 = c4[0], c23 = c4[1];
+          const float cx[4] = {c01.x, c01.z, c23.x, c23.z}, sy[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const float a = lo[v], b = hi[v];
+            lo[v] = a * cx[v] - b * sy[v];
+            hi[v] = b * cx[v] + a * sy[v];
+          }
+        }
+        const uint2 plo = make_uint2(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]));
+        const uint2 phi = make_uint2(pack2(hi[0], hi[1]), pack2(hi[2], hi[3]));
+        if (h < R.Hq) {
+          const int rep = R.Hq / R.Hkv, kvh = h / rep;
+          const int q = (row - R.seq_row0[sq]) * rep + h % rep;
+          const size_t tile = ((size_t)kvh * R.total_qt + R.seq_qt0[sq] + (q >> 4)) * tph;
+          const int d1 = f + half;
+          *(uint2*)(R.Q + ((tile + (f >> 5)) * 64 + ((f & 31) >> 3) * 16 + (q & 15)) * 8 + (f & 7)) = plo;
+          *(uint2*)(R.Q + ((tile + (d1 >> 5)) * 64 + ((d1 & 31) >> 3) * 16 + (q & 15)) * 8 + (d1 & 7)) = phi;
+        } else {
+          const int pos = R.row_pos[row] + R.pos_add;
+          const int page = R.block_table[sq * R.pps + pos / EE_PAGE], pp = pos % EE_PAGE;
+          if (h < R.Hq + R.Hkv) {
+            bf16_t* slab = R.kv + kv_slab(R.layer, page, h - R.Hq, R.n_pages, R.Hkv, D);
+            *(uint2*)(slab + k_page_off(pp, f, D)) = plo;
+            *(uint2*)(slab + k_page_off(pp, f + half, D)) = phi;
+          } else {
+            bf16_t* slab = R.kv + kv_slab(R.layer, page, h - R.Hq - R.Hkv, R.n_pages, R.Hkv, D) + EE_PAGE * D;
+            const uint32_t wl[2] = {plo.x, plo.y}, wh[2] = {phi.x, phi.y};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              slab[v_page_off(pp, f + v, D)] = (bf16_t)(wl[v >> 1] >> (16 * (v & 1)));
+              slab[v_page_off(pp, f + half + v, D)] = (bf16_t)(wh[v >> 1] >> (16 * (v & 1)));
+            }
+          }
+        }
       }
     } else {   // EPI_ARGMAX: per-row (max, arg max) over this tile's 16 outputs; lowest index wins ties
       float best = -INFINITY; int bi = 0x7fffffff;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int n = task * 16 + 4 * g + v;
-        float t = acc[0][mt][v];
+        float t = acc[0][mt][v] * sc;
         if (n < N) {
-          if (out.Y && m < M) out.Y[(size_t)m * out.ldy + n] = t;
+          if (out.Y && ok) out.Y[(size_t)row * out.ldy + n] = t;
           if (t > best) { best = t; bi = n; }
         }
       }
@@ -192,58 +316,54 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
         float ob = __shfl_xor(best, sh, 64); int oi = __shfl_xor(bi, sh, 64);
         if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
       }
-      if (g == 0 && m < M) {
-        out.pmax[(size_t)task * out.pstride + m] = best;
-        out.pidx[(size_t)task * out.pstride + m] = bi;
+      if (g == 0 && ok) {
+        out.pmax[(size_t)task * out.pstride + row] = best;
+        out.pidx[(size_t)task * out.pstride + row] = bi;
       }
     }
   }
 }
 
 template <int MT, int U>
-static void launch_gemm_mt(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int M, int N,
+static void launch_gemm_mt(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int row0, int M, int N,
                            const GemmOut& out, int nw, int ksplit) {
   dim3 blk(64 * nw);
   const int tpw = nw / ksplit;
-  const int ntasks = epi == EPI_SWIGLU ? ntiles / 2 : ntiles;
+  const int ntasks = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? ntiles / 2 : ntiles;
   dim3 grid(ceil_div(ntasks, tpw));
   switch (epi) {
-    case EPI_STORE: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_STORE, U>), grid, blk, 0, st, W, ktiles, ntasks, A, M, N, out, ksplit); break;
-    case EPI_ADD: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ADD, U>), grid, blk, 0, st, W, ktiles, ntasks, A, M, N, out, ksplit); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_SWIGLU, U>), grid, blk, 0, st, W, ktiles, ntasks, A, M, N, out, ksplit); break;
-    default: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ARGMAX, U>), grid, blk, 0, st, W, ktiles, ntasks, A, M, N, out, ksplit); break;
+    case EPI_ADD: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ADD, U>), grid, blk, 0, st, W, ktiles, ntasks, A, row0, M, N, out, ksplit); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_SWIGLU, U>), grid, blk, 0, st, W, ktiles, ntasks, A, row0, M, N, out, ksplit); break;
+    case EPI_ROPE: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ROPE, U>), grid, blk, 0, st, W, ktiles, ntasks, A, row0, M, N, out, ksplit); break;
+    default: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ARGMAX, U>), grid, blk, 0, st, W, ktiles, ntasks, A, row0, M, N, out, ksplit); break;
   }
 }
 
 // launch shape: nw waves per workgroup, ksplit of them per task, register pipeline depth U (2, 4 or 8)
 void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
-                   const GemmOut& out0, int nw, int ksplit, int U) {
+                   const GemmOut& out, int nw, int ksplit, int U) {
+  const uint4* Wc = (const uint4*)W;
+  const uint4* Ac = (const uint4*)A;
   for (int m0 = 0; m0 < M; m0 += 64) {
-    int mc = min(64, M - m0);
-    GemmOut out = out0;
-    if (out.Y) out.Y += (size_t)m0 * out.ldy;
-    if (out.H) out.H += (size_t)(m0 / 16) * out.h_ktiles * 512;
-    if (out.pmax) { out.pmax += m0; out.pidx += m0; }
-    const uint4* Ac = (const uint4*)A + (size_t)(m0 / 16) * ktiles * 64;
-    const uint4* Wc = (const uint4*)W;
+    const int mc = min(64, M - m0);
     if (mc <= 16) {
-      if (U >= 8) launch_gemm_mt<1, 8>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
-      else if (U >= 4) launch_gemm_mt<1, 4>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
-      else launch_gemm_mt<1, 2>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
+      if (U >= 8) launch_gemm_mt<1, 8>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
+      else if (U >= 4) launch_gemm_mt<1, 4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
+      else launch_gemm_mt<1, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
     } else if (mc <= 32) {
-      if (U >= 4) launch_gemm_mt<2, 4>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
-      else launch_gemm_mt<2, 2>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
+      if (U >= 4) launch_gemm_mt<2, 4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
+      else launch_gemm_mt<2, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
     } else {
-      launch_gemm_mt<4, 2>(st, epi, Wc, ntiles, ktiles, Ac, mc, N, out, nw, ksplit);
+      launch_gemm_mt<4, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
     }
   }
 }
 
 // Launch shape by task count (measured on MI355X at M <= 16): many tasks -> one wave streams a whole
 // strip (no reduction, deepest pipeline); few tasks -> split K over the waves of a workgroup so that
-// about two thousand waves are in flight.  M may exceed 64: rows go in chunks of 64 (weights re-streamed).
+// about two thousand waves are in flight.  M may exceed 64: rows go in passes of 64 (weights re-streamed).
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out) {
-  const int ntasks = epi == EPI_SWIGLU ? ntiles / 2 : ntiles;
+  const int ntasks = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? ntiles / 2 : ntiles;
   int ksplit = ntasks >= 768 ? 1 : (ntasks >= 320 ? 4 : 8);
   while (ksplit > 1 && ktiles / ksplit < 4) ksplit >>= 1;
   const int nw = ksplit > 4 ? ksplit : 4;
@@ -275,249 +395,385 @@ void bf16_argmax_reduce(hipStream_t st, const float* pmax, const int* pidx, int 
 }
 
 // ---------------------------------------------------------------------------------------------
-// RoPE + KV append.  Q goes to the attention kernel's B-operand layout
-//   Q[kv head][global q-tile][s = D/32][lane][8],  lane = 16*((d%32)/8) + q%16, q = row_in_seq*rep + head_in_group
-// K and V go to their cache page in fragment order (common.h).  Rotation in fp32, then bf16.
-// ---------------------------------------------------------------------------------------------
-__global__ void bf16_rope_append_kernel(const float* QKV, int ldq, const float2* cs, const int* row_seq, const int* row_pos,
-                                        const int* seq_row0, const int* seq_qt0, const int* block_table, int pos_add, int M,
-                                        int Hq, int Hkv, int D, int layer, int n_pages, int pps, int total_qt, bf16_t* Q,
-                                        bf16_t* kv) {
-  int half = D >> 1, heads = Hq + 2 * Hkv;
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= M * heads * half) return;
-  int f = i % half, h = (i / half) % heads, r = i / (half * heads);
-  const float* src = QKV + (size_t)r * ldq + (size_t)h * D;
-  float a = src[f], b = src[f + half];
-  float2 c = cs[r * half + f];
-  int sq = row_seq[r];
-  if (h < Hq) {
-    int rep = Hq / Hkv, kvh = h / rep, hh = h % rep;
-    int q = (r - seq_row0[sq]) * rep + hh;
-    size_t tile = ((size_t)kvh * total_qt + seq_qt0[sq] + (q >> 4)) * (D >> 5);
-    int d0 = f, d1 = f + half;
-    Q[((tile + (d0 >> 5)) * 64 + ((d0 & 31) >> 3) * 16 + (q & 15)) * 8 + (d0 & 7)] = f32_to_bf16(a * c.x - b * c.y);
-    Q[((tile + (d1 >> 5)) * 64 + ((d1 & 31) >> 3) * 16 + (q & 15)) * 8 + (d1 & 7)] = f32_to_bf16(b * c.x + a * c.y);
-    return;
-  }
-  int pos = row_pos[r] + pos_add;
-  int page = block_table[sq * pps + pos / EE_PAGE], pp = pos % EE_PAGE;
-  if (h < Hq + Hkv) {
-    size_t slab = kv_slab(layer, page, h - Hq, n_pages, Hkv, D);
-    kv[slab + k_page_off(pp, f, D)] = f32_to_bf16(a * c.x - b * c.y);
-    kv[slab + k_page_off(pp, f + half, D)] = f32_to_bf16(b * c.x + a * c.y);
-  } else {
-    size_t slab = kv_slab(layer, page, h - Hq - Hkv, n_pages, Hkv, D) + EE_PAGE * D;
-    kv[slab + v_page_off(pp, f, D)] = f32_to_bf16(a);
-    kv[slab + v_page_off(pp, f + half, D)] = f32_to_bf16(b);
-  }
-}
-void bf16_rope_append(hipStream_t st, const float* QKV, int ldq, const float2* cs, const CallMeta& meta, int pos_add, int M,
-                      int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq, int total_qt, bf16_t* Q, bf16_t* kv) {
-  int total = M * (Hq + 2 * Hkv) * (D / 2);
-  hipLaunchKernelGGL(bf16_rope_append_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, QKV, ldq, cs, meta.row_seq,
-                     meta.row_pos, meta.seq_row0, meta.seq_qt0, meta.block_table, pos_add, M, Hq, Hkv, D, layer, n_pages,
-                     pages_per_seq, total_qt, Q, kv);
-}
-
-// ---------------------------------------------------------------------------------------------
 // k-query causal-in-block GQA attention over the paged cache, split over the KV axis.
 // A sequence's block of m rows times the `rep` query heads sharing one KV head forms nq = m*rep
-// query rows, cut into 16-row q-tiles.  Workgroup = (KV split, KV head [x q-tile group], sequence);
-// each wave owns one q-tile and walks the split's pages.  Per page (64 positions):
+// query rows, cut into 16-row q-tiles.  Workgroup = (KV split, KV head [x group of q-tiles],
+// sequence), eight waves with fixed roles: six compute waves, each owning one q-tile, and two loader
+// waves.  The split's pages stream HBM -> loader registers -> LDS: each loader fetches half of every
+// page (1 KiB chunks) and keeps three pages in flight in its registers, which is what hides HBM latency;
+// the compute waves read whole pages back from a three-slot LDS ring, so a page crosses HBM, L2 and the
+// vector memory path once however many q-tiles consume it.  One barrier per page hands a slot over.  Per page (64 positions) and q-tile:
 //   S^T[pos][q] = K[pos][:] . Q[q][:]        4 pos-tiles x D/32 MFMAs  (K page = A operand, Q^T = B)
 //   online softmax per q column (= per lane%16; the 4 lane groups hold 16 positions each)
 //   O^T[d][q] += V^T[d][pos] P^T[pos][q]     D/16 d-tiles x 2 MFMAs    (V page = A operand, P^T = B)
 // The page's element order (common.h) makes the S^T accumulators, once exponentiated and packed to
-// bf16, exactly the B operand of the second product: no LDS, no shuffles beyond the row statistics.
+// bf16, exactly the B operand of the second product: no shuffles beyond the row statistics.
 // Row r of the block sits at position p0+r and may see cache positions 0..p0+r (its own block rows
 // included, they were appended just before).  Dead cache entries (>= p0+m) are never trusted:
 // scores are masked by select and V elements are zeroed, so NaN there cannot leak.
-// Partials (max, sum, unnormalised O) go to scratch; attn_combine merges the splits.
+// With one split the normalised output goes straight to the O-projection operand; otherwise the
+// partials (max, sum, unnormalised O) go to scratch and attn_merge_kernel combines them.
 // ---------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(512) void attn_split_kernel(const uint4* __restrict__ Q, const bf16_t* __restrict__ kv,
-                                                         const int* seq_m, const int* seq_p0, const int* seq_qt0,
-                                                         const int* block_table, int pos_add, int rep, int total_qt, int Hkv,
-                                                         int layer, int n_pages, int pps, int nsplit, float* part_o,
-                                                         float* part_ml) {
+#define EE_MAX_SPLITS 64
+#define EE_ATTN_WAVES 8
+#define EE_ATTN_COMPUTE 6   // compute waves = q-tiles per workgroup; the other waves load
+#define EE_ATTN_AHEAD 3     // pages each loader wave keeps in flight
+
+template <int D, int QPW>
+__global__ __launch_bounds__(64 * EE_ATTN_WAVES) void attn_kernel(const uint4* __restrict__ Q, const bf16_t* __restrict__ kv,
+                                                                  const int* seq_m, const int* seq_p0, const int* seq_qt0,
+                                                                  const int* seq_row0, const int* block_table, int pos_add, int rep,
+                                                                  int total_qt, int Hkv, int layer, int n_pages, int pps, int nsplit,
+                                                                  float* part_o, float* part_ml, bf16_t* __restrict__ out,
+                                                                  int out_ktiles) {
   constexpr int DS = D / 32, DT = D / 16;
-  const int lane = threadIdx.x & 63, g = lane >> 4, qc = lane & 15;
+  constexpr int KCH = 4 * DS, CH = KCH + 2 * DT;       // 1 KiB chunks of a page: K first, then V
+  constexpr int NL = EE_ATTN_WAVES - EE_ATTN_COMPUTE, PF = EE_ATTN_AHEAD;
+  constexpr int CPL = CH / NL;                         // chunks each loader wave fetches per page
+  static_assert(CH % NL == 0, "page chunks must divide among the loader waves");
+  __shared__ u32x4 lds[3][CH * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, qc = lane & 15;
   const int b = blockIdx.z, kvh = blockIdx.y % Hkv, sp = blockIdx.x;
-  const int qt = (blockIdx.y / Hkv) * 8 + (threadIdx.x >> 6);
   const int m = seq_m[b];
-  if (m == 0) return;
+  if (m == 0) return;                                  // whole workgroup
   const int nq = m * rep;
-  if (qt * 16 >= nq) return;
+  const int qt0 = (blockIdx.y / Hkv) * (EE_ATTN_COMPUTE * QPW);
+  if (qt0 * 16 >= nq) return;                          // whole workgroup
   const int p0 = seq_p0[b] + pos_add, kv_end = p0 + m;
   const int npages = (kv_end + EE_PAGE - 1) / EE_PAGE;
   const int per = (npages + nsplit - 1) / nsplit;
   const int pg0 = sp * per, pg1 = min(npages, pg0 + per);
-  const int gqt = seq_qt0[b] + qt;
-  const int qrow = qt * 16 + qc;
-  const int limit = qrow < nq ? p0 + qrow / rep : -1;
+  const int* bt = block_table + b * pps;
 
-  uint4 qf[DS];
+  const bool loader = wave >= EE_ATTN_COMPUTE;
+  const int lw = wave - EE_ATTN_COMPUTE;
+  int limit[QPW];
+  bool has[QPW];
+  u32x4 qf[QPW][DS];
+  float mrun[QPW];
+  f32x4 o[QPW][DT], lacc[QPW];   // lacc: running row sums (every element of a lane holds its column's sum)
 #pragma unroll
-  for (int s = 0; s < DS; ++s) qf[s] = Q[(((size_t)kvh * total_qt + gqt) * DS + s) * 64 + lane];
-
-  const float scale = 1.0f / sqrtf((float)D);
-  float mrun = -INFINITY, lrun = 0.f;
-  f32x4 o[DT];
+  for (int i = 0; i < QPW; ++i) {
+    const int qt = qt0 + wave * QPW + i;
+    has[i] = !loader && qt * 16 < nq;
+    const int qrow = qt * 16 + qc;
+    limit[i] = (has[i] && qrow < nq) ? p0 + qrow / rep : -1;
+    const int gqt = seq_qt0[b] + (has[i] ? qt : 0);
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  for (int pg = pg0; pg < pg1; ++pg) {
-    const int page = block_table[b * pps + pg];
-    const uint4* Kp = (const uint4*)(kv + kv_slab(layer, page, kvh, n_pages, Hkv, D)) + lane;
-    const uint4* Vp = Kp + (EE_PAGE * D / 8);
-    uint4 kf[4][DS];
+    for (int s = 0; s < DS; ++s) qf[i][s] = ((const u32x4*)Q)[(((size_t)kvh * total_qt + gqt) * DS + s) * 64 + lane];
+    mrun[i] = -INFINITY; lacc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int dt = 0; dt < DT; ++dt) o[i][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  // loader side: st[q] holds this wave's chunks (lw, lw + NL, ...) of the page q pages ahead (mod PF)
+  u32x4 st[PF][CPL];
+#define ATTN_FETCH(q_, pg_)                                                                                  \
+  do {                                                                                                       \
+    const u32x4* src_ = (const u32x4*)(kv + kv_slab(layer, bt[pg_], kvh, n_pages, Hkv, D)) + lw * 64 + lane; \
+    _Pragma("unroll") for (int j = 0; j < CPL; ++j) st[q_][j] = __builtin_nontemporal_load(src_ + j * NL * 64); \
+  } while (0)
+#define ATTN_DEPOSIT(buf_, q_)                                                                               \
+  do {                                                                                                       \
+    u32x4* dst_ = lds[buf_] + lw * 64 + lane;                                                                \
+    _Pragma("unroll") for (int j = 0; j < CPL; ++j) dst_[j * NL * 64] = st[q_][j];                           \
+  } while (0)
+  // Scores are kept in base-2 units (s * log2(e)/sqrt(D)) so that the exponential is a bare v_exp_f32;
+  // the row sums of the bf16-rounded weights come from one more MFMA column block (an all-ones A
+  // operand), not from the vector ALU.  One step handles the scores and softmax of page pg and the
+  // P.V product of page pg-1, whose weights the previous step left in registers: the two are
+  // independent, so the second's MFMAs run under the first's vector arithmetic.  TAIL steps (a page
+  // reaching into the block or past the end) mask scores and zero dead V.
+  const float sc2 = 1.4426950408889634f / sqrtf((float)D);
+  const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  u32x4 Pp0 = {0u, 0u, 0u, 0u}, Pp1 = {0u, 0u, 0u, 0u};   // weights of the previous page (B operand of P.V)
+  // LDS fragment reads are issued as whole groups ahead of the MFMAs that consume them, and scheduling
+  // barriers keep the compiler from sinking them back next to their uses (which would expose the LDS
+  // latency once per fragment).
+  auto pv_mfma = [&](auto tail_c, const u32x4 (&vf)[2 * DT], int ppg) __attribute__((always_inline)) {
+    constexpr bool TAIL = decltype(tail_c)::value;
+    const int pbase = ppg * EE_PAGE + 16 * g;
+    lacc[0] = mfma16(ones, Pp0, lacc[0]);
 #pragma unroll
-      for (int s = 0; s < DS; ++s) kf[t][s] = Kp[(t * DS + s) * 64];
-    uint4 vf[DT][2];
+    for (int ks = 0; ks < 2; ++ks) {     // the two MFMAs of a d-tile depend on each other: keep them 8 apart
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) { vf[dt][0] = Vp[(dt * 2) * 64]; vf[dt][1] = Vp[(dt * 2 + 1) * 64]; }
-
+      for (int dt = 0; dt < DT; ++dt) {
+        u32x4 v = vf[dt * 2 + ks];
+        if (TAIL) {   // zero V at dead positions: element j of the fragment is position pbase + 8*ks + j
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int pa = pbase + 8 * ks + 2 * j;
+            v[j] &= pa + 1 < kv_end ? 0xffffffffu : (pa < kv_end ? 0xffffu : 0u);
+          }
+        }
+        o[0][dt] = mfma16(v, ks == 0 ? Pp0 : Pp1, o[0][dt]);
+      }
+    }
+    lacc[0] = mfma16(ones, Pp1, lacc[0]);
+  };
+  auto step = [&](auto tail_c, auto prev_c, int slot, int pslot, int pg) __attribute__((always_inline)) {
+    constexpr bool TAIL = decltype(tail_c)::value, PREV = decltype(prev_c)::value;
+    const u32x4* L = lds[slot] + lane;
+    const u32x4* Lp = lds[pslot] + lane;
+    const int base = pg * EE_PAGE + 16 * g;          // this lane group holds positions base .. base+15
+    u32x4 kf[4 * DS];
+#pragma unroll
+    for (int c = 0; c < 4 * DS; ++c) kf[c] = L[c * 64];
+    __builtin_amdgcn_sched_barrier(0);
     f32x4 s4[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      s4[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < 4; ++t) s4[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int s = 0; s < DS; ++s) s4[t] = mfma16(kf[t][s], qf[s], s4[t]);
+    for (int s = 0; s < DS; ++s)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) s4[t] = mfma16(kf[t * DS + s], qf[0][s], s4[t]);
+    u32x4 vf[2 * DT];
+    if (PREV) {
+#pragma unroll
+      for (int c = 0; c < 2 * DT; ++c) vf[c] = Lp[(KCH + c) * 64];
     }
-    const int base = pg * EE_PAGE + 16 * g;          // this lane group holds positions base .. base+15
-    const bool tail = pg * EE_PAGE + EE_PAGE > p0;   // page reaches into the block (or past the end)
+    __builtin_amdgcn_sched_barrier(0);
+    if (PREV) pv_mfma(tail_c, vf, pg - 1);
+    // raw scores; the maximum is taken before scaling (the scale is positive) and the scale is folded
+    // into the exponent's argument as one fused multiply-add
     float tmax = -INFINITY;
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        float x = s4[t][v] * scale;
-        if (tail && base + 4 * t + v > limit) x = -INFINITY;
-        s4[t][v] = x;
-        tmax = fmaxf(tmax, x);
+        if (TAIL && base + 4 * t + v > limit[0]) s4[t][v] = -INFINITY;
+        tmax = fmaxf(tmax, s4[t][v]);
       }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float mnew = fmaxf(mrun, tmax);
-    const float msafe = mnew == -INFINITY ? 0.f : mnew;
-    const float alpha = __expf(mrun - msafe);
-    float psum = 0.f;
+    tmax *= sc2;
+    // the running maximum only has to be an upper bound shared by the four lane groups of a column:
+    // the cross-lane reduction and the rescaling run only when some score of the wave exceeds it
+    if (__builtin_amdgcn_ballot_w64(tmax > mrun[0]) != 0) {
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float mnew = fmaxf(mrun[0], tmax);
+      const float alpha = __builtin_amdgcn_exp2f(mrun[0] - (mnew == -INFINITY ? 0.f : mnew));
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) { o[0][dt][0] *= alpha; o[0][dt][1] *= alpha; o[0][dt][2] *= alpha; o[0][dt][3] *= alpha; }
+      lacc[0][0] *= alpha; lacc[0][1] *= alpha; lacc[0][2] *= alpha; lacc[0][3] *= alpha;
+      mrun[0] = mnew;
+    }
+    const float nm = mrun[0] == -INFINITY ? 0.f : -mrun[0];
     uint32_t pk[8];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      float e0 = __expf(s4[t][0] - msafe), e1 = __expf(s4[t][1] - msafe);
-      float e2 = __expf(s4[t][2] - msafe), e3 = __expf(s4[t][3] - msafe);
-      bf16_t b0 = f32_to_bf16(e0), b1 = f32_to_bf16(e1), b2 = f32_to_bf16(e2), b3 = f32_to_bf16(e3);
-      psum += (bf16_to_f32(b0) + bf16_to_f32(b1)) + (bf16_to_f32(b2) + bf16_to_f32(b3));
-      pk[2 * t] = (uint32_t)b0 | ((uint32_t)b1 << 16);
-      pk[2 * t + 1] = (uint32_t)b2 | ((uint32_t)b3 << 16);
+      pk[2 * t] = pack2(__builtin_amdgcn_exp2f(fmaf(s4[t][0], sc2, nm)), __builtin_amdgcn_exp2f(fmaf(s4[t][1], sc2, nm)));
+      pk[2 * t + 1] = pack2(__builtin_amdgcn_exp2f(fmaf(s4[t][2], sc2, nm)), __builtin_amdgcn_exp2f(fmaf(s4[t][3], sc2, nm)));
     }
-    lrun = lrun * alpha + psum;
-    mrun = mnew;
-    const uint4 P0 = make_uint4(pk[0], pk[1], pk[2], pk[3]);   // positions base+0..7  (pos-tiles 0, 1)
-    const uint4 P1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);   // positions base+8..15 (pos-tiles 2, 3)
-    if (tail) {
-      // zero V at dead positions: element j of vf[.][ks] is position base + 8*ks + j
+    Pp0 = u32x4{pk[0], pk[1], pk[2], pk[3]};   // positions base+0..7  (pos-tiles 0, 1)
+    Pp1 = u32x4{pk[4], pk[5], pk[6], pk[7]};   // positions base+8..15 (pos-tiles 2, 3)
+  };
+  auto pv_last = [&](auto tail_c, int pslot, int ppg) __attribute__((always_inline)) {
+    const u32x4* Lp = lds[pslot] + lane;
+    u32x4 vf[2 * DT];
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+    for (int c = 0; c < 2 * DT; ++c) vf[c] = Lp[(KCH + c) * 64];
+    pv_mfma(tail_c, vf, ppg);
+  };
+  // u = page offset mod 3 = ring slot; the first page of the split has no predecessor
+  auto compute_page = [&](int u, int pg) __attribute__((always_inline)) {
+    const int pslot = (u + 2) % 3;
+    const bool tail = pg * EE_PAGE + EE_PAGE > p0;   // page pg-1 of a non-tail page is never a tail page either
+    if (pg == pg0) {
+      if (tail) step(std::true_type{}, std::false_type{}, u, pslot, pg);
+      else step(std::false_type{}, std::false_type{}, u, pslot, pg);
+    } else {
+      if (tail) step(std::true_type{}, std::true_type{}, u, pslot, pg);
+      else step(std::false_type{}, std::true_type{}, u, pslot, pg);
+    }
+  };
+
+  // software pipeline over a ring of three LDS slots (slot = page offset mod 3): while the compute waves
+  // work on page p (scores) and p-1 (P.V), the loaders drop page p+1 into the third slot and request
+  // page p+1+PF; every wave passes one barrier per page
+  // (the two roles run separate loops with the same number of barriers, so neither carries the other's
+  // registers)
+  if (loader) {
+    // Loads return in order and the compiler places the waits from what it can prove about the order of
+    // issue, so the long-split path is kept free of branches from the first fetch to the end of its
+    // steady-state loop: one conditional fetch on the way in would make every deposit of the loop wait
+    // for all outstanding loads.
+    int pg = pg0;
+    if (pg0 + 2 * PF < pg1) {
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-          uint32_t w[4] = {vf[dt][ks].x, vf[dt][ks].y, vf[dt][ks].z, vf[dt][ks].w};
+      for (int q = 0; q < PF; ++q) ATTN_FETCH(q, pg0 + q);
+      ATTN_DEPOSIT(0, 0);
+      ATTN_FETCH(0, pg0 + PF);
+      __syncthreads();
+      for (; pg + 2 * PF < pg1; pg += PF) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            int pa = base + 8 * ks + 2 * j;
-            if (pa >= kv_end) w[j] = 0;
-            else if (pa + 1 >= kv_end) w[j] &= 0xffffu;
-          }
-          vf[dt][ks] = make_uint4(w[0], w[1], w[2], w[3]);
+        for (int u = 0; u < PF; ++u) {
+          ATTN_DEPOSIT((u + 1) % 3, (u + 1) % PF);
+          ATTN_FETCH((u + 1) % PF, pg + u + 1 + PF);
+          __syncthreads();
         }
-    }
+      }
+    } else {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      f32x4 acc = o[dt];
-      acc[0] *= alpha; acc[1] *= alpha; acc[2] *= alpha; acc[3] *= alpha;
-      acc = mfma16(vf[dt][0], P0, acc);
-      acc = mfma16(vf[dt][1], P1, acc);
-      o[dt] = acc;
+      for (int q = 0; q < PF; ++q)
+        if (pg0 + q < pg1) ATTN_FETCH(q, pg0 + q);
+      if (pg0 < pg1) ATTN_DEPOSIT(0, 0);
+      if (pg0 + PF < pg1) ATTN_FETCH(0, pg0 + PF);
+      __syncthreads();
+    }
+    for (; pg < pg1; pg += PF) {     // guarded tail (and short splits)
+#pragma unroll
+      for (int u = 0; u < PF; ++u) {
+        const int p = pg + u;
+        if (p + 1 < pg1) ATTN_DEPOSIT((u + 1) % 3, (u + 1) % PF);
+        if (p + 1 + PF < pg1) ATTN_FETCH((u + 1) % PF, p + 1 + PF);
+        __syncthreads();
+      }
+    }
+  } else {
+    __syncthreads();
+    for (int pg = pg0; pg < pg1; pg += PF) {
+#pragma unroll
+      for (int u = 0; u < PF; ++u) {
+        const int p = pg + u;
+        if (p < pg1 && has[0]) compute_page(u, p);
+        __syncthreads();
+      }
     }
   }
+#undef ATTN_FETCH
+#undef ATTN_DEPOSIT
+  if (loader) return;
+  static_assert(PF == 3 && QPW == 1, "the page loop is unrolled by the ring size");
+  if (has[0] && pg0 < pg1) {    // P.V of the split's last page (its slot is not written again)
+    const int last = pg1 - 1, u = (last - pg0) % 3;
+    if (last * EE_PAGE + EE_PAGE > p0) pv_last(std::true_type{}, u, last);
+    else pv_last(std::false_type{}, u, last);
+  }
 
-  lrun += __shfl_xor(lrun, 16, 64);
-  lrun += __shfl_xor(lrun, 32, 64);
-  const size_t slot = ((size_t)gqt * Hkv + kvh) * nsplit + sp;
-  if (g == 0) { part_ml[slot * 32 + qc * 2] = mrun; part_ml[slot * 32 + qc * 2 + 1] = lrun; }
-  float* po = part_o + (slot * 16 + qc) * D;
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt) *(float4*)(po + dt * 16 + 4 * g) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
+  for (int i = 0; i < QPW; ++i) {
+    if (!has[i]) continue;
+    const int qt = qt0 + wave * QPW + i, gqt = seq_qt0[b] + qt, qrow = qt * 16 + qc;
+    const float l = lacc[i][0];
+    if (nsplit == 1) {
+      if (qrow < nq) {
+        const float inv = 1.0f / l;
+        const int row = seq_row0[b] + qrow / rep, col0 = (kvh * rep + qrow % rep) * D + 4 * g;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          *(uint2*)(out + frag_offset(row, col0 + dt * 16, out_ktiles)) =
+              make_uint2(pack2(o[i][dt][0] * inv, o[i][dt][1] * inv), pack2(o[i][dt][2] * inv, o[i][dt][3] * inv));
+      }
+    } else {
+      // partial O of a split: [d-tile][lane] float4, the accumulator registers as they are
+      const size_t slot = ((size_t)gqt * Hkv + kvh) * nsplit + sp;
+      if (g == 0) *(float2*)(part_ml + slot * 32 + qc * 2) = make_float2(mrun[i], l);
+      float4* po = (float4*)part_o + slot * (DT * 64) + lane;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) po[dt * 64] = make_float4(o[i][dt][0], o[i][dt][1], o[i][dt][2], o[i][dt][3]);
+    }
+  }
 }
 
-// merge the KV splits and emit the bf16 attention output in fragment layout (O-projection operand):
-// first the normalised weight of every (query row, split) pair goes to LDS, then each thread sums
-// four output dims over the splits with coalesced float4 reads.
-#define EE_MAX_SPLITS 64
-__global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                           const int* qt_seq, const int* qt_local, const int* seq_m,
-                                                           const int* seq_row0, int rep, int Hkv, int D, int nsplit,
-                                                           bf16_t* out, int out_ktiles) {
-  __shared__ float w[16][EE_MAX_SPLITS];
+// merge the KV splits of one (q-tile, KV head) and emit the bf16 attention output in fragment layout
+// (O-projection operand).  Four waves, each taking a quarter of the head dimension; every lane owns the
+// same accumulator elements the split kernel's lanes did, so partials are read as coalesced float4.
+// Loads go out in batches so the merge costs a few L2 round trips, not one per split.
+template <int D>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                         const int* qt_seq, const int* qt_local, const int* seq_m,
+                                                         const int* seq_row0, int rep, int Hkv, int nsplit,
+                                                         bf16_t* __restrict__ out, int out_ktiles) {
+  constexpr int DT = D / 16, DW = DT / 4;    // d-tiles per wave
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, qc = lane & 15;
   const int gqt = blockIdx.x, kvh = blockIdx.y;
   const int b = qt_seq[gqt], qt = qt_local[gqt];
-  const int nq = seq_m[b] * rep;
+  const int nq = seq_m[b] * rep, qrow = qt * 16 + qc;
   const size_t slot0 = ((size_t)gqt * Hkv + kvh) * nsplit;
-  {
-    // 16 threads per query row: each takes splits s = t, t+16, ...
-    const int qc = threadIdx.x >> 4, t = threadIdx.x & 15;
-    float mloc = -INFINITY;
-    for (int s = t; s < nsplit; s += 16) mloc = fmaxf(mloc, part_ml[(slot0 + s) * 32 + qc * 2]);
-    for (int sh = 1; sh < 16; sh <<= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, sh, 64));
-    float den = 0.f;
-    for (int s = t; s < nsplit; s += 16) {
-      float ms = part_ml[(slot0 + s) * 32 + qc * 2];
-      float e = ms == -INFINITY ? 0.f : __expf(ms - mloc);
-      w[qc][s] = e;
-      den += e * part_ml[(slot0 + s) * 32 + qc * 2 + 1];
-    }
-    for (int sh = 1; sh < 16; sh <<= 1) den += __shfl_xor(den, sh, 64);
-    const float inv = 1.0f / den;
-    for (int s = t; s < nsplit; s += 16) w[qc][s] *= inv;
+  const float2* ml = (const float2*)(part_ml + slot0 * 32) + qc;
+  float mall = -INFINITY, den = 0.f;
+  for (int s0 = 0; s0 < nsplit; s0 += 8) {
+    float2 t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = s0 + i < nsplit ? ml[(s0 + i) * 16] : make_float2(-INFINITY, 0.f);
+    float bm = mall;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bm = fmaxf(bm, t[i].x);
+    const float safe = bm == -INFINITY ? 0.f : bm;
+    den *= __builtin_amdgcn_exp2f(mall - safe);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) den += __builtin_amdgcn_exp2f(t[i].x - safe) * t[i].y;
+    mall = bm;
   }
-  __syncthreads();
-  const int d4n = D >> 2;
-  for (int i = threadIdx.x; i < 16 * d4n; i += blockDim.x) {
-    const int qc = i / d4n, d = (i % d4n) * 4;
-    const int qrow = qt * 16 + qc;
-    if (qrow >= nq) continue;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < nsplit; ++s) {
-      const float ws = w[qc][s];
-      const float4 o = *(const float4*)(part_o + ((slot0 + s) * 16 + qc) * D + d);
-      acc.x += ws * o.x; acc.y += ws * o.y; acc.z += ws * o.z; acc.w += ws * o.w;
+  const float msafe = mall == -INFINITY ? 0.f : mall;
+  const float inv = 1.0f / den;
+  f32x4 acc[DW];
+#pragma unroll
+  for (int j = 0; j < DW; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const f32x4* pi = (const f32x4*)part_o + slot0 * (DT * 64) + (size_t)wave * DW * 64 + lane;
+  for (int s0 = 0; s0 < nsplit; s0 += 8) {
+    float2 t[8];
+    f32x4 ov[8][DW];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int sl = min(s0 + i, nsplit - 1);
+      t[i] = ml[sl * 16];
+#pragma unroll
+      for (int j = 0; j < DW; ++j) ov[i][j] = __builtin_nontemporal_load(pi + ((size_t)sl * DT + j) * 64);
     }
-    const int row = seq_row0[b] + qrow / rep, col = (kvh * rep + qrow % rep) * D + d;
-    *(uint2*)(out + frag_offset(row, col, out_ktiles)) = make_uint2(pack2(acc.x, acc.y), pack2(acc.z, acc.w));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float w = s0 + i < nsplit ? __builtin_amdgcn_exp2f(t[i].x - msafe) * inv : 0.f;
+#pragma unroll
+      for (int j = 0; j < DW; ++j) { acc[j][0] += w * ov[i][j][0]; acc[j][1] += w * ov[i][j][1]; acc[j][2] += w * ov[i][j][2]; acc[j][3] += w * ov[i][j][3]; }
+    }
+  }
+  if (qrow < nq) {
+    const int row = seq_row0[b] + qrow / rep, col0 = (kvh * rep + qrow % rep) * D + wave * DW * 16 + 4 * g;
+#pragma unroll
+    for (int j = 0; j < DW; ++j)
+      *(uint2*)(out + frag_offset(row, col0 + j * 16, out_ktiles)) = make_uint2(pack2(acc[j][0], acc[j][1]), pack2(acc[j][2], acc[j][3]));
+  }
+}
+
+// number of KV splits: about two workgroups per compute unit when the context allows, at least four
+// pages per split (the software pipeline's depth)
+static int attn_default_splits(int B, int Hkv, int qt_groups, int max_pages, int max_splits) {
+  int nsplit = ceil_div(512, max(1, B * Hkv * qt_groups));
+  return max(1, min(nsplit, min(ceil_div(max_pages, 4), min(max_splits, EE_MAX_SPLITS))));
+}
+
+template <int D, int QPW>
+static void launch_attn(hipStream_t st, dim3 grid, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int rep,
+                        int total_qt, int Hkv, int layer, int n_pages, int pps, int nsplit, const AttnScratch& scr, bf16_t* out,
+                        int out_ktiles) {
+  hipLaunchKernelGGL((attn_kernel<D, QPW>), grid, dim3(64 * EE_ATTN_WAVES), 0, st, (const uint4*)Q, kv, meta.seq_m, meta.seq_p0,
+                     meta.seq_qt0, meta.seq_row0, meta.block_table, pos_add, rep, total_qt, Hkv, layer, n_pages, pps, nsplit,
+                     scr.part_o, scr.part_ml, out, out_ktiles);
+}
+
+void bf16_attention_cfg(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,
+                        int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
+                        const AttnScratch& scr, bf16_t* out, int out_ktiles, int nsplit) {
+  const int rep = Hq / Hkv;
+  const int max_qt = ceil_div(max_m * rep, 16);
+  const int qt_groups = ceil_div(max_qt, EE_ATTN_COMPUTE);
+  if (nsplit <= 0) nsplit = attn_default_splits(B, Hkv, qt_groups, ceil_div(max_kv_end, EE_PAGE), scr.max_splits);
+  dim3 grid(nsplit, Hkv * qt_groups, B);
+  if (D == 128) launch_attn<128, 1>(st, grid, Q, kv, meta, pos_add, rep, total_qt, Hkv, layer, n_pages, pages_per_seq, nsplit, scr, out, out_ktiles);
+  else launch_attn<64, 1>(st, grid, Q, kv, meta, pos_add, rep, total_qt, Hkv, layer, n_pages, pages_per_seq, nsplit, scr, out, out_ktiles);
+  if (nsplit > 1) {
+    if (D == 128)
+      hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(total_qt, Hkv), dim3(256), 0, st, scr.part_o, scr.part_ml, meta.qt_seq,
+                         meta.qt_local, meta.seq_m, meta.seq_row0, rep, Hkv, nsplit, out, out_ktiles);
+    else
+      hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(total_qt, Hkv), dim3(256), 0, st, scr.part_o, scr.part_ml, meta.qt_seq,
+                         meta.qt_local, meta.seq_m, meta.seq_row0, rep, Hkv, nsplit, out, out_ktiles);
   }
 }
 
 void bf16_attention(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,
                     int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
                     const AttnScratch& scr, bf16_t* out, int out_ktiles) {
-  const int rep = Hq / Hkv;
-  const int max_qt = ceil_div(max_m * rep, 16);
-  const int qt_groups = ceil_div(max_qt, 8), waves = min(max_qt, 8);
-  const int max_pages = ceil_div(max_kv_end, EE_PAGE);
-  // enough (split, head, q-tile) waves to cover the chip, but at least two pages per wave when possible
-  int nsplit = ceil_div(768, max(1, B * Hkv * max_qt));
-  nsplit = max(1, min(nsplit, min(ceil_div(max_pages, 2), min(scr.max_splits, EE_MAX_SPLITS))));
-  dim3 grid(nsplit, Hkv * qt_groups, B), blk(64 * waves);
-  if (D == 128)
-    hipLaunchKernelGGL((attn_split_kernel<128>), grid, blk, 0, st, (const uint4*)Q, kv, meta.seq_m, meta.seq_p0, meta.seq_qt0,
-                       meta.block_table, pos_add, rep, total_qt, Hkv, layer, n_pages, pages_per_seq, nsplit, scr.part_o, scr.part_ml);
-  else
-    hipLaunchKernelGGL((attn_split_kernel<64>), grid, blk, 0, st, (const uint4*)Q, kv, meta.seq_m, meta.seq_p0, meta.seq_qt0,
-                       meta.block_table, pos_add, rep, total_qt, Hkv, layer, n_pages, pages_per_seq, nsplit, scr.part_o, scr.part_ml);
-  hipLaunchKernelGGL(attn_combine_kernel, dim3(total_qt, Hkv), dim3(256), 0, st, scr.part_o, scr.part_ml, meta.qt_seq,
-                     meta.qt_local, meta.seq_m, meta.seq_row0, rep, Hkv, D, nsplit, out, out_ktiles);
+  bf16_attention_cfg(st, Q, kv, meta, pos_add, B, max_m, total_qt, max_kv_end, Hq, Hkv, D, layer, n_pages, pages_per_seq, scr, out,
+                     out_ktiles, 0);
 }

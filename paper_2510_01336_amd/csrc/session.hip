@@ -34,7 +34,7 @@ struct ee_session {
   void *XN = nullptr, *Qb = nullptr, *AO = nullptr, *H = nullptr;
   float2* cs = nullptr;
   int *vtok = nullptr, *tok_next = nullptr, *draft_dev = nullptr, *out_dev = nullptr, *page_scratch = nullptr;
-  float *part_o = nullptr, *part_ml = nullptr, *pmax = nullptr;
+  float *part_o = nullptr, *part_ml = nullptr, *pmax = nullptr, *ssq = nullptr;
   int* pidx = nullptr;
   int max_splits = 64;
   // host side
@@ -95,7 +95,7 @@ static size_t carve(ee_session* s, char* base) {
   s->X = cv.take<float>((size_t)s->maxM * d);
   s->XN = bf ? (void*)cv.take<bf16_t>((size_t)Mp * ceil_div(d, 32) * 32) : (void*)cv.take<float>((size_t)s->maxM * d);
   const int nqkv = (Hq + 2 * Hkv) * D, nqkv_p = bf ? ceil_div(nqkv, 16) * 16 : nqkv;
-  s->QKV = cv.take<float>((size_t)s->maxM * nqkv_p);
+  s->QKV = bf ? nullptr : cv.take<float>((size_t)s->maxM * nqkv_p);
   s->Qb = bf ? (void*)cv.take<bf16_t>((size_t)Hkv * s->maxQT * 16 * D) : (void*)cv.take<float>((size_t)s->maxM * Hq * D);
   s->AO = bf ? (void*)cv.take<bf16_t>((size_t)Mp * ceil_div(Hq * D, 32) * 32) : (void*)cv.take<float>((size_t)s->maxM * Hq * D);
   s->GU = bf ? nullptr : cv.take<float>((size_t)s->maxM * 2 * m->Fp);
@@ -114,6 +114,7 @@ static size_t carve(ee_session* s, char* base) {
     s->part_ml = cv.take<float>((size_t)s->maxQT * Hkv * s->max_splits * 32);
     s->pmax = cv.take<float>((size_t)m->head.ntiles() * Mp);
     s->pidx = cv.take<int>((size_t)m->head.ntiles() * Mp);
+    s->ssq = cv.take<float>((size_t)ceil_div(d, 16) * Mp);            // deferred-RMSNorm partials [d/16][Mp]
   }
   s->slot[0].d = cv.take<int>(s->meta_ints);
   s->slot[1].d = cv.take<int>(s->meta_ints);
@@ -313,25 +314,35 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
     const float* g1 = (const float*)(m->base + L.g1);
     const float* g2 = (const float*)(m->base + L.g2);
     if (m->bf16) {
+      // five launches per layer; RMSNorm is deferred into the projections (see NormIn / NormOut)
       const bf16_t* Wqkv = (const bf16_t*)(m->base + L.qkv.off);
       const bf16_t* Wo = (const bf16_t*)(m->base + L.o.off);
       const bf16_t* Wgu = (const bf16_t*)(m->base + L.gu.off);
       const bf16_t* Wd = (const bf16_t*)(m->base + L.down.off);
+      const int Mp = s->Mp;
+      NormIn nin;         // operand left by the previous EPI_ADD launch
+      nin.ssq = s->ssq; nin.n_part = d / 16; nin.stride = Mp; nin.inv_d = 1.0f / (float)d; nin.eps = c.rms_eps;
+      NormOut nout;
+      nout.xn = (bf16_t*)s->XN; nout.ktiles = ceil_div(d, 32); nout.ssq = s->ssq; nout.stride = Mp;
       GemmOut o;
-      KF(KF_NORM, bf16_rmsnorm(st, s->X, g1, c.rms_eps, (bf16_t*)s->XN, L.qkv.ktiles(), M, d));
-      o = GemmOut(); o.Y = s->QKV; o.ldy = L.qkv.Np;
-      KF(KF_GEMM_QKV, bf16_gemm(st, EPI_STORE, Wqkv, L.qkv.ntiles(), L.qkv.ktiles(), (const bf16_t*)s->XN, M, L.qkv.N, o));
-      KF(KF_ROPE, bf16_rope_append(st, s->QKV, L.qkv.Np, s->cs, mt, pos_add, M, Hq, Hkv, D, l, s->n_pages, s->pps, p.total_qt,
-                                   (bf16_t*)s->Qb, (bf16_t*)s->kv));
+      if (l == l0) KF(KF_NORM, bf16_rmsnorm(st, s->X, g1, c.rms_eps, (bf16_t*)s->XN, L.qkv.ktiles(), M, d));
+      else o.nin = nin;
+      RopeOut& R = o.rope;
+      R.cs = s->cs; R.row_seq = mt.row_seq; R.row_pos = mt.row_pos; R.seq_row0 = mt.seq_row0; R.seq_qt0 = mt.seq_qt0;
+      R.block_table = mt.block_table; R.pos_add = pos_add; R.Hq = Hq; R.Hkv = Hkv; R.D = D; R.layer = l;
+      R.n_pages = s->n_pages; R.pps = s->pps; R.total_qt = p.total_qt; R.Q = (bf16_t*)s->Qb; R.kv = (bf16_t*)s->kv;
+      KF(KF_GEMM_QKV, bf16_gemm(st, EPI_ROPE, Wqkv, L.qkv.ntiles(), L.qkv.ktiles(), (const bf16_t*)s->XN, M, L.qkv.N, o));
       AttnScratch scr{s->part_o, s->part_ml, s->max_splits};
       KF(KF_ATTN, bf16_attention(st, (const bf16_t*)s->Qb, (const bf16_t*)s->kv, mt, pos_add, s->B, p.max_m, p.total_qt,
                                  p.max_kv_end + pos_add, Hq, Hkv, D, l, s->n_pages, s->pps, scr, (bf16_t*)s->AO, L.o.ktiles()));
-      o = GemmOut(); o.Y = s->X; o.ldy = d;
+      o = GemmOut(); o.Y = s->X; o.ldy = d; o.nout = nout; o.nout.g = g2;
       KF(KF_GEMM_O, bf16_gemm(st, EPI_ADD, Wo, L.o.ntiles(), L.o.ktiles(), (const bf16_t*)s->AO, M, L.o.N, o));
-      KF(KF_NORM, bf16_rmsnorm(st, s->X, g2, c.rms_eps, (bf16_t*)s->XN, L.gu.ktiles(), M, d));
-      o = GemmOut(); o.H = (bf16_t*)s->H; o.h_ktiles = L.down.ktiles();
+      o = GemmOut(); o.H = (bf16_t*)s->H; o.h_ktiles = L.down.ktiles(); o.nin = nin;
       KF(KF_GEMM_GU, bf16_gemm(st, EPI_SWIGLU, Wgu, L.gu.ntiles(), L.gu.ktiles(), (const bf16_t*)s->XN, M, L.gu.N, o));
-      o = GemmOut(); o.Y = s->X; o.ldy = d;
+      // the down projection leaves the operand of whatever reads the stream next: the next layer's QKV
+      // projection, or the shared exit head behind the last layer of the pass
+      o = GemmOut(); o.Y = s->X; o.ldy = d; o.nout = nout;
+      o.nout.g = l + 1 < l1 ? (const float*)(m->base + m->L[l + 1].g1) : (const float*)(m->base + m->gfinal);
       KF(KF_GEMM_DOWN, bf16_gemm(st, EPI_ADD, Wd, L.down.ntiles(), L.down.ktiles(), (const bf16_t*)s->H, M, L.down.N, o));
     } else {
       const float* Wqkv = (const float*)(m->base + L.qkv.off);
@@ -359,9 +370,10 @@ static void exit_head(ee_session* s, int M) {
   hipStream_t st = s->st;
   const float* gf = (const float*)(m->base + m->gfinal);
   if (m->bf16) {
-    KF(KF_NORM, bf16_rmsnorm(st, s->X, gf, c.rms_eps, (bf16_t*)s->XN, m->head.ktiles(), M, c.d_model));
+    // the last down projection of the pass left XN = bf16(x * gfinal) and the partial sums of squares
     GemmOut o;
     const int Mp = s->Mp;
+    o.nin.ssq = s->ssq; o.nin.n_part = c.d_model / 16; o.nin.stride = Mp; o.nin.inv_d = 1.0f / (float)c.d_model; o.nin.eps = c.rms_eps;
     o.pmax = s->pmax; o.pidx = s->pidx; o.pstride = Mp;
     if (s->debug_logits) { o.Y = s->LOGITS; o.ldy = c.vocab; }
     KF(KF_GEMM_HEAD, bf16_gemm(st, EPI_ARGMAX, (const bf16_t*)(m->base + m->head.off), m->head.ntiles(), m->head.ktiles(),

@@ -83,24 +83,25 @@ int ee_tensor_map(const ee_model* m, int tid, int layer, TensorMap* t) {
   const ee_config& c = m->cfg;
   const int d = c.d_model, D = c.head_dim;
   if (tid >= EE_T_G1 && (layer < 0 || layer >= c.n_layers)) { ee_set_error("layer out of range"); return EE_ERR_ARG; }
-  t->row_off = 0; t->interleave = 0; t->Kp = 0;
+  t->row_off = 0; t->interleave = 0; t->Kp = 0; t->hd = D;
   switch (tid) {
-    case EE_T_EMB: *t = {2, c.vocab, d, m->emb, 0, 0, d}; return EE_OK;
-    case EE_T_GFINAL: *t = {1, d, 1, m->gfinal, 0, 0, 0}; return EE_OK;
-    case EE_T_HEAD: *t = {0, c.vocab, d, m->head.off, 0, 0, m->head.Kp}; return EE_OK;
+    case EE_T_EMB: *t = {2, c.vocab, d, m->emb, 0, 0, d, D}; return EE_OK;
+    case EE_T_GFINAL: *t = {1, d, 1, m->gfinal, 0, 0, 0, D}; return EE_OK;
+    case EE_T_HEAD: *t = {0, c.vocab, d, m->head.off, 0, 0, m->head.Kp, D}; return EE_OK;
     default: break;
   }
   const LayerLoc& L = m->L[layer];
+  const int qi = m->bf16 ? 3 : 0;   // bf16 models keep the rotary halves of every head in adjacent tiles
   switch (tid) {
-    case EE_T_G1: *t = {1, d, 1, L.g1, 0, 0, 0}; break;
-    case EE_T_G2: *t = {1, d, 1, L.g2, 0, 0, 0}; break;
-    case EE_T_WQ: *t = {0, c.n_q_heads * D, d, L.qkv.off, 0, 0, L.qkv.Kp}; break;
-    case EE_T_WK: *t = {0, c.n_kv_heads * D, d, L.qkv.off, c.n_q_heads * D, 0, L.qkv.Kp}; break;
-    case EE_T_WV: *t = {0, c.n_kv_heads * D, d, L.qkv.off, (c.n_q_heads + c.n_kv_heads) * D, 0, L.qkv.Kp}; break;
-    case EE_T_WO: *t = {0, d, c.n_q_heads * D, L.o.off, 0, 0, L.o.Kp}; break;
-    case EE_T_WGATE: *t = {0, c.d_ffn, d, L.gu.off, 0, 1, L.gu.Kp}; break;
-    case EE_T_WUP: *t = {0, c.d_ffn, d, L.gu.off, 0, 2, L.gu.Kp}; break;
-    case EE_T_WDOWN: *t = {0, d, c.d_ffn, L.down.off, 0, 0, L.down.Kp}; break;
+    case EE_T_G1: *t = {1, d, 1, L.g1, 0, 0, 0, D}; break;
+    case EE_T_G2: *t = {1, d, 1, L.g2, 0, 0, 0, D}; break;
+    case EE_T_WQ: *t = {0, c.n_q_heads * D, d, L.qkv.off, 0, qi, L.qkv.Kp, D}; break;
+    case EE_T_WK: *t = {0, c.n_kv_heads * D, d, L.qkv.off, c.n_q_heads * D, qi, L.qkv.Kp, D}; break;
+    case EE_T_WV: *t = {0, c.n_kv_heads * D, d, L.qkv.off, (c.n_q_heads + c.n_kv_heads) * D, qi, L.qkv.Kp, D}; break;
+    case EE_T_WO: *t = {0, d, c.n_q_heads * D, L.o.off, 0, 0, L.o.Kp, D}; break;
+    case EE_T_WGATE: *t = {0, c.d_ffn, d, L.gu.off, 0, 1, L.gu.Kp, D}; break;
+    case EE_T_WUP: *t = {0, c.d_ffn, d, L.gu.off, 0, 2, L.gu.Kp, D}; break;
+    case EE_T_WDOWN: *t = {0, d, c.d_ffn, L.down.off, 0, 0, L.down.Kp, D}; break;
     default: ee_set_error("unknown tensor id %d", tid); return EE_ERR_ARG;
   }
   return EE_OK;
@@ -116,7 +117,7 @@ __device__ inline void store_elem(char* base, const TensorMap& t, int bf16, int 
     if (bf16) ((bf16_t*)(base + t.off))[i] = f32_to_bf16(v); else ((float*)(base + t.off))[i] = v;
     return;
   }
-  int pr = phys_row(r, t.row_off, t.interleave);
+  int pr = phys_row(r, t.row_off, t.interleave, t.hd);
   if (bf16) ((bf16_t*)(base + t.off))[frag_offset(pr, c, t.Kp >> 5)] = f32_to_bf16(v);
   else ((float*)(base + t.off))[(size_t)pr * t.Kp + c] = v;
 }
@@ -126,7 +127,7 @@ __device__ inline float load_elem(const char* base, const TensorMap& t, int bf16
     size_t i = (size_t)r * t.cols + c;
     return bf16 ? bf16_to_f32(((const bf16_t*)(base + t.off))[i]) : ((const float*)(base + t.off))[i];
   }
-  int pr = phys_row(r, t.row_off, t.interleave);
+  int pr = phys_row(r, t.row_off, t.interleave, t.hd);
   if (bf16) return bf16_to_f32(((const bf16_t*)(base + t.off))[frag_offset(pr, c, t.Kp >> 5)]);
   return ((const float*)(base + t.off))[(size_t)pr * t.Kp + c];
 }
