@@ -31,9 +31,11 @@ import synth  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 MODEL_SEED = 20251001
 
-# HBM traffic of one gate/up GEMM launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE,
-# calibrated against a copy kernel); see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# HBM traffic of one gate/up GEMM launch (8b_b1_ctx2048_k8) measured with two rocprofv3 --pmc runs
+# (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the calibration copy
+# below; the figures and the commands are in profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = 236_528_000
+CALIBRATION_COPY_BYTES = 1 << 30
 
 WORKLOADS = {
     # name: (config factory, batch, ctx, k, agreement p)
@@ -135,6 +137,20 @@ def cpu_baseline(w):
                       f"({t_step:.1f} s); float64 numpy"}
 
 
+def calibration_copy(stream_ptr):
+    """One plain device-to-device copy of known size (reads and writes CALIBRATION_COPY_BYTES each): the
+    reference dispatch for scaling hardware byte counters when this script runs under rocprofv3 --pmc."""
+    import torch
+    import paper_2510_01336_amd as hs
+    src = torch.full((CALIBRATION_COPY_BYTES,), 7, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    hs.ee_debug_stream_copy(dst.data_ptr(), src.data_ptr(), CALIBRATION_COPY_BYTES, stream_ptr)
+    torch.cuda.synchronize()
+    assert int(dst[12345]) == 7
+    del src, dst
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -152,6 +168,7 @@ def main():
     torch.cuda.set_device(0)
     w = build_workload(args.workload)
     cfg, sess = w["cfg"], w["sess"]
+    calibration_copy(w["model"].stream)
 
     for _ in range(args.warmup):
         a, f = one_step(w)

@@ -174,6 +174,11 @@ int ee_debug_time_kernels(ee_session* s, int on);
 int ee_debug_kernel_times(ee_session* s, int32_t* n_families, const char** names /*[16]*/,
                           float* ms /*[16]*/, int32_t* launches /*[16]*/);
 
+/* Plain device-to-device streaming copy on `stream` (pointers and size multiples of 16 bytes; not
+ * synchronised).  A kernel of exactly known traffic -- `bytes` read, `bytes` written -- used to
+ * calibrate hardware byte counters when the HBM traffic of the other kernels is measured. */
+int ee_debug_stream_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
+
 const char* ee_last_error(void);
 
 #ifdef __cplusplus

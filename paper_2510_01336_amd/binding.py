@@ -17,7 +17,7 @@ __all__ = [
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv",
-    "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_last_error",
+    "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
     "EE_F32", "EE_BF16", "TENSOR_IDS", "EXPORTED_SYMBOLS",
 ]
 
@@ -30,7 +30,7 @@ EXPORTED_SYMBOLS = [
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv",
-    "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_last_error",
+    "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
 ]
 
 
@@ -54,7 +54,7 @@ def lib_path() -> str:
 def _load():
     path = lib_path()
     if not os.path.exists(path):
-        raise ImportError(f"{path} is missing: build it with `python -m paper_2510_01336_amd.build` "
+        raise ImportError(f"{path} is missing: build it with `python paper_2510_01336_amd/build.py` "
                           "(there is no fallback path)")
     # torch ships its own HIP runtime; it must be in the process before libhispec.so is mapped so
     # that both resolve the one libamdhip64.so.7 (two runtimes in a process do not share a device)
@@ -86,6 +86,7 @@ def _load():
         "ee_debug_poison_dead_kv": (C.c_int, [vp, C.c_int]),
         "ee_debug_time_kernels": (C.c_int, [vp, C.c_int]),
         "ee_debug_kernel_times": (C.c_int, [vp, i32p, C.POINTER(C.c_char_p), f32p, i32p]),
+        "ee_debug_stream_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
         "ee_last_error": (C.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -288,6 +289,10 @@ def ee_debug_kernel_times(session: int) -> dict:
     ms, cnt = np.zeros(16, np.float32), np.zeros(16, np.int32)
     _chk(lib.ee_debug_kernel_times(session, C.byref(n), names, _p_f32(ms), _p_i32(cnt)))
     return {names[i].decode(): (float(ms[i]), int(cnt[i])) for i in range(n.value)}
+
+
+def ee_debug_stream_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream_ptr: int) -> None:
+    _chk(lib.ee_debug_stream_copy(dst_ptr, src_ptr, nbytes, stream_ptr))
 
 
 # ---- arena owners ---------------------------------------------------------------------------------

@@ -2,6 +2,7 @@
 // The fp32 kernels favour clarity over speed: EE_F32 exists for the small reference-precision
 // configuration; the bandwidth-critical work is in kernels_bf16.hip.
 #include "kernels.h"
+#include <algorithm>
 #include <cmath>
 
 // ---------------------------------------------------------------------------------------------
@@ -119,6 +120,25 @@ void k_read_kv(hipStream_t st, bool bf16, const void* kv, const int* pages, int 
   if (n <= 0) return;
   hipLaunchKernelGGL(read_kv_kernel, dim3(ceil_div(n * n_kv * D, 256)), dim3(256), 0, st, kv, (int)bf16, pages, layer, pos0, n,
                      n_pages, n_kv, D, k_out, v_out);
+}
+
+// Plain streaming copy (16 bytes per lane, grid-stride): the known-size kernel against which hardware
+// byte counters are calibrated when HBM traffic of the other kernels is measured.
+__global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+extern "C" int ee_debug_stream_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream) {
+  if (!dst_dev || !src_dev || (bytes & 15) || ((uintptr_t)dst_dev & 15) || ((uintptr_t)src_dev & 15)) {
+    ee_set_error("stream copy needs non-null 16-byte aligned pointers and a size that is a multiple of 16");
+    return EE_ERR_ARG;
+  }
+  if (!bytes) return EE_OK;
+  const size_t n16 = bytes / 16;
+  const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+  hipLaunchKernelGGL(stream_copy_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)dst_dev, (const uint4*)src_dev, n16);
+  HIP_TRY(hipGetLastError());
+  return EE_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
