@@ -132,13 +132,59 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) wp[nb] = (const u32x4*)W + (size_t)(task * NB + nb) * ktiles * 64 + lane;
   const u32x4* ap = (const u32x4*)A + (size_t)(row0 >> 4) * ktiles * 64 + lane;
-  Frags<MT, NB, U> cur, nxt;
+  Frags<MT, NB, U> cur;
+
+  // Epilogue operands that do not depend on the product (residual rows and gains; rotary table and page
+  // lookups) are requested by the epilogue wave now, so their latency is not paid after the reduction.
+  const int g = lane >> 4, mc = lane & 15;
+  const bool epi_wave = active && kpart == 0;
+  float4 res[MT], gnext = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 rc01[MT], rc23[MT];
+  int r_a[MT], r_b[MT];      // EPI_ROPE: Q heads: (global q-tile, row in tile); K/V heads: (page, position in page)
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    res[mt] = make_float4(0.f, 0.f, 0.f, 0.f);
+    rc01[mt] = rc23[mt] = make_float4(1.f, 0.f, 1.f, 0.f);
+    r_a[mt] = r_b[mt] = 0;
+  }
+  if (EPI == EPI_ADD && epi_wave) {
+    const int n = task * 16 + 4 * g;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 16 + mc;
+      if (m < M) res[mt] = *(const float4*)(out.Y + (size_t)(row0 + m) * out.ldy + n);
+    }
+    if (out.nout.xn) gnext = *(const float4*)(out.nout.g + n);
+  }
+  if (EPI == EPI_ROPE && epi_wave) {
+    const RopeOut& R = out.rope;
+    const int half = R.D >> 1, tph = R.D >> 5;
+    const int h = task / tph, f = (task % tph) * 16 + 4 * g;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 16 + mc, row = row0 + m;
+      if (m < M) {
+        const int sq = R.row_seq[row];
+        if (h < R.Hq + R.Hkv) {
+          const float4* c4 = (const float4*)(R.cs + (size_t)row * half + f);
+          rc01[mt] = c4[0]; rc23[mt] = c4[1];
+        }
+        if (h < R.Hq) {
+          const int q = (row - R.seq_row0[sq]) * (R.Hq / R.Hkv) + h % (R.Hq / R.Hkv);
+          r_a[mt] = R.seq_qt0[sq] + (q >> 4); r_b[mt] = q & 15;
+        } else {
+          const int pos = R.row_pos[row] + R.pos_add;
+          r_a[mt] = R.block_table[sq * R.pps + pos / EE_PAGE]; r_b[mt] = pos % EE_PAGE;
+        }
+      }
+    }
+  }
 
   // Deferred RMSNorm: sum of squares of row mt*16 + lane%16 from the producer's per-tile partials, in a
   // fixed order.  The ksplit waves of a task each sum a contiguous share of the partials (lane group g
   // takes every 4th); the first batch is requested before the first weight fragments and added once
   // those are in flight, so its (L2) latency hides under the first HBM fetch.
-  constexpr int SB = 16;   // partials per lane, m-tile and batch
+  constexpr int SB = 64 / MT;   // partials per lane, m-tile and batch: d_model 4096 is one batch at 16 rows
   const bool normed = out.nin.ssq != nullptr && active;
   float ssl[MT];
 #pragma unroll
@@ -175,16 +221,19 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
   }
 
   if (stream) {
-    for (int kt = kt0; kt < kt1; kt += U) {
-      const bool more = kt + U < kt1;
-      if (more) load_frags<MT, NB, U>(nxt, wp, ap, ktiles, kt + U, kt1);
+    {
+      Frags<MT, NB, U> nxt;
+      for (int kt = kt0; kt < kt1; kt += U) {
+        const bool more = kt + U < kt1;
+        if (more) load_frags<MT, NB, U>(nxt, wp, ap, ktiles, kt + U, kt1);
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+          for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = mfma16(cur.w[nb][u], cur.x[mt][u], acc[nb][mt]);
-      if (more) cur = nxt;
+            for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = mfma16(cur.w[nb][u], cur.x[mt][u], acc[nb][mt]);
+        if (more) cur = nxt;
+      }
     }
   }
 
@@ -213,7 +262,6 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
         acc[nb][mt][0] += t.x; acc[nb][mt][1] += t.y; acc[nb][mt][2] += t.z; acc[nb][mt][3] += t.w;
       }
 
-  const int g = lane >> 4, mc = lane & 15;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int m = mt * 16 + mc, row = row0 + m;
@@ -227,14 +275,10 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
     if (EPI == EPI_ADD) {
       const int n = task * 16 + 4 * g;
       float4 r = make_float4(acc[0][mt][0] * sc, acc[0][mt][1] * sc, acc[0][mt][2] * sc, acc[0][mt][3] * sc);
-      if (ok) {
-        float4* p = (float4*)(out.Y + (size_t)row * out.ldy + n);
-        const float4 o = *p;
-        r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w;
-        *p = r;
-      }
+      r.x += res[mt].x; r.y += res[mt].y; r.z += res[mt].z; r.w += res[mt].w;
+      if (ok) *(float4*)(out.Y + (size_t)row * out.ldy + n) = r;
       if (out.nout.xn) {
-        const float4 gn = *(const float4*)(out.nout.g + n);
+        const float4 gn = gnext;
         if (ok) *(uint2*)(out.nout.xn + frag_offset(row, n, out.nout.ktiles)) = make_uint2(pack2(r.x * gn.x, r.y * gn.y), pack2(r.z * gn.z, r.w * gn.w));
         float ss = ok ? (r.x * r.x + r.y * r.y) + (r.z * r.z + r.w * r.w) : 0.f;
         ss += __shfl_xor(ss, 16, 64);
@@ -261,11 +305,8 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
         float lo[4], hi[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) { lo[v] = acc[0][mt][v] * sc; hi[v] = acc[NB - 1][mt][v] * sc; }
-        const int sq = R.row_seq[row];
         if (h < R.Hq + R.Hkv) {
-          const float4* c4 = (const float4*)(R.cs + (size_t)row * half + f);
-          const float4 c01 = c4[0], c23 = c4[1];
-          const float cx[4] = {c01.x, c01.z, c23.x, c23.z}, sy[4] = {c01.y, c01.w, c23.y, c23.w};
+          const float cx[4] = {rc01[mt].x, rc01[mt].z, rc23[mt].x, rc23[mt].z}, sy[4] = {rc01[mt].y, rc01[mt].w, rc23[mt].y, rc23[mt].w};
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const float a = lo[v], b = hi[v];
@@ -276,15 +317,13 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
         const uint2 plo = make_uint2(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]));
         const uint2 phi = make_uint2(pack2(hi[0], hi[1]), pack2(hi[2], hi[3]));
         if (h < R.Hq) {
-          const int rep = R.Hq / R.Hkv, kvh = h / rep;
-          const int q = (row - R.seq_row0[sq]) * rep + h % rep;
-          const size_t tile = ((size_t)kvh * R.total_qt + R.seq_qt0[sq] + (q >> 4)) * tph;
+          const int kvh = h / (R.Hq / R.Hkv), q15 = r_b[mt];
+          const size_t tile = ((size_t)kvh * R.total_qt + r_a[mt]) * tph;
           const int d1 = f + half;
-          *(uint2*)(R.Q + ((tile + (f >> 5)) * 64 + ((f & 31) >> 3) * 16 + (q & 15)) * 8 + (f & 7)) = plo;
-          *(uint2*)(R.Q + ((tile + (d1 >> 5)) * 64 + ((d1 & 31) >> 3) * 16 + (q & 15)) * 8 + (d1 & 7)) = phi;
+          *(uint2*)(R.Q + ((tile + (f >> 5)) * 64 + ((f & 31) >> 3) * 16 + q15) * 8 + (f & 7)) = plo;
+          *(uint2*)(R.Q + ((tile + (d1 >> 5)) * 64 + ((d1 & 31) >> 3) * 16 + q15) * 8 + (d1 & 7)) = phi;
         } else {
-          const int pos = R.row_pos[row] + R.pos_add;
-          const int page = R.block_table[sq * R.pps + pos / EE_PAGE], pp = pos % EE_PAGE;
+          const int page = r_a[mt], pp = r_b[mt];
           if (h < R.Hq + R.Hkv) {
             bf16_t* slab = R.kv + kv_slab(R.layer, page, h - R.Hq, R.n_pages, R.Hkv, D);
             *(uint2*)(slab + k_page_off(pp, f, D)) = plo;
