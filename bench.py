@@ -37,36 +37,49 @@ MODEL_SEED = 20251001
 MEASURED_TRAFFIC_BYTES = 236_528_000
 CALIBRATION_COPY_BYTES = 1 << 30
 
+def _ragged16():
+    return [int(c) for c in synth.gen_context_lengths(16, 5)]     # lognormal(ln 1024, 0.7) clipped to [128, 4096]
+
+
 WORKLOADS = {
-    # name: (config factory, batch, ctx, k, agreement p)
-    "8b_b1_ctx2048_k8": (synth.llama8b_config, 1, 2048, 8, 0.8),
-    "tiny_b1_ctx32_k4": (lambda: synth.tiny_config(gamma=(1.0, 0.3, 0.3)), 1, 32, 4, 0.8),
-    "8b_reduced_b1_ctx2048_k8": (lambda: synth.llama8b_config(n_layers=8, exit_draft=1, exit_inter=4), 1, 2048, 8, 0.8),
+    # name: (config factory, per-sequence KV context lengths, k, agreement p)
+    # the default is the configuration the metric is quoted on; the others are the remaining single-GPU
+    # configurations, kept runnable for profiling (their parity is covered by the GPU tests)
+    "8b_b1_ctx2048_k8": (synth.llama8b_config, [2048], 8, 0.8),
+    "8b_b16_ragged_k8": (synth.llama8b_config, _ragged16, 8, 0.7),
+    "8b_b1_ctx32768_k16": (synth.llama8b_config, [32768], 16, 0.9),
+    "8b_b1_ctx32768_k16_li8": (lambda: synth.llama8b_config(exit_inter=8), [32768], 16, 0.9),
+    "8b_b1_ctx32768_k16_li24": (lambda: synth.llama8b_config(exit_inter=24), [32768], 16, 0.9),
+    "70b_b4_ctx1024_k8": (synth.llama70b_config, [1024] * 4, 8, 0.75),
+    "tiny_b1_ctx32_k4": (lambda: synth.tiny_config(gamma=(1.0, 0.3, 0.3)), [32], 4, 0.8),
+    "8b_reduced_b1_ctx2048_k8": (lambda: synth.llama8b_config(n_layers=8, exit_draft=1, exit_inter=4), [2048], 8, 0.8),
 }
 
 
-def step_bytes(cfg, batch, ctx, k, rows_full):
+def step_bytes(cfg, ctxs, k, rows_full):
     """Algorithmic HBM bytes of one step: every weight of the layers run once, the two exit heads,
     and the KV context once per layer pass (activations are negligible and left out)."""
     es = 2 if cfg.dtype == "bf16" else 4
     d, D, Hq, Hkv, F = cfg.d_model, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads, cfg.d_ffn
     per_layer = ((Hq + 2 * Hkv) * D * d + d * Hq * D + 3 * F * d) * es
     head = cfg.vocab * d * es
-    kv_layer = batch * ctx * 2 * Hkv * D * es
+    kv_layer = sum(ctxs) * 2 * Hkv * D * es
     layers = cfg.n_layers + (cfg.exit_inter if rows_full else 0)   # G1+G2+G3, + catch-up row through G1+G2
     return layers * (per_layer + kv_layer) + 2 * head
 
 
 def build_workload(name, seed=MODEL_SEED):
     import paper_2510_01336_amd as hs
-    factory, batch, ctx, k, p = WORKLOADS[name]
+    factory, ctxs, k, p = WORKLOADS[name]
+    ctxs = list(ctxs() if callable(ctxs) else ctxs)
+    batch = len(ctxs)
     cfg = factory()
     model = hs.Model(cfg, seed)
-    sess = hs.Session(model, batch, ctx + 64, 2 * (k + 1) + 2)
-    prompts = [synth.gen_prompt(cfg.vocab, ctx, 7 + b) for b in range(batch)]
+    sess = hs.Session(model, batch, max(ctxs) + 64, 2 * (k + 1) + 2)
+    prompts = [synth.gen_prompt(cfg.vocab, c, 7 + b) for b, c in enumerate(ctxs)]
     sess.prefill(prompts)
     # teacher-forced greedy continuation of the intermediate verifier, found with the library itself
-    # (k+1 untimed rounds), then a block agreeing with it with probability p per position
+    # (k untimed rounds), then a block agreeing with it with probability p per position
     rng = np.random.default_rng(11)
     greedy = np.zeros((batch, k), np.int64)
     for j in range(k):
@@ -74,11 +87,11 @@ def build_workload(name, seed=MODEL_SEED):
         S[:, :j] = greedy[:, :j]
         sess.draft_inject(S)
         a, nxt = sess.verify_intermediate()
-        greedy[:, j] = nxt
+        greedy[:, j] = np.where(a > j, S[:, j], nxt)      # (a random token may match by chance)
         for b in range(batch):
-            sess.rollback(b, 0b111, ctx)
+            sess.rollback(b, 0b111, ctxs[b])
     drafts = np.stack([synth.make_draft_block(greedy[b], k, p, cfg.vocab, rng) for b in range(batch)])
-    return dict(cfg=cfg, model=model, sess=sess, batch=batch, ctx=ctx, k=k, p=p, drafts=drafts, name=name)
+    return dict(cfg=cfg, model=model, sess=sess, batch=batch, ctxs=ctxs, k=k, p=p, drafts=drafts, name=name)
 
 
 def one_step(w, collect=None):
@@ -93,7 +106,7 @@ def one_step(w, collect=None):
     if collect is not None:
         collect(sess.kernel_times(), "full")
     for b in range(w["batch"]):
-        sess.rollback(b, 0b111, w["ctx"])
+        sess.rollback(b, 0b111, w["ctxs"][b])
     return a, f
 
 
@@ -102,7 +115,8 @@ def cpu_baseline(w):
     a random KV context of the workload's length) plus ONE exit head, scaled to the layer and head
     count of a full step."""
     from oracle import ee_oracle as eo
-    cfg, k, ctx, batch = w["cfg"], w["k"], w["ctx"], w["batch"]
+    cfg, k, batch = w["cfg"], w["k"], w["batch"]
+    ctx = int(round(sum(w["ctxs"]) / batch))           # mean context: the sample times one sequence's layer pass
     spec = eo.ModelSpec.from_config(cfg)
     l = cfg.exit_draft                         # first layer of G2
     store = synth.WeightStore(cfg, MODEL_SEED, cache=True)
@@ -205,7 +219,7 @@ def main():
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": gu_bytes, "avg_launch_us": gu_avg_s * 1e6,
                 "launches": gu_n}
-    sb = step_bytes(cfg, w["batch"], w["ctx"], w["k"], True)
+    sb = step_bytes(cfg, w["ctxs"], w["k"], True)
     kernel_ms = {k2: round(v[0] / args.steps, 4) for k2, v in acc.items()}
 
     out = {
@@ -213,7 +227,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "batch": w["batch"], "kv_context": w["ctx"], "k": w["k"],
+        "config": {"workload": args.workload, "batch": w["batch"],
+                   "kv_context": w["ctxs"][0] if w["batch"] == 1 else w["ctxs"], "k": w["k"],
                    "draft_agreement_p": w["p"], "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers],
                    "step": "draft_inject(G1) + verify_intermediate(G2) + verify_full(G1+G2 catch-up row, G3) + rollback",
                    "accepted_inter": [int(x) for x in a], "accepted_full": [int(x) for x in f]},
