@@ -38,6 +38,7 @@ enum { EPI_ADD = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_ROPE = 3 };
 // null = the operand is already fully normalised.
 struct NormIn {
   const float* ssq = nullptr; int n_part = 0, stride = 0; float inv_d = 0.f, eps = 0.f;
+  const float* inv_rms = nullptr;   // row-tiled GEMM only: the factors themselves, reduced from ssq beforehand
 };
 // EPI_ADD extra output: the updated residual rows as the next GEMM's operand, bf16(x * g) in fragment
 // layout, plus this tile's partial sums of squares ssq[tile][row].
@@ -64,6 +65,12 @@ struct GemmOut {
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out);
 void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                    const GemmOut& out, int nw, int ksplit, int U);
+// Row-tiled variant for 64 < M <= 256 rows (rows start at row 0 of the operand; the operand buffer holds
+// whole row tiles up to the next multiple of 64 rows).  scratch: bf16_gemm_rows_scratch_floats() floats for
+// this shape (may be null when that is 0); inv_rms: M floats of scratch for the deferred RMSNorm factors.
+size_t bf16_gemm_rows_scratch_floats(int ntiles, int ktiles);
+void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
+                    const GemmOut& out, float* scratch, float* inv_rms);
 void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf16_t* out, int ktiles, int M, int d);
 struct AttnScratch { float* part_o; float* part_ml; int max_splits; };
 void bf16_attention(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,

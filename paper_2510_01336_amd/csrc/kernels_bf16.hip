@@ -88,6 +88,141 @@ void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf1
 //   EPI_ARGMAX  per-row (max, arg max) of the tile (+ optional fp32 logits)
 // Every epilogue first applies the operand's deferred RMSNorm factor (NormIn).
 // ---------------------------------------------------------------------------------------------
+// ---- epilogue of one 16 x 16 output tile (or tile pair), shared by the skinny and the row-tiled GEMM ----
+// A lane of the epilogue wave holds, for row m = mt*16 + lane%16, the four consecutive outputs
+// n = 16*tile + 4*(lane/16) .. +3 (acc[0]); for the paired epilogues acc[1] is the same lane's slice of the
+// partner tile (up for gate, the rotary partner half for Q/K/V).
+struct EpiPre {            // operands of the epilogue that do not depend on the product
+  float4 res, gnext;       // EPI_ADD: residual row slice, gains of the next operand
+  float4 rc01, rc23;       // EPI_ROPE: (cos, sin) of the lane's four rotary pairs
+  int r_a, r_b;            // EPI_ROPE: Q heads: (global q-tile, row in tile); K/V heads: (page, position in page)
+};
+
+template <int EPI>
+__device__ inline void epi_prefetch(EpiPre& p, const GemmOut& out, int task, int row, bool ok, int lane) {
+  const int g = lane >> 4;
+  p.res = p.gnext = make_float4(0.f, 0.f, 0.f, 0.f);
+  p.rc01 = p.rc23 = make_float4(1.f, 0.f, 1.f, 0.f);
+  p.r_a = p.r_b = 0;
+  if (EPI == EPI_ADD) {
+    const int n = task * 16 + 4 * g;
+    if (ok) p.res = *(const float4*)(out.Y + (size_t)row * out.ldy + n);
+    if (out.nout.xn) p.gnext = *(const float4*)(out.nout.g + n);
+  }
+  if (EPI == EPI_ROPE && ok) {
+    const RopeOut& R = out.rope;
+    const int half = R.D >> 1, tph = R.D >> 5;
+    const int h = task / tph, f = (task % tph) * 16 + 4 * g;
+    const int sq = R.row_seq[row];
+    if (h < R.Hq + R.Hkv) {
+      const float4* c4 = (const float4*)(R.cs + (size_t)row * half + f);
+      p.rc01 = c4[0]; p.rc23 = c4[1];
+    }
+    if (h < R.Hq) {
+      const int q = (row - R.seq_row0[sq]) * (R.Hq / R.Hkv) + h % (R.Hq / R.Hkv);
+      p.r_a = R.seq_qt0[sq] + (q >> 4); p.r_b = q & 15;
+    } else {
+      const int pos = R.row_pos[row] + R.pos_add;
+      p.r_a = R.block_table[sq * R.pps + pos / EE_PAGE]; p.r_b = pos % EE_PAGE;
+    }
+  }
+}
+
+// sc: the row's deferred RMSNorm factor (1 when the operand was already normalised)
+template <int EPI>
+__device__ inline void epi_apply(const f32x4& acc0, const f32x4& acc1, float sc, const EpiPre& p, const GemmOut& out, int task,
+                                 int row, bool ok, int N, int lane) {
+  const int g = lane >> 4;
+  if (EPI == EPI_ADD) {
+    const int n = task * 16 + 4 * g;
+    float4 r = make_float4(acc0[0] * sc, acc0[1] * sc, acc0[2] * sc, acc0[3] * sc);
+    r.x += p.res.x; r.y += p.res.y; r.z += p.res.z; r.w += p.res.w;
+    if (ok) *(float4*)(out.Y + (size_t)row * out.ldy + n) = r;
+    if (out.nout.xn) {
+      const float4 gn = p.gnext;
+      if (ok) *(uint2*)(out.nout.xn + frag_offset(row, n, out.nout.ktiles)) = make_uint2(pack2(r.x * gn.x, r.y * gn.y), pack2(r.z * gn.z, r.w * gn.w));
+      float ss = ok ? (r.x * r.x + r.y * r.y) + (r.z * r.z + r.w * r.w) : 0.f;
+      ss += __shfl_xor(ss, 16, 64);
+      ss += __shfl_xor(ss, 32, 64);
+      if (g == 0) out.nout.ssq[(size_t)task * out.nout.stride + row] = ss;
+    }
+  } else if (EPI == EPI_SWIGLU) {
+    const int f = task * 16 + 4 * g;     // h[m][f..f+3] = silu(gate) * up
+    if (ok) {
+      float h[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float gt = acc0[v] * sc, up = acc1[v] * sc;
+        h[v] = gt / (1.0f + __expf(-gt)) * up;
+      }
+      *(uint2*)(out.H + frag_offset(row, f, out.h_ktiles)) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
+    }
+  } else if (EPI == EPI_ROPE) {
+    // task = (head h, 16 rotary pairs f0..f0+15): acc0 holds features f, acc1 their partners f + D/2
+    const RopeOut& R = out.rope;
+    const int D = R.D, half = D >> 1, tph = D >> 5;
+    const int h = task / tph, f = (task % tph) * 16 + 4 * g;
+    if (ok) {
+      float lo[4], hi[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) { lo[v] = acc0[v] * sc; hi[v] = acc1[v] * sc; }
+      if (h < R.Hq + R.Hkv) {
+        const float cx[4] = {p.rc01.x, p.rc01.z, p.rc23.x, p.rc23.z}, sy[4] = {p.rc01.y, p.rc01.w, p.rc23.y, p.rc23.w};
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float a = lo[v], b = hi[v];
+          lo[v] = a * cx[v] - b * sy[v];
+          hi[v] = b * cx[v] + a * sy[v];
+        }
+      }
+      const uint2 plo = make_uint2(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]));
+      const uint2 phi = make_uint2(pack2(hi[0], hi[1]), pack2(hi[2], hi[3]));
+      if (h < R.Hq) {
+        const int kvh = h / (R.Hq / R.Hkv), q15 = p.r_b;
+        const size_t tile = ((size_t)kvh * R.total_qt + p.r_a) * tph;
+        const int d1 = f + half;
+        *(uint2*)(R.Q + ((tile + (f >> 5)) * 64 + ((f & 31) >> 3) * 16 + q15) * 8 + (f & 7)) = plo;
+        *(uint2*)(R.Q + ((tile + (d1 >> 5)) * 64 + ((d1 & 31) >> 3) * 16 + q15) * 8 + (d1 & 7)) = phi;
+      } else {
+        const int page = p.r_a, pp = p.r_b;
+        if (h < R.Hq + R.Hkv) {
+          bf16_t* slab = R.kv + kv_slab(R.layer, page, h - R.Hq, R.n_pages, R.Hkv, D);
+          *(uint2*)(slab + k_page_off(pp, f, D)) = plo;
+          *(uint2*)(slab + k_page_off(pp, f + half, D)) = phi;
+        } else {
+          bf16_t* slab = R.kv + kv_slab(R.layer, page, h - R.Hq - R.Hkv, R.n_pages, R.Hkv, D) + EE_PAGE * D;
+          const uint32_t wl[2] = {plo.x, plo.y}, wh[2] = {phi.x, phi.y};
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            slab[v_page_off(pp, f + v, D)] = (bf16_t)(wl[v >> 1] >> (16 * (v & 1)));
+            slab[v_page_off(pp, f + half + v, D)] = (bf16_t)(wh[v >> 1] >> (16 * (v & 1)));
+          }
+        }
+      }
+    }
+  } else {   // EPI_ARGMAX: per-row (max, arg max) over this tile's 16 outputs; lowest index wins ties
+    float best = -INFINITY; int bi = 0x7fffffff;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int n = task * 16 + 4 * g + v;
+      const float t = acc0[v] * sc;
+      if (n < N) {
+        if (out.Y && ok) out.Y[(size_t)row * out.ldy + n] = t;
+        if (t > best) { best = t; bi = n; }
+      }
+    }
+#pragma unroll
+    for (int sh = 16; sh <= 32; sh <<= 1) {
+      const float ob = __shfl_xor(best, sh, 64); const int oi = __shfl_xor(bi, sh, 64);
+      if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
+    }
+    if (g == 0 && ok) {
+      out.pmax[(size_t)task * out.pstride + row] = best;
+      out.pidx[(size_t)task * out.pstride + row] = bi;
+    }
+  }
+}
+
 template <int MT, int NB, int U>
 struct Frags {
   u32x4 w[NB][U];
@@ -136,48 +271,12 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 
   // Epilogue operands that do not depend on the product (residual rows and gains; rotary table and page
   // lookups) are requested by the epilogue wave now, so their latency is not paid after the reduction.
-  const int g = lane >> 4, mc = lane & 15;
+  const int mc = lane & 15;
   const bool epi_wave = active && kpart == 0;
-  float4 res[MT], gnext = make_float4(0.f, 0.f, 0.f, 0.f);
-  float4 rc01[MT], rc23[MT];
-  int r_a[MT], r_b[MT];      // EPI_ROPE: Q heads: (global q-tile, row in tile); K/V heads: (page, position in page)
+  EpiPre pre[MT];
+  if (epi_wave) {
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    res[mt] = make_float4(0.f, 0.f, 0.f, 0.f);
-    rc01[mt] = rc23[mt] = make_float4(1.f, 0.f, 1.f, 0.f);
-    r_a[mt] = r_b[mt] = 0;
-  }
-  if (EPI == EPI_ADD && epi_wave) {
-    const int n = task * 16 + 4 * g;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = mt * 16 + mc;
-      if (m < M) res[mt] = *(const float4*)(out.Y + (size_t)(row0 + m) * out.ldy + n);
-    }
-    if (out.nout.xn) gnext = *(const float4*)(out.nout.g + n);
-  }
-  if (EPI == EPI_ROPE && epi_wave) {
-    const RopeOut& R = out.rope;
-    const int half = R.D >> 1, tph = R.D >> 5;
-    const int h = task / tph, f = (task % tph) * 16 + 4 * g;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = mt * 16 + mc, row = row0 + m;
-      if (m < M) {
-        const int sq = R.row_seq[row];
-        if (h < R.Hq + R.Hkv) {
-          const float4* c4 = (const float4*)(R.cs + (size_t)row * half + f);
-          rc01[mt] = c4[0]; rc23[mt] = c4[1];
-        }
-        if (h < R.Hq) {
-          const int q = (row - R.seq_row0[sq]) * (R.Hq / R.Hkv) + h % (R.Hq / R.Hkv);
-          r_a[mt] = R.seq_qt0[sq] + (q >> 4); r_b[mt] = q & 15;
-        } else {
-          const int pos = R.row_pos[row] + R.pos_add;
-          r_a[mt] = R.block_table[sq * R.pps + pos / EE_PAGE]; r_b[mt] = pos % EE_PAGE;
-        }
-      }
-    }
+    for (int mt = 0; mt < MT; ++mt) epi_prefetch<EPI>(pre[mt], out, task, row0 + mt * 16 + mc, mt * 16 + mc < M, lane);
   }
 
   // Deferred RMSNorm: sum of squares of row mt*16 + lane%16 from the producer's per-tile partials, in a
@@ -221,19 +320,17 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
   }
 
   if (stream) {
-    {
-      Frags<MT, NB, U> nxt;
-      for (int kt = kt0; kt < kt1; kt += U) {
-        const bool more = kt + U < kt1;
-        if (more) load_frags<MT, NB, U>(nxt, wp, ap, ktiles, kt + U, kt1);
+    Frags<MT, NB, U> nxt;
+    for (int kt = kt0; kt < kt1; kt += U) {
+      const bool more = kt + U < kt1;
+      if (more) load_frags<MT, NB, U>(nxt, wp, ap, ktiles, kt + U, kt1);
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+      for (int u = 0; u < U; ++u)
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = mfma16(cur.w[nb][u], cur.x[mt][u], acc[nb][mt]);
-        if (more) cur = nxt;
-      }
+          for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = mfma16(cur.w[nb][u], cur.x[mt][u], acc[nb][mt]);
+      if (more) cur = nxt;
     }
   }
 
@@ -264,103 +361,230 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int m = mt * 16 + mc, row = row0 + m;
-    const bool ok = m < M;
+    const int m = mt * 16 + mc;
     float sc = 1.0f;
     if (normed) {
       float ss = ssl[mt];
       for (int w = 1; w < ksplit; ++w) ss += ssq_red[wave + w][m];
       sc = 1.0f / sqrtf(ss * out.nin.inv_d + out.nin.eps);
     }
-    if (EPI == EPI_ADD) {
-      const int n = task * 16 + 4 * g;
-      float4 r = make_float4(acc[0][mt][0] * sc, acc[0][mt][1] * sc, acc[0][mt][2] * sc, acc[0][mt][3] * sc);
-      r.x += res[mt].x; r.y += res[mt].y; r.z += res[mt].z; r.w += res[mt].w;
-      if (ok) *(float4*)(out.Y + (size_t)row * out.ldy + n) = r;
-      if (out.nout.xn) {
-        const float4 gn = gnext;
-        if (ok) *(uint2*)(out.nout.xn + frag_offset(row, n, out.nout.ktiles)) = make_uint2(pack2(r.x * gn.x, r.y * gn.y), pack2(r.z * gn.z, r.w * gn.w));
-        float ss = ok ? (r.x * r.x + r.y * r.y) + (r.z * r.z + r.w * r.w) : 0.f;
-        ss += __shfl_xor(ss, 16, 64);
-        ss += __shfl_xor(ss, 32, 64);
-        if (g == 0) out.nout.ssq[(size_t)task * out.nout.stride + row] = ss;
-      }
-    } else if (EPI == EPI_SWIGLU) {
-      const int f = task * 16 + 4 * g;     // h[m][f..f+3] = silu(gate) * up
-      if (ok) {
-        float h[4];
+    epi_apply<EPI>(acc[0][mt], acc[NB - 1][mt], sc, pre[mt], out, task, row0 + m, m < M, N, lane);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row-tiled GEMM for 64 < M <= 256 rows: weights still cross HBM once, but every weight fragment now
+// meets up to 16 row tiles, so the kernel sits near the machine's ridge (M flop per weight byte).
+// Workgroup = 4 waves on a group of 8 weight tiles (128 output features) and a share of K (grid.y);
+// wave (rh, nh) owns 4 of the tiles and half of the TMT row tiles: 2*TMT accumulators.
+//   weights      HBM -> registers, a rolling ring three k-tiles deep per wave
+//   activations  L2 -> registers (two k-tiles ahead) -> a two-slot LDS ring shared by the four waves
+// The steady-state loop is free of branches around its loads (indices past the end are clamped and
+// only the MFMAs are guarded), so the in-order load counters never force a full drain.
+// With grid.y == 1 the epilogue is fused; otherwise fp32 partial tiles go to scratch and
+// gemm_rows_reduce_kernel sums the K shares in a fixed order and runs the same epilogue.
+// ---------------------------------------------------------------------------------------------
+#define EE_ROWS_TN 4
+template <int TMT, int EPI>
+__global__ __launch_bounds__(256) void gemm_rows_kernel(const uint4* __restrict__ W, int ktiles, int ntiles,
+                                                        const uint4* __restrict__ A, int M, int N, GemmOut out,
+                                                        int per, float* __restrict__ partial) {
+  constexpr int TN = EE_ROWS_TN, NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
+  constexpr int CPW = TMT / 4, TMW = TMT / 2;       // activation chunks each wave stages per k-tile; row tiles per wave
+  static_assert(TMT % 4 == 0, "row tiles are staged four ways");
+  __shared__ u32x4 xs[2][TMT * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, rh = wave >> 1;
+  const int nt0 = blockIdx.x * (2 * TN) + (wave & 1) * TN;      // first weight tile of this wave
+  const int mt0 = rh * TMW;                                     // first row tile of this wave
+  const int kt0 = blockIdx.y * per, kt1 = min(ktiles, kt0 + per);
+  if (kt0 >= kt1) return;                                       // whole workgroup (never with the launcher's shapes)
+  const int last = kt1 - 1;
+
+  f32x4 acc[TN][TMW];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          float gt = acc[0][mt][v] * sc, up = acc[NB - 1][mt][v] * sc;
-          h[v] = gt / (1.0f + __expf(-gt)) * up;
-        }
-        *(uint2*)(out.H + frag_offset(row, f, out.h_ktiles)) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
-      }
-    } else if (EPI == EPI_ROPE) {
-      // task = (head h, 16 rotary pairs f0..f0+15): acc[0] holds features f, acc[1] their partners f + D/2
-      const RopeOut& R = out.rope;
-      const int D = R.D, half = D >> 1, tph = D >> 5;
-      const int h = task / tph, f = (task % tph) * 16 + 4 * g;
-      if (ok) {
-        float lo[4], hi[4];
+  for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) { lo[v] = acc[0][mt][v] * sc; hi[v] = acc[NB - 1][mt][v] * sc; }
-        if (h < R.Hq + R.Hkv) {
-          const float cx[4] = {rc01[mt].x, rc01[mt].z, rc23[mt].x, rc23[mt].z}, sy[4] = {rc01[mt].y, rc01[mt].w, rc23[mt].y, rc23[mt].w};
+    for (int mt = 0; mt < TMW; ++mt) acc[tn][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const u32x4* wp[TN];
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const float a = lo[v], b = hi[v];
-            lo[v] = a * cx[v] - b * sy[v];
-            hi[v] = b * cx[v] + a * sy[v];
-          }
-        }
-        const uint2 plo = make_uint2(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]));
-        const uint2 phi = make_uint2(pack2(hi[0], hi[1]), pack2(hi[2], hi[3]));
-        if (h < R.Hq) {
-          const int kvh = h / (R.Hq / R.Hkv), q15 = r_b[mt];
-          const size_t tile = ((size_t)kvh * R.total_qt + r_a[mt]) * tph;
-          const int d1 = f + half;
-          *(uint2*)(R.Q + ((tile + (f >> 5)) * 64 + ((f & 31) >> 3) * 16 + q15) * 8 + (f & 7)) = plo;
-          *(uint2*)(R.Q + ((tile + (d1 >> 5)) * 64 + ((d1 & 31) >> 3) * 16 + q15) * 8 + (d1 & 7)) = phi;
-        } else {
-          const int page = r_a[mt], pp = r_b[mt];
-          if (h < R.Hq + R.Hkv) {
-            bf16_t* slab = R.kv + kv_slab(R.layer, page, h - R.Hq, R.n_pages, R.Hkv, D);
-            *(uint2*)(slab + k_page_off(pp, f, D)) = plo;
-            *(uint2*)(slab + k_page_off(pp, f + half, D)) = phi;
-          } else {
-            bf16_t* slab = R.kv + kv_slab(R.layer, page, h - R.Hq - R.Hkv, R.n_pages, R.Hkv, D) + EE_PAGE * D;
-            const uint32_t wl[2] = {plo.x, plo.y}, wh[2] = {phi.x, phi.y};
+  for (int tn = 0; tn < TN; ++tn) wp[tn] = (const u32x4*)W + (size_t)min(nt0 + tn, ntiles - 1) * ktiles * 64 + lane;
+  const u32x4* xp = (const u32x4*)A + (size_t)(wave * CPW) * ktiles * 64 + lane;   // this wave stages row tiles wave*CPW ..
+  // register rings: weights WR k-tiles deep, staged activations XR deep; the loop is unrolled by their common multiple
+  constexpr int WR = 3, XR = 2, UN = 6;
+  u32x4 wf[WR][TN], xst[XR][CPW];
+#define ROWS_FETCH_W(s_, kt_)                                                                            \
+  do {                                                                                                   \
+    const size_t k_ = (size_t)min(kt_, last) * 64;                                                       \
+    _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) wf[s_][tn] = __builtin_nontemporal_load(wp[tn] + k_); \
+  } while (0)
+#define ROWS_FETCH_X(s_, kt_)                                                                            \
+  do {                                                                                                   \
+    const size_t k_ = (size_t)min(kt_, last) * 64;                                                       \
+    _Pragma("unroll") for (int c = 0; c < CPW; ++c) xst[s_][c] = xp[(size_t)c * ktiles * 64 + k_];      \
+  } while (0)
+#define ROWS_DEPOSIT_X(slot_, s_)                                                                        \
+  do {                                                                                                   \
+    _Pragma("unroll") for (int c = 0; c < CPW; ++c) xs[slot_][(wave * CPW + c) * 64 + lane] = xst[s_][c]; \
+  } while (0)
+  // activations of k-tile kt live in register set kt%XR until deposited into LDS slot kt%2 one iteration ahead of use
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              slab[v_page_off(pp, f + v, D)] = (bf16_t)(wl[v >> 1] >> (16 * (v & 1)));
-              slab[v_page_off(pp, f + half + v, D)] = (bf16_t)(wh[v >> 1] >> (16 * (v & 1)));
-            }
-          }
-        }
-      }
-    } else {   // EPI_ARGMAX: per-row (max, arg max) over this tile's 16 outputs; lowest index wins ties
-      float best = -INFINITY; int bi = 0x7fffffff;
+  for (int j = 0; j < XR; ++j) ROWS_FETCH_X(j, kt0 + j);
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int n = task * 16 + 4 * g + v;
-        float t = acc[0][mt][v] * sc;
-        if (n < N) {
-          if (out.Y && ok) out.Y[(size_t)row * out.ldy + n] = t;
-          if (t > best) { best = t; bi = n; }
-        }
-      }
+  for (int j = 0; j < WR; ++j) ROWS_FETCH_W(j, kt0 + j);
+  ROWS_DEPOSIT_X(0, 0);
+  ROWS_FETCH_X(0, kt0 + XR);
+  __syncthreads();
+  for (int kt = kt0; kt < kt1; kt += UN) {
 #pragma unroll
-      for (int sh = 16; sh <= 32; sh <<= 1) {
-        float ob = __shfl_xor(best, sh, 64); int oi = __shfl_xor(bi, sh, 64);
-        if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
+    for (int j = 0; j < UN; ++j) {
+      ROWS_DEPOSIT_X((j + 1) & 1, (j + 1) % XR);
+      ROWS_FETCH_X((j + 1) % XR, kt + j + 1 + XR);
+      if (kt + j < kt1) {
+        // all activation fragments of the k-tile are read from LDS in one group (one exposed LDS latency
+        // per k-tile; the scheduling barrier keeps the compiler from sinking the reads next to their uses)
+        const u32x4* xl = xs[j & 1] + mt0 * 64 + lane;
+        u32x4 xf[TMW];
+#pragma unroll
+        for (int mt = 0; mt < TMW; ++mt) xf[mt] = xl[mt * 64];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < TMW; ++mt)
+#pragma unroll
+          for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = mfma16(wf[j % WR][tn], xf[mt], acc[tn][mt]);
       }
-      if (g == 0 && ok) {
-        out.pmax[(size_t)task * out.pstride + row] = best;
-        out.pidx[(size_t)task * out.pstride + row] = bi;
-      }
+      ROWS_FETCH_W(j % WR, kt + j + WR);
+      __syncthreads();
     }
   }
+#undef ROWS_FETCH_W
+#undef ROWS_FETCH_X
+#undef ROWS_DEPOSIT_X
+
+  const int mc = lane & 15;
+  if (gridDim.y > 1) {
+    // K share: raw accumulator tiles [k share][weight tile][row tile][lane] for the reduce kernel
+    f32x4* pp = (f32x4*)partial + (size_t)blockIdx.y * ntiles * TMT * 64 + lane;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      if (nt0 + tn >= ntiles) continue;
+#pragma unroll
+      for (int mt = 0; mt < TMW; ++mt)
+        if ((mt0 + mt) * 16 < M) __builtin_nontemporal_store(acc[tn][mt], pp + ((size_t)(nt0 + tn) * TMT + mt0 + mt) * 64);
+    }
+    return;
+  }
+#pragma unroll
+  for (int t = 0; t < TN / NB; ++t) {
+    const int nt = nt0 + t * NB;
+    if (nt >= ntiles) continue;
+    const int task = nt / NB;
+#pragma unroll
+    for (int mt = 0; mt < TMW; ++mt) {
+      const int m = (mt0 + mt) * 16 + mc;
+      if ((mt0 + mt) * 16 >= M) continue;
+      const float sc = out.nin.inv_rms ? out.nin.inv_rms[min(m, M - 1)] : 1.0f;
+      EpiPre pre;
+      epi_prefetch<EPI>(pre, out, task, m, m < M, lane);
+      epi_apply<EPI>(acc[t * NB][mt], acc[t * NB + NB - 1][mt], sc, pre, out, task, m, m < M, N, lane);
+    }
+  }
+}
+
+// sums the K shares of one (task, row tile) in a fixed order and runs the epilogue; one wave per unit
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_rows_reduce_kernel(const float* __restrict__ partial, int ksplit, int ntiles, int TMT,
+                                                               int M, int N, GemmOut out) {
+  constexpr int NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
+  const int lane = threadIdx.x & 63, mc = lane & 15;
+  const int mtiles = (M + 15) >> 4;
+  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int task = unit / mtiles, mt = unit % mtiles;
+  if (task * NB >= ntiles) return;
+  const int m = mt * 16 + mc;
+  EpiPre pre;
+  epi_prefetch<EPI>(pre, out, task, m, m < M, lane);
+  const float sc = out.nin.inv_rms ? out.nin.inv_rms[min(m, M - 1)] : 1.0f;
+  f32x4 acc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const f32x4* pp = (const f32x4*)partial + ((size_t)(task * NB + nb) * TMT + mt) * 64 + lane;
+    for (int s0 = 0; s0 < ksplit; s0 += 8) {
+      f32x4 t[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = __builtin_nontemporal_load(pp + (size_t)min(s0 + i, ksplit - 1) * ntiles * TMT * 64);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (s0 + i < ksplit) acc[nb] += t[i];
+    }
+  }
+  epi_apply<EPI>(acc[0], acc[NB - 1], sc, pre, out, task, m, m < M, N, lane);
+}
+
+// per-row factor rsqrt(mean(x^2) + eps) from the producer's per-tile partial sums of squares, in a fixed order
+__global__ __launch_bounds__(256) void norm_factor_kernel(const float* __restrict__ ssq, int n_part, int stride, float inv_d, float eps,
+                                                          float* __restrict__ inv_rms, int M) {
+  // 16 lanes per row, each taking every 16th partial
+  const int row = blockIdx.x * 16 + (threadIdx.x >> 4), t = threadIdx.x & 15;
+  float ss = 0.f;
+  if (row < M)
+    for (int i = t; i < n_part; i += 16) ss += ssq[(size_t)i * stride + row];
+  for (int sh = 1; sh < 16; sh <<= 1) ss += __shfl_xor(ss, sh, 64);
+  if (row < M && t == 0) inv_rms[row] = 1.0f / sqrtf(ss * inv_d + eps);
+}
+
+// number of K shares the row-tiled GEMM runs with: enough workgroups for the chip, at least 16 k-tiles each
+static int rows_ksplit(int ntiles, int ktiles) {
+  const int groups = ceil_div(ntiles, 2 * EE_ROWS_TN);
+  int ks = groups >= 192 ? 1 : min(8, ceil_div(224, groups));
+  while (ks > 1 && ktiles / ks < 16) --ks;
+  return ks;
+}
+size_t bf16_gemm_rows_scratch_floats(int ntiles, int ktiles) {
+  const int ks = rows_ksplit(ntiles, ktiles);
+  return ks > 1 ? (size_t)ks * ntiles * 16 * 256 : 0;       // [k share][weight tile][16 row tiles][64 lanes x 4]
+}
+
+template <int TMT>
+static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int M, int N,
+                             const GemmOut& out, float* scratch) {
+  const int ks = rows_ksplit(ntiles, ktiles), per = ceil_div(ktiles, ks);
+  dim3 grid(ceil_div(ntiles, 2 * EE_ROWS_TN), ceil_div(ktiles, per)), blk(256);
+  const int ksr = grid.y;
+  switch (epi) {
+    case EPI_ADD: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ADD>), grid, blk, 0, st, W, ktiles, ntiles, A, M, N, out, per, scratch); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_SWIGLU>), grid, blk, 0, st, W, ktiles, ntiles, A, M, N, out, per, scratch); break;
+    case EPI_ROPE: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ROPE>), grid, blk, 0, st, W, ktiles, ntiles, A, M, N, out, per, scratch); break;
+    default: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ARGMAX>), grid, blk, 0, st, W, ktiles, ntiles, A, M, N, out, per, scratch); break;
+  }
+  if (ksr > 1) {
+    const int nb = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? 2 : 1;
+    const int units = (ntiles / nb) * ceil_div(M, 16);
+    dim3 rgrid(ceil_div(units, 4));
+    switch (epi) {
+      case EPI_ADD: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ADD>), rgrid, blk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
+      case EPI_SWIGLU: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_SWIGLU>), rgrid, blk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
+      case EPI_ROPE: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ROPE>), rgrid, blk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
+      default: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ARGMAX>), rgrid, blk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
+    }
+  }
+}
+
+// 64 < M <= 256 rows from row 0 of the operand; out.nin.ssq, if set, is first reduced to per-row factors
+void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
+                    const GemmOut& out0, float* scratch, float* inv_rms) {
+  GemmOut out = out0;
+  if (out.nin.ssq) {
+    hipLaunchKernelGGL(norm_factor_kernel, dim3(ceil_div(M, 16)), dim3(256), 0, st, out.nin.ssq, out.nin.n_part, out.nin.stride,
+                       out.nin.inv_d, out.nin.eps, inv_rms, M);
+    out.nin.inv_rms = inv_rms;
+  }
+  const uint4* Wc = (const uint4*)W;
+  const uint4* Ac = (const uint4*)A;
+  if (M <= 128) launch_gemm_rows<8>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
+  else if (M <= 192) launch_gemm_rows<12>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
+  else launch_gemm_rows<16>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
 }
 
 template <int MT, int U>

@@ -34,7 +34,8 @@ struct ee_session {
   void *XN = nullptr, *Qb = nullptr, *AO = nullptr, *H = nullptr;
   float2* cs = nullptr;
   int *vtok = nullptr, *tok_next = nullptr, *draft_dev = nullptr, *out_dev = nullptr, *page_scratch = nullptr;
-  float *part_o = nullptr, *part_ml = nullptr, *pmax = nullptr, *ssq = nullptr;
+  float *part_o = nullptr, *part_ml = nullptr, *pmax = nullptr, *ssq = nullptr, *gemm_part = nullptr, *inv_rms = nullptr;
+  size_t part_units = 0;        // capacity of the attention split scratch in (q-tile, split) units per KV head
   int* pidx = nullptr;
   int max_splits = 64;
   // host side
@@ -110,11 +111,19 @@ static size_t carve(ee_session* s, char* base) {
   s->out_dev = cv.take<int>(2 * (size_t)s->B);
   s->page_scratch = cv.take<int>(s->pps);
   if (bf) {
-    s->part_o = cv.take<float>((size_t)s->maxQT * Hkv * s->max_splits * 16 * D);
-    s->part_ml = cv.take<float>((size_t)s->maxQT * Hkv * s->max_splits * 32);
+    // attention split scratch: all 64 splits for verify-sized calls (<= 64 rows), 8 for context-build passes
+    const size_t qt_small = (size_t)ceil_div(std::min(s->maxM, 64) * rep, 16) + s->B;
+    s->part_units = std::max(qt_small * s->max_splits, (size_t)s->maxQT * 8);
+    s->part_o = cv.take<float>(s->part_units * Hkv * 16 * D);
+    s->part_ml = cv.take<float>(s->part_units * Hkv * 32);
     s->pmax = cv.take<float>((size_t)m->head.ntiles() * Mp);
     s->pidx = cv.take<int>((size_t)m->head.ntiles() * Mp);
     s->ssq = cv.take<float>((size_t)ceil_div(d, 16) * Mp);            // deferred-RMSNorm partials [d/16][Mp]
+    size_t gp = 0;                                                    // K-share scratch of the row-tiled GEMM
+    for (const MatLoc* ml : {&m->L[0].qkv, &m->L[0].o, &m->L[0].gu, &m->L[0].down, &m->head})
+      gp = std::max(gp, bf16_gemm_rows_scratch_floats(ml->ntiles(), ml->ktiles()));
+    s->gemm_part = s->maxM > 64 ? cv.take<float>(gp) : nullptr;
+    s->inv_rms = cv.take<float>(256);
   }
   s->slot[0].d = cv.take<int>(s->meta_ints);
   s->slot[1].d = cv.take<int>(s->meta_ints);
@@ -130,9 +139,10 @@ static int shape_session(ee_session* s, const ee_model* m, int batch, int max_ct
   s->B = batch; s->max_ctx = max_ctx; s->max_rows = max_rows;
   s->pps = ceil_div(max_ctx, EE_PAGE);
   s->n_pages = total_pages > 0 ? total_pages : batch * s->pps;
-  s->chunk = 64;                                        // prefill rows per pass
+  s->chunk = m->bf16 ? 256 : 64;                        // context-build rows per pass
   s->maxM = std::max(batch * max_rows, s->chunk);
-  s->Mp = ceil_div(s->maxM, 64) * 64;                   // activation rows padded to whole 64-row GEMM passes
+  // activation rows padded to whole GEMM passes: 64 rows (skinny kernel), 256 (row-tiled kernel reads 16 row tiles)
+  s->Mp = s->maxM <= 64 ? 64 : std::max(256, ceil_div(s->maxM, 64) * 64);
   s->maxQT = ceil_div(s->maxM * rep, 16) + batch;
   layout_meta(s);
   return EE_OK;
@@ -303,6 +313,14 @@ static void reset_accounting(ee_session* s) {
 // ---------------------------------------------------------------------------------------------
 // forward pass pieces
 // ---------------------------------------------------------------------------------------------
+// weights cross HBM once per call: up to 64 rows the skinny kernel, up to 256 the row-tiled one (beyond that
+// the skinny kernel goes over the rows in passes of 64)
+static void gemm(ee_session* s, int epi, const MatLoc& ml, const bf16_t* A, int M, const GemmOut& o) {
+  const bf16_t* W = (const bf16_t*)(s->m->base + ml.off);
+  if (M > 64 && M <= 256) bf16_gemm_rows(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o, s->gemm_part, s->inv_rms);
+  else bf16_gemm(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o);
+}
+
 static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const CallMeta& mt, int pos_add) {
   const ee_model* m = s->m;
   const ee_config& c = m->cfg;
@@ -315,10 +333,6 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
     const float* g2 = (const float*)(m->base + L.g2);
     if (m->bf16) {
       // five launches per layer; RMSNorm is deferred into the projections (see NormIn / NormOut)
-      const bf16_t* Wqkv = (const bf16_t*)(m->base + L.qkv.off);
-      const bf16_t* Wo = (const bf16_t*)(m->base + L.o.off);
-      const bf16_t* Wgu = (const bf16_t*)(m->base + L.gu.off);
-      const bf16_t* Wd = (const bf16_t*)(m->base + L.down.off);
       const int Mp = s->Mp;
       NormIn nin;         // operand left by the previous EPI_ADD launch
       nin.ssq = s->ssq; nin.n_part = d / 16; nin.stride = Mp; nin.inv_d = 1.0f / (float)d; nin.eps = c.rms_eps;
@@ -331,19 +345,19 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
       R.cs = s->cs; R.row_seq = mt.row_seq; R.row_pos = mt.row_pos; R.seq_row0 = mt.seq_row0; R.seq_qt0 = mt.seq_qt0;
       R.block_table = mt.block_table; R.pos_add = pos_add; R.Hq = Hq; R.Hkv = Hkv; R.D = D; R.layer = l;
       R.n_pages = s->n_pages; R.pps = s->pps; R.total_qt = p.total_qt; R.Q = (bf16_t*)s->Qb; R.kv = (bf16_t*)s->kv;
-      KF(KF_GEMM_QKV, bf16_gemm(st, EPI_ROPE, Wqkv, L.qkv.ntiles(), L.qkv.ktiles(), (const bf16_t*)s->XN, M, L.qkv.N, o));
-      AttnScratch scr{s->part_o, s->part_ml, s->max_splits};
+      KF(KF_GEMM_QKV, gemm(s, EPI_ROPE, L.qkv, (const bf16_t*)s->XN, M, o));
+      AttnScratch scr{s->part_o, s->part_ml, (int)std::min<size_t>(s->max_splits, s->part_units / std::max(1, p.total_qt))};
       KF(KF_ATTN, bf16_attention(st, (const bf16_t*)s->Qb, (const bf16_t*)s->kv, mt, pos_add, s->B, p.max_m, p.total_qt,
                                  p.max_kv_end + pos_add, Hq, Hkv, D, l, s->n_pages, s->pps, scr, (bf16_t*)s->AO, L.o.ktiles()));
       o = GemmOut(); o.Y = s->X; o.ldy = d; o.nout = nout; o.nout.g = g2;
-      KF(KF_GEMM_O, bf16_gemm(st, EPI_ADD, Wo, L.o.ntiles(), L.o.ktiles(), (const bf16_t*)s->AO, M, L.o.N, o));
+      KF(KF_GEMM_O, gemm(s, EPI_ADD, L.o, (const bf16_t*)s->AO, M, o));
       o = GemmOut(); o.H = (bf16_t*)s->H; o.h_ktiles = L.down.ktiles(); o.nin = nin;
-      KF(KF_GEMM_GU, bf16_gemm(st, EPI_SWIGLU, Wgu, L.gu.ntiles(), L.gu.ktiles(), (const bf16_t*)s->XN, M, L.gu.N, o));
+      KF(KF_GEMM_GU, gemm(s, EPI_SWIGLU, L.gu, (const bf16_t*)s->XN, M, o));
       // the down projection leaves the operand of whatever reads the stream next: the next layer's QKV
       // projection, or the shared exit head behind the last layer of the pass
       o = GemmOut(); o.Y = s->X; o.ldy = d; o.nout = nout;
       o.nout.g = l + 1 < l1 ? (const float*)(m->base + m->L[l + 1].g1) : (const float*)(m->base + m->gfinal);
-      KF(KF_GEMM_DOWN, bf16_gemm(st, EPI_ADD, Wd, L.down.ntiles(), L.down.ktiles(), (const bf16_t*)s->H, M, L.down.N, o));
+      KF(KF_GEMM_DOWN, gemm(s, EPI_ADD, L.down, (const bf16_t*)s->H, M, o));
     } else {
       const float* Wqkv = (const float*)(m->base + L.qkv.off);
       const float* Wo = (const float*)(m->base + L.o.off);
@@ -376,8 +390,7 @@ static void exit_head(ee_session* s, int M) {
     o.nin.ssq = s->ssq; o.nin.n_part = c.d_model / 16; o.nin.stride = Mp; o.nin.inv_d = 1.0f / (float)c.d_model; o.nin.eps = c.rms_eps;
     o.pmax = s->pmax; o.pidx = s->pidx; o.pstride = Mp;
     if (s->debug_logits) { o.Y = s->LOGITS; o.ldy = c.vocab; }
-    KF(KF_GEMM_HEAD, bf16_gemm(st, EPI_ARGMAX, (const bf16_t*)(m->base + m->head.off), m->head.ntiles(), m->head.ktiles(),
-                               (const bf16_t*)s->XN, M, c.vocab, o));
+    KF(KF_GEMM_HEAD, gemm(s, EPI_ARGMAX, m->head, (const bf16_t*)s->XN, M, o));
     KF(KF_ARGMAX, bf16_argmax_reduce(st, s->pmax, s->pidx, m->head.ntiles(), Mp, M, s->vtok));
   } else {
     KF(KF_NORM, f32_rmsnorm(st, s->X, gf, c.rms_eps, (float*)s->XN, M, c.d_model));

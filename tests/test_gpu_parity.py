@@ -175,6 +175,9 @@ CASES = [
     ("bf16_small_nobonus", bf16_small(), [33, 130], 5, (False, False)),
     ("bf16_d128", bf16_d128(), [100, 260], 8, (True, True)),
     ("bf16_d128_k16", bf16_d128(), [300], 16, (True, True)),
+    # more than 64 block rows in one call: the row-tiled GEMM (8 and 12 row tiles), ragged contexts
+    ("bf16_small_batch10", bf16_small(), [70, 5, 200, 64, 33, 129, 17, 90, 150, 260], 8, (True, True)),
+    ("bf16_d128_batch16", bf16_d128(), [100, 260, 31, 64, 65, 7, 190, 128, 40, 77, 300, 12, 55, 201, 99, 160], 8, (True, True)),
 ]
 
 
