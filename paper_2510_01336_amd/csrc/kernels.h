@@ -73,11 +73,11 @@ void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kt
                     const GemmOut& out, float* scratch, float* inv_rms);
 void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf16_t* out, int ktiles, int M, int d);
 struct AttnScratch { float* part_o; float* part_ml; int max_splits; };
+// pages each KV split takes, chosen from the call's sequence ends (kv_end[b] = first position past the
+// block, 0 for a sequence not taking part) so that a ragged batch is cut into equal workgroups
+int bf16_attention_pages_per_split(const int* kv_end, const int* seq_m, int B, int Hq, int Hkv, int max_splits);
+// per = pages per KV split (ceil(max pages / per) must not exceed scr.max_splits)
 void bf16_attention(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,
                     int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
-                    const AttnScratch& scr, bf16_t* out, int out_ktiles);
-// same with an explicit number of KV splits (<= 0: chosen from the shape; must not exceed scr.max_splits)
-void bf16_attention_cfg(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,
-                        int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
-                        const AttnScratch& scr, bf16_t* out, int out_ktiles, int nsplit);
+                    const AttnScratch& scr, bf16_t* out, int out_ktiles, int per);
 void bf16_argmax_reduce(hipStream_t st, const float* pmax, const int* pidx, int ntiles, int pstride, int M, int* v);

@@ -677,6 +677,17 @@ void bf16_argmax_reduce(hipStream_t st, const float* pmax, const int* pidx, int 
 // With one split the normalised output goes straight to the O-projection operand; otherwise the
 // partials (max, sum, unnormalised O) go to scratch and attn_merge_kernel combines them.
 // ---------------------------------------------------------------------------------------------
+// maximum over the four 16-lane rows of a wave, delivered to every lane: lane l ends up with
+// max(x[l % 16 + 16 r], r = 0..3).  v_permlane16_swap exchanges the odd rows of its first operand with the
+// even rows of its second, v_permlane32_swap the upper half of the first with the lower half of the second.
+__device__ inline float colmax4(float x) {
+  typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+  u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 #define EE_MAX_SPLITS 64
 #define EE_ATTN_WAVES 8
 #define EE_ATTN_COMPUTE 6   // compute waves = q-tiles per workgroup; the other waves load
@@ -687,7 +698,7 @@ __global__ __launch_bounds__(64 * EE_ATTN_WAVES) void attn_kernel(const uint4* _
                                                                   const int* seq_m, const int* seq_p0, const int* seq_qt0,
                                                                   const int* seq_row0, const int* block_table, int pos_add, int rep,
                                                                   int total_qt, int Hkv, int layer, int n_pages, int pps, int nsplit,
-                                                                  float* part_o, float* part_ml, bf16_t* __restrict__ out,
+                                                                  int per, float* part_o, float* part_ml, bf16_t* __restrict__ out,
                                                                   int out_ktiles) {
   constexpr int DS = D / 32, DT = D / 16;
   constexpr int KCH = 4 * DS, CH = KCH + 2 * DT;       // 1 KiB chunks of a page: K first, then V
@@ -697,16 +708,26 @@ __global__ __launch_bounds__(64 * EE_ATTN_WAVES) void attn_kernel(const uint4* _
   __shared__ u32x4 lds[3][CH * 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, qc = lane & 15;
   const int b = blockIdx.z, kvh = blockIdx.y % Hkv, sp = blockIdx.x;
-  const int m = seq_m[b];
+  const int pg0 = sp * per;                            // every split takes `per` pages: a short sequence has fewer splits
+  const int* bt = block_table + b * pps;
+  // every scalar the workgroup needs before its first KV fetch is requested ahead of the first branch,
+  // so the prologue costs one memory round trip, not one per dependent step (indices clamped into the table)
+  int m = seq_m[b], sp0 = seq_p0[b], sqt0 = seq_qt0[b];
+  int bt0[EE_ATTN_AHEAD];
+#pragma unroll
+  for (int q = 0; q < EE_ATTN_AHEAD; ++q) bt0[q] = bt[min(pg0 + q, pps - 1)];
+  static_assert(EE_ATTN_AHEAD == 3, "the statement below names the look-ahead entries one by one");
+  // ties the values together ahead of the branches (not volatile and without a memory clobber, so later
+  // table lookups stay scalar loads)
+  asm("" : "+s"(m), "+s"(sp0), "+s"(sqt0), "+s"(bt0[0]), "+s"(bt0[1]), "+s"(bt0[2]));
   if (m == 0) return;                                  // whole workgroup
   const int nq = m * rep;
   const int qt0 = (blockIdx.y / Hkv) * (EE_ATTN_COMPUTE * QPW);
   if (qt0 * 16 >= nq) return;                          // whole workgroup
-  const int p0 = seq_p0[b] + pos_add, kv_end = p0 + m;
+  const int p0 = sp0 + pos_add, kv_end = p0 + m;
   const int npages = (kv_end + EE_PAGE - 1) / EE_PAGE;
-  const int per = (npages + nsplit - 1) / nsplit;
-  const int pg0 = sp * per, pg1 = min(npages, pg0 + per);
-  const int* bt = block_table + b * pps;
+  const int pg1 = min(npages, pg0 + per);
+  if (pg0 >= npages) return;                           // whole workgroup; the merge pass knows this sequence's split count
 
   const bool loader = wave >= EE_ATTN_COMPUTE;
   const int lw = wave - EE_ATTN_COMPUTE;
@@ -721,7 +742,7 @@ __global__ __launch_bounds__(64 * EE_ATTN_WAVES) void attn_kernel(const uint4* _
     has[i] = !loader && qt * 16 < nq;
     const int qrow = qt * 16 + qc;
     limit[i] = (has[i] && qrow < nq) ? p0 + qrow / rep : -1;
-    const int gqt = seq_qt0[b] + (has[i] ? qt : 0);
+    const int gqt = sqt0 + (has[i] ? qt : 0);
 #pragma unroll
     for (int s = 0; s < DS; ++s) qf[i][s] = ((const u32x4*)Q)[(((size_t)kvh * total_qt + gqt) * DS + s) * 64 + lane];
     mrun[i] = -INFINITY; lacc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -730,9 +751,9 @@ __global__ __launch_bounds__(64 * EE_ATTN_WAVES) void attn_kernel(const uint4* _
   }
   // loader side: st[q] holds this wave's chunks (lw, lw + NL, ...) of the page q pages ahead (mod PF)
   u32x4 st[PF][CPL];
-#define ATTN_FETCH(q_, pg_)                                                                                  \
+#define ATTN_FETCH(q_, page_)                                                                                \
   do {                                                                                                       \
-    const u32x4* src_ = (const u32x4*)(kv + kv_slab(layer, bt[pg_], kvh, n_pages, Hkv, D)) + lw * 64 + lane; \
+    const u32x4* src_ = (const u32x4*)(kv + kv_slab(layer, page_, kvh, n_pages, Hkv, D)) + lw * 64 + lane;   \
     _Pragma("unroll") for (int j = 0; j < CPL; ++j) st[q_][j] = __builtin_nontemporal_load(src_ + j * NL * 64); \
   } while (0)
 #define ATTN_DEPOSIT(buf_, q_)                                                                               \
@@ -775,8 +796,8 @@ __global__ __launch_bounds__(64 * EE_ATTN_WAVES) void attn_kernel(const uint4* _
   };
   auto step = [&](auto tail_c, auto prev_c, int slot, int pslot, int pg) __attribute__((always_inline)) {
     constexpr bool TAIL = decltype(tail_c)::value, PREV = decltype(prev_c)::value;
-    const u32x4* L = lds[slot] + lane;
-    const u32x4* Lp = lds[pslot] + lane;
+    const u32x4* L = &lds[0][0] + slot * (CH * 64) + lane;     // the slot is a run-time value: one loop body serves the whole ring
+    const u32x4* Lp = &lds[0][0] + pslot * (CH * 64) + lane;
     const int base = pg * EE_PAGE + 16 * g;          // this lane group holds positions base .. base+15
     u32x4 kf[4 * DS];
 #pragma unroll
@@ -807,48 +828,40 @@ __global__ __launch_bounds__(64 * EE_ATTN_WAVES) void attn_kernel(const uint4* _
         tmax = fmaxf(tmax, s4[t][v]);
       }
     tmax *= sc2;
-    // the running maximum only has to be an upper bound shared by the four lane groups of a column:
-    // the cross-lane reduction and the rescaling run only when some score of the wave exceeds it
-    if (__builtin_amdgcn_ballot_w64(tmax > mrun[0]) != 0) {
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float mnew = fmaxf(mrun[0], tmax);
-      const float alpha = __builtin_amdgcn_exp2f(mrun[0] - (mnew == -INFINITY ? 0.f : mnew));
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) { o[0][dt][0] *= alpha; o[0][dt][1] *= alpha; o[0][dt][2] *= alpha; o[0][dt][3] *= alpha; }
-      lacc[0][0] *= alpha; lacc[0][1] *= alpha; lacc[0][2] *= alpha; lacc[0][3] *= alpha;
-      mrun[0] = mnew;
-    }
-    const float nm = mrun[0] == -INFINITY ? 0.f : -mrun[0];
+    // running maximum of the column, shared by the four lane groups that hold its positions (two
+    // register swaps across lane rows, no LDS traffic).  Everything up to the packed weights is
+    // straight-line code, so the exponentials can be scheduled under the MFMAs; only the rescaling of
+    // the accumulators, which is rare once the maximum has settled, sits behind a branch at the end.
+    tmax = colmax4(tmax);
+    const float mnew = fmaxf(mrun[0], tmax);
+    const float msafe = mnew == -INFINITY ? 0.f : mnew;
+    const float alpha = __builtin_amdgcn_exp2f(mrun[0] - msafe);
+    mrun[0] = mnew;
+    const float nm = -msafe;
     uint32_t pk[8];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       pk[2 * t] = pack2(__builtin_amdgcn_exp2f(fmaf(s4[t][0], sc2, nm)), __builtin_amdgcn_exp2f(fmaf(s4[t][1], sc2, nm)));
       pk[2 * t + 1] = pack2(__builtin_amdgcn_exp2f(fmaf(s4[t][2], sc2, nm)), __builtin_amdgcn_exp2f(fmaf(s4[t][3], sc2, nm)));
     }
+    // (the empty statement pins the weights ahead of the branch: otherwise the exponentials are sunk
+    // below it, out of the block that holds the MFMAs)
+    asm volatile("" : "+v"(pk[0]), "+v"(pk[1]), "+v"(pk[2]), "+v"(pk[3]), "+v"(pk[4]), "+v"(pk[5]), "+v"(pk[6]), "+v"(pk[7]));
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) { o[0][dt][0] *= alpha; o[0][dt][1] *= alpha; o[0][dt][2] *= alpha; o[0][dt][3] *= alpha; }
+      lacc[0][0] *= alpha; lacc[0][1] *= alpha; lacc[0][2] *= alpha; lacc[0][3] *= alpha;
+    }
     Pp0 = u32x4{pk[0], pk[1], pk[2], pk[3]};   // positions base+0..7  (pos-tiles 0, 1)
     Pp1 = u32x4{pk[4], pk[5], pk[6], pk[7]};   // positions base+8..15 (pos-tiles 2, 3)
   };
   auto pv_last = [&](auto tail_c, int pslot, int ppg) __attribute__((always_inline)) {
-    const u32x4* Lp = lds[pslot] + lane;
+    const u32x4* Lp = &lds[0][0] + pslot * (CH * 64) + lane;
     u32x4 vf[2 * DT];
 #pragma unroll
     for (int c = 0; c < 2 * DT; ++c) vf[c] = Lp[(KCH + c) * 64];
     pv_mfma(tail_c, vf, ppg);
   };
-  // u = page offset mod 3 = ring slot; the first page of the split has no predecessor
-  auto compute_page = [&](int u, int pg) __attribute__((always_inline)) {
-    const int pslot = (u + 2) % 3;
-    const bool tail = pg * EE_PAGE + EE_PAGE > p0;   // page pg-1 of a non-tail page is never a tail page either
-    if (pg == pg0) {
-      if (tail) step(std::true_type{}, std::false_type{}, u, pslot, pg);
-      else step(std::false_type{}, std::false_type{}, u, pslot, pg);
-    } else {
-      if (tail) step(std::true_type{}, std::true_type{}, u, pslot, pg);
-      else step(std::false_type{}, std::true_type{}, u, pslot, pg);
-    }
-  };
-
   // software pipeline over a ring of three LDS slots (slot = page offset mod 3): while the compute waves
   // work on page p (scores) and p-1 (P.V), the loaders drop page p+1 into the third slot and request
   // page p+1+PF; every wave passes one barrier per page
@@ -862,60 +875,76 @@ __global__ __launch_bounds__(64 * EE_ATTN_WAVES) void attn_kernel(const uint4* _
     int pg = pg0;
     if (pg0 + 2 * PF < pg1) {
 #pragma unroll
-      for (int q = 0; q < PF; ++q) ATTN_FETCH(q, pg0 + q);
+      for (int q = 0; q < PF; ++q) ATTN_FETCH(q, bt0[q]);
       ATTN_DEPOSIT(0, 0);
-      ATTN_FETCH(0, pg0 + PF);
+      ATTN_FETCH(0, bt[pg0 + PF]);
       __syncthreads();
       for (; pg + 2 * PF < pg1; pg += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
           ATTN_DEPOSIT((u + 1) % 3, (u + 1) % PF);
-          ATTN_FETCH((u + 1) % PF, pg + u + 1 + PF);
+          ATTN_FETCH((u + 1) % PF, bt[pg + u + 1 + PF]);
           __syncthreads();
         }
       }
     } else {
 #pragma unroll
       for (int q = 0; q < PF; ++q)
-        if (pg0 + q < pg1) ATTN_FETCH(q, pg0 + q);
+        if (pg0 + q < pg1) ATTN_FETCH(q, bt0[q]);
       if (pg0 < pg1) ATTN_DEPOSIT(0, 0);
-      if (pg0 + PF < pg1) ATTN_FETCH(0, pg0 + PF);
+      if (pg0 + PF < pg1) ATTN_FETCH(0, bt[pg0 + PF]);
       __syncthreads();
     }
-    for (; pg < pg1; pg += PF) {     // guarded tail (and short splits)
+    for (; pg < pg1; pg += PF) {     // guarded tail (and short splits): one barrier per remaining page
 #pragma unroll
       for (int u = 0; u < PF; ++u) {
         const int p = pg + u;
+        if (p >= pg1) break;
         if (p + 1 < pg1) ATTN_DEPOSIT((u + 1) % 3, (u + 1) % PF);
-        if (p + 1 + PF < pg1) ATTN_FETCH((u + 1) % PF, p + 1 + PF);
+        if (p + 1 + PF < pg1) ATTN_FETCH((u + 1) % PF, bt[p + 1 + PF]);
         __syncthreads();
       }
     }
-  } else {
-    __syncthreads();
-    for (int pg = pg0; pg < pg1; pg += PF) {
-#pragma unroll
-      for (int u = 0; u < PF; ++u) {
-        const int p = pg + u;
-        if (p < pg1 && has[0]) compute_page(u, p);
-        __syncthreads();
-      }
-    }
+    return;
   }
 #undef ATTN_FETCH
 #undef ATTN_DEPOSIT
-  if (loader) return;
-  static_assert(PF == 3 && QPW == 1, "the page loop is unrolled by the ring size");
-  if (has[0] && pg0 < pg1) {    // P.V of the split's last page (its slot is not written again)
-    const int last = pg1 - 1, u = (last - pg0) % 3;
-    if (last * EE_PAGE + EE_PAGE > p0) pv_last(std::true_type{}, u, last);
-    else pv_last(std::false_type{}, u, last);
+  static_assert(PF == 3 && QPW == 1, "three ring slots, one q-tile per compute wave");
+  // Compute side: 1 + (pg1 - pg0) barriers like the loaders.  The page loop is cut into three plain loops
+  // (first page, pages wholly before the block, pages reaching into it) whose bodies are one step
+  // variant each, so the accumulators stay in place: no variant merges inside the steady-state loop.
+  __syncthreads();
+  if (!has[0]) {
+    for (int pg = pg0; pg < pg1; ++pg) __syncthreads();
+    return;
+  }
+  {
+    const int first_tail = p0 / EE_PAGE;       // pages from here on reach into the block or past the end
+    int pg = pg0, slot = 0, pslot = 2;
+    if (pg >= first_tail) step(std::true_type{}, std::false_type{}, slot, pslot, pg);
+    else step(std::false_type{}, std::false_type{}, slot, pslot, pg);
+    __syncthreads();
+    pslot = 0; slot = 1; ++pg;
+    const int pe = min(pg1, first_tail);
+    for (; pg < pe; ++pg) {
+      step(std::false_type{}, std::true_type{}, slot, pslot, pg);
+      __syncthreads();
+      pslot = slot; slot = slot == 2 ? 0 : slot + 1;
+    }
+    for (; pg < pg1; ++pg) {
+      step(std::true_type{}, std::true_type{}, slot, pslot, pg);
+      __syncthreads();
+      pslot = slot; slot = slot == 2 ? 0 : slot + 1;
+    }
+    // P.V of the split's last page (its slot is not written again)
+    if (pg1 > first_tail) pv_last(std::true_type{}, pslot, pg1 - 1);
+    else pv_last(std::false_type{}, pslot, pg1 - 1);
   }
 
 #pragma unroll
   for (int i = 0; i < QPW; ++i) {
     if (!has[i]) continue;
-    const int qt = qt0 + wave * QPW + i, gqt = seq_qt0[b] + qt, qrow = qt * 16 + qc;
+    const int qt = qt0 + wave * QPW + i, gqt = sqt0 + qt, qrow = qt * 16 + qc;
     const float l = lacc[i][0];
     if (nsplit == 1) {
       if (qrow < nq) {
@@ -938,105 +967,136 @@ __global__ __launch_bounds__(64 * EE_ATTN_WAVES) void attn_kernel(const uint4* _
 }
 
 // merge the KV splits of one (q-tile, KV head) and emit the bf16 attention output in fragment layout
-// (O-projection operand).  Four waves, each taking a quarter of the head dimension; every lane owns the
-// same accumulator elements the split kernel's lanes did, so partials are read as coalesced float4.
-// Loads go out in batches so the merge costs a few L2 round trips, not one per split.
+// (O-projection operand).  Workgroup = (q-tile, KV head, pair of d-tiles); its four waves share out the
+// splits (wave w takes w, w+4, ...), each folding its share with all loads of a batch of eight splits in
+// flight at once, and the four wave results meet in LDS.  Every lane owns the accumulator elements the
+// split kernel's lanes did, so partials are read as coalesced float4.
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                                                          const int* qt_seq, const int* qt_local, const int* seq_m,
-                                                         const int* seq_row0, int rep, int Hkv, int nsplit,
-                                                         bf16_t* __restrict__ out, int out_ktiles) {
-  constexpr int DT = D / 16, DW = DT / 4;    // d-tiles per wave
+                                                         const int* seq_p0, const int* seq_row0, int pos_add, int rep, int Hkv,
+                                                         int slot_stride, int per, bf16_t* __restrict__ out, int out_ktiles) {
+  constexpr int DT = D / 16, DW = 2;         // d-tiles per workgroup; gridDim.z = DT / DW
+  __shared__ float sm[4][64], sd[4][64];
+  __shared__ f32x4 sacc[4][DW][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, qc = lane & 15;
-  const int gqt = blockIdx.x, kvh = blockIdx.y;
+  const int gqt = blockIdx.x, kvh = blockIdx.y, dq = blockIdx.z;
   const int b = qt_seq[gqt], qt = qt_local[gqt];
   const int nq = seq_m[b] * rep, qrow = qt * 16 + qc;
-  const size_t slot0 = ((size_t)gqt * Hkv + kvh) * nsplit;
+  const int npages = (seq_p0[b] + pos_add + seq_m[b] + EE_PAGE - 1) / EE_PAGE;
+  const int nsplit = (npages + per - 1) / per;          // this sequence's split count
+  const size_t slot0 = ((size_t)gqt * Hkv + kvh) * slot_stride;
   const float2* ml = (const float2*)(part_ml + slot0 * 32) + qc;
-  float mall = -INFINITY, den = 0.f;
-  for (int s0 = 0; s0 < nsplit; s0 += 8) {
-    float2 t[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) t[i] = s0 + i < nsplit ? ml[(s0 + i) * 16] : make_float2(-INFINITY, 0.f);
-    float bm = mall;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) bm = fmaxf(bm, t[i].x);
-    const float safe = bm == -INFINITY ? 0.f : bm;
-    den *= __builtin_amdgcn_exp2f(mall - safe);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) den += __builtin_amdgcn_exp2f(t[i].x - safe) * t[i].y;
-    mall = bm;
-  }
-  const float msafe = mall == -INFINITY ? 0.f : mall;
-  const float inv = 1.0f / den;
+  const f32x4* pi = (const f32x4*)part_o + slot0 * (DT * 64) + (size_t)dq * DW * 64 + lane;
+  float mw = -INFINITY, den = 0.f;
   f32x4 acc[DW];
 #pragma unroll
   for (int j = 0; j < DW; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const f32x4* pi = (const f32x4*)part_o + slot0 * (DT * 64) + (size_t)wave * DW * 64 + lane;
-  for (int s0 = 0; s0 < nsplit; s0 += 8) {
+  for (int s0 = wave; s0 < nsplit; s0 += 32) {
     float2 t[8];
     f32x4 ov[8][DW];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int sl = min(s0 + i, nsplit - 1);
+      const int sl = min(s0 + 4 * i, nsplit - 1);
       t[i] = ml[sl * 16];
 #pragma unroll
       for (int j = 0; j < DW; ++j) ov[i][j] = __builtin_nontemporal_load(pi + ((size_t)sl * DT + j) * 64);
     }
+    float bm = mw;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bm = fmaxf(bm, s0 + 4 * i < nsplit ? t[i].x : -INFINITY);
+    const float safe = bm == -INFINITY ? 0.f : bm;
+    const float sc = __builtin_amdgcn_exp2f(mw - safe);
+    den *= sc;
+#pragma unroll
+    for (int j = 0; j < DW; ++j) { acc[j][0] *= sc; acc[j][1] *= sc; acc[j][2] *= sc; acc[j][3] *= sc; }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const float w = s0 + i < nsplit ? __builtin_amdgcn_exp2f(t[i].x - msafe) * inv : 0.f;
+      const float w = s0 + 4 * i < nsplit ? __builtin_amdgcn_exp2f(t[i].x - safe) : 0.f;
+      den += w * t[i].y;
 #pragma unroll
       for (int j = 0; j < DW; ++j) { acc[j][0] += w * ov[i][j][0]; acc[j][1] += w * ov[i][j][1]; acc[j][2] += w * ov[i][j][2]; acc[j][3] += w * ov[i][j][3]; }
     }
+    mw = bm;
+  }
+  sm[wave][lane] = mw; sd[wave][lane] = den;
+#pragma unroll
+  for (int j = 0; j < DW; ++j) sacc[wave][j][lane] = acc[j];
+  __syncthreads();
+  if (wave != 0) return;
+  float mall = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) mall = fmaxf(mall, sm[w][lane]);
+  const float msafe = mall == -INFINITY ? 0.f : mall;
+  den = 0.f;
+#pragma unroll
+  for (int j = 0; j < DW; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {        // fixed order: the result does not depend on timing
+    const float f = __builtin_amdgcn_exp2f(sm[w][lane] - msafe);
+    den += f * sd[w][lane];
+#pragma unroll
+    for (int j = 0; j < DW; ++j) {
+      const f32x4 a = sacc[w][j][lane];
+      acc[j][0] += f * a[0]; acc[j][1] += f * a[1]; acc[j][2] += f * a[2]; acc[j][3] += f * a[3];
+    }
   }
   if (qrow < nq) {
-    const int row = seq_row0[b] + qrow / rep, col0 = (kvh * rep + qrow % rep) * D + wave * DW * 16 + 4 * g;
+    const float inv = 1.0f / den;
+    const int row = seq_row0[b] + qrow / rep, col0 = (kvh * rep + qrow % rep) * D + dq * DW * 16 + 4 * g;
 #pragma unroll
     for (int j = 0; j < DW; ++j)
-      *(uint2*)(out + frag_offset(row, col0 + j * 16, out_ktiles)) = make_uint2(pack2(acc[j][0], acc[j][1]), pack2(acc[j][2], acc[j][3]));
+      *(uint2*)(out + frag_offset(row, col0 + j * 16, out_ktiles)) =
+          make_uint2(pack2(acc[j][0] * inv, acc[j][1] * inv), pack2(acc[j][2] * inv, acc[j][3] * inv));
   }
 }
 
-// number of KV splits: about two workgroups per compute unit when the context allows, at least four
-// pages per split (the software pipeline's depth)
-static int attn_default_splits(int B, int Hkv, int qt_groups, int max_pages, int max_splits) {
-  int nsplit = ceil_div(512, max(1, B * Hkv * qt_groups));
-  return max(1, min(nsplit, min(ceil_div(max_pages, 4), min(max_splits, EE_MAX_SPLITS))));
+// Pages per KV split.  Every split of every sequence takes the same number of pages, so that a ragged
+// batch is cut into workgroups of equal length; the count is the smallest one (>= 4, the software
+// pipeline's depth) that keeps the launch within one workgroup per compute unit (the LDS ring admits
+// one resident workgroup, so a second round would start cold).  kv_end[b] = 0: sequence not taking part.
+int bf16_attention_pages_per_split(const int* kv_end, const int* seq_m, int B, int Hq, int Hkv, int max_splits) {
+  const int rep = Hq / Hkv;
+  int max_pages = 1;
+  for (int b = 0; b < B; ++b) max_pages = max(max_pages, ceil_div(kv_end[b], EE_PAGE));
+  int per = max(4, ceil_div(max_pages, max(1, min(max_splits, EE_MAX_SPLITS))));
+  for (; per < max_pages; ++per) {
+    long wgs = 0;
+    for (int b = 0; b < B; ++b)
+      if (kv_end[b] > 0)
+        wgs += (long)ceil_div(ceil_div(kv_end[b], EE_PAGE), per) * Hkv * ceil_div(ceil_div(seq_m[b] * rep, 16), EE_ATTN_COMPUTE);
+    if (wgs <= 256) break;
+  }
+  return min(per, max_pages);
 }
 
 template <int D, int QPW>
 static void launch_attn(hipStream_t st, dim3 grid, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int rep,
-                        int total_qt, int Hkv, int layer, int n_pages, int pps, int nsplit, const AttnScratch& scr, bf16_t* out,
-                        int out_ktiles) {
+                        int total_qt, int Hkv, int layer, int n_pages, int pps, int nsplit, int per, const AttnScratch& scr,
+                        bf16_t* out, int out_ktiles) {
   hipLaunchKernelGGL((attn_kernel<D, QPW>), grid, dim3(64 * EE_ATTN_WAVES), 0, st, (const uint4*)Q, kv, meta.seq_m, meta.seq_p0,
-                     meta.seq_qt0, meta.seq_row0, meta.block_table, pos_add, rep, total_qt, Hkv, layer, n_pages, pps, nsplit,
+                     meta.seq_qt0, meta.seq_row0, meta.block_table, pos_add, rep, total_qt, Hkv, layer, n_pages, pps, nsplit, per,
                      scr.part_o, scr.part_ml, out, out_ktiles);
-}
-
-void bf16_attention_cfg(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,
-                        int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
-                        const AttnScratch& scr, bf16_t* out, int out_ktiles, int nsplit) {
-  const int rep = Hq / Hkv;
-  const int max_qt = ceil_div(max_m * rep, 16);
-  const int qt_groups = ceil_div(max_qt, EE_ATTN_COMPUTE);
-  if (nsplit <= 0) nsplit = attn_default_splits(B, Hkv, qt_groups, ceil_div(max_kv_end, EE_PAGE), scr.max_splits);
-  dim3 grid(nsplit, Hkv * qt_groups, B);
-  if (D == 128) launch_attn<128, 1>(st, grid, Q, kv, meta, pos_add, rep, total_qt, Hkv, layer, n_pages, pages_per_seq, nsplit, scr, out, out_ktiles);
-  else launch_attn<64, 1>(st, grid, Q, kv, meta, pos_add, rep, total_qt, Hkv, layer, n_pages, pages_per_seq, nsplit, scr, out, out_ktiles);
-  if (nsplit > 1) {
-    if (D == 128)
-      hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(total_qt, Hkv), dim3(256), 0, st, scr.part_o, scr.part_ml, meta.qt_seq,
-                         meta.qt_local, meta.seq_m, meta.seq_row0, rep, Hkv, nsplit, out, out_ktiles);
-    else
-      hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(total_qt, Hkv), dim3(256), 0, st, scr.part_o, scr.part_ml, meta.qt_seq,
-                         meta.qt_local, meta.seq_m, meta.seq_row0, rep, Hkv, nsplit, out, out_ktiles);
-  }
 }
 
 void bf16_attention(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const CallMeta& meta, int pos_add, int B, int max_m,
                     int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
-                    const AttnScratch& scr, bf16_t* out, int out_ktiles) {
-  bf16_attention_cfg(st, Q, kv, meta, pos_add, B, max_m, total_qt, max_kv_end, Hq, Hkv, D, layer, n_pages, pages_per_seq, scr, out,
-                     out_ktiles, 0);
+                    const AttnScratch& scr, bf16_t* out, int out_ktiles, int per) {
+  const int rep = Hq / Hkv;
+  const int max_qt = ceil_div(max_m * rep, 16);
+  const int qt_groups = ceil_div(max_qt, EE_ATTN_COMPUTE);
+  const int max_pages = ceil_div(max_kv_end, EE_PAGE);
+  per = max(1, min(per, max_pages));
+  const int nsplit = ceil_div(max_pages, per);       // grid width and stride of the partial slots
+  dim3 grid(nsplit, Hkv * qt_groups, B);
+  if (D == 128) launch_attn<128, 1>(st, grid, Q, kv, meta, pos_add, rep, total_qt, Hkv, layer, n_pages, pages_per_seq, nsplit, per, scr, out, out_ktiles);
+  else launch_attn<64, 1>(st, grid, Q, kv, meta, pos_add, rep, total_qt, Hkv, layer, n_pages, pages_per_seq, nsplit, per, scr, out, out_ktiles);
+  if (nsplit > 1) {
+    if (D == 128)
+      hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(total_qt, Hkv, 4), dim3(256), 0, st, scr.part_o, scr.part_ml, meta.qt_seq,
+                         meta.qt_local, meta.seq_m, meta.seq_p0, meta.seq_row0, pos_add, rep, Hkv, nsplit, per, out, out_ktiles);
+    else
+      hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(total_qt, Hkv, 2), dim3(256), 0, st, scr.part_o, scr.part_ml, meta.qt_seq,
+                         meta.qt_local, meta.seq_m, meta.seq_p0, meta.seq_row0, pos_add, rep, Hkv, nsplit, per, out, out_ktiles);
+  }
 }

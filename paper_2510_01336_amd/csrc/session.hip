@@ -327,6 +327,14 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
   const int d = c.d_model, D = c.head_dim, Hq = c.n_q_heads, Hkv = c.n_kv_heads, M = p.M;
   hipStream_t st = s->st;
   KF(KF_ROPE, k_rope_table(st, mt.row_pos, pos_add, m->inv_freq, s->cs, M, D / 2));
+  // attention split plan of this call (the same for all its layers)
+  AttnScratch scr{s->part_o, s->part_ml, (int)std::min<size_t>(s->max_splits, s->part_units / std::max(1, p.total_qt))};
+  int per = 1;
+  if (m->bf16) {
+    std::vector<int> kv_end(s->B);
+    for (int b = 0; b < s->B; ++b) kv_end[b] = p.m[b] > 0 ? p.p0[b] + p.m[b] + pos_add : 0;
+    per = bf16_attention_pages_per_split(kv_end.data(), p.m.data(), s->B, Hq, Hkv, scr.max_splits);
+  }
   for (int l = l0; l < l1; ++l) {
     const LayerLoc& L = m->L[l];
     const float* g1 = (const float*)(m->base + L.g1);
@@ -346,9 +354,8 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
       R.block_table = mt.block_table; R.pos_add = pos_add; R.Hq = Hq; R.Hkv = Hkv; R.D = D; R.layer = l;
       R.n_pages = s->n_pages; R.pps = s->pps; R.total_qt = p.total_qt; R.Q = (bf16_t*)s->Qb; R.kv = (bf16_t*)s->kv;
       KF(KF_GEMM_QKV, gemm(s, EPI_ROPE, L.qkv, (const bf16_t*)s->XN, M, o));
-      AttnScratch scr{s->part_o, s->part_ml, (int)std::min<size_t>(s->max_splits, s->part_units / std::max(1, p.total_qt))};
       KF(KF_ATTN, bf16_attention(st, (const bf16_t*)s->Qb, (const bf16_t*)s->kv, mt, pos_add, s->B, p.max_m, p.total_qt,
-                                 p.max_kv_end + pos_add, Hq, Hkv, D, l, s->n_pages, s->pps, scr, (bf16_t*)s->AO, L.o.ktiles()));
+                                 p.max_kv_end + pos_add, Hq, Hkv, D, l, s->n_pages, s->pps, scr, (bf16_t*)s->AO, L.o.ktiles(), per));
       o = GemmOut(); o.Y = s->X; o.ldy = d; o.nout = nout; o.nout.g = g2;
       KF(KF_GEMM_O, gemm(s, EPI_ADD, L.o, (const bf16_t*)s->AO, M, o));
       o = GemmOut(); o.H = (bf16_t*)s->H; o.h_ktiles = L.down.ktiles(); o.nin = nin;
