@@ -377,24 +377,36 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 // meets up to 16 row tiles, so the kernel sits near the machine's ridge (M flop per weight byte).
 // Workgroup = 4 waves on a group of 8 weight tiles (128 output features) and a share of K (grid.y);
 // wave (rh, nh) owns 4 of the tiles and half of the TMT row tiles: 2*TMT accumulators.
-//   weights      HBM -> registers, a rolling ring three k-tiles deep per wave
-//   activations  L2 -> registers (two k-tiles ahead) -> a two-slot LDS ring shared by the four waves
-// The steady-state loop is free of branches around its loads (indices past the end are clamped and
-// only the MFMAs are guarded), so the in-order load counters never force a full drain.
+// Both operands reach LDS by direct global->LDS loads (no staging registers, no LDS store
+// instructions): a ring of S stages, one k-tile each (8 KiB of weights + TMT KiB of activations), as many
+// as LDS holds, of which up to S-2 are in flight: that is what covers the HBM latency with one workgroup
+// per compute unit.  Each wave requests a quarter of every stage; per k-tile it waits until its own share
+// of the next stage has landed (the load counter is in order), meets the other waves at a barrier --
+// which also says that everyone is past the MFMAs of the previous stage, whose slot the next request then
+// overwrites -- reads the next stage's fragments (1 KiB, lane-linear, conflict-free) into the second
+// register set and runs the 2*TMT MFMAs of the current one under them.  The loop is unrolled over the ring
+// so that every LDS address is a constant, and indices past the end are clamped (only the MFMAs are guarded).
 // With grid.y == 1 the epilogue is fused; otherwise fp32 partial tiles go to scratch and
 // gemm_rows_reduce_kernel sums the K shares in a fixed order and runs the same epilogue.
 // ---------------------------------------------------------------------------------------------
 #define EE_ROWS_TN 4
+// s_waitcnt immediate: at most n vector-memory loads outstanding, all LDS reads done, export counter untouched
+__host__ __device__ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
+
 template <int TMT, int EPI>
 __global__ __launch_bounds__(256) void gemm_rows_kernel(const uint4* __restrict__ W, int ktiles, int ntiles,
                                                         const uint4* __restrict__ A, int M, int N, GemmOut out,
                                                         int per, float* __restrict__ partial) {
   constexpr int TN = EE_ROWS_TN, NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
-  constexpr int CPW = TMT / 4, TMW = TMT / 2;       // activation chunks each wave stages per k-tile; row tiles per wave
-  static_assert(TMT % 4 == 0, "row tiles are staged four ways");
-  __shared__ u32x4 xs[2][TMT * 64];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, rh = wave >> 1;
-  const int nt0 = blockIdx.x * (2 * TN) + (wave & 1) * TN;      // first weight tile of this wave
+  constexpr int CPW = TMT / 4, TMW = TMT / 2;       // activation tiles each wave requests per k-tile; row tiles per wave
+  static_assert(TMT % 4 == 0, "row tiles are requested four ways");
+  constexpr int STAGE = (2 * TN + TMT) * 64;        // 16-byte units: weight tiles first, then row tiles
+  constexpr int S = (160 / (2 * TN + TMT)) & ~1;    // stages in the ring: what 160 KiB of LDS holds (even: fragments alternate between two register sets)
+  constexpr int L = 2 + CPW;                        // requests per wave and stage
+  static_assert((S - 1) * L < 64, "the load counter has six bits");
+  __shared__ u32x4 ring[S][STAGE];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, rh = wave >> 1, nh = wave & 1;
+  const int nt0 = blockIdx.x * (2 * TN) + nh * TN;              // first weight tile of this wave
   const int mt0 = rh * TMW;                                     // first row tile of this wave
   const int kt0 = blockIdx.y * per, kt1 = min(ktiles, kt0 + per);
   if (kt0 >= kt1) return;                                       // whole workgroup (never with the launcher's shapes)
@@ -406,60 +418,57 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(const uint4* __restrict_
 #pragma unroll
     for (int mt = 0; mt < TMW; ++mt) acc[tn][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const u32x4* wp[TN];
+  // this wave's share of a stage: weight tiles 2*wave, 2*wave+1 of the group and row tiles wave*CPW ..
+  // (every wave requests both kinds with the same lead: a wave's load counter is in order, so it could not
+  // wait for a recent request without draining all its older ones)
+  const u32x4* wsrc[2];
 #pragma unroll
-  for (int tn = 0; tn < TN; ++tn) wp[tn] = (const u32x4*)W + (size_t)min(nt0 + tn, ntiles - 1) * ktiles * 64 + lane;
-  const u32x4* xp = (const u32x4*)A + (size_t)(wave * CPW) * ktiles * 64 + lane;   // this wave stages row tiles wave*CPW ..
-  // register rings: weights WR k-tiles deep, staged activations XR deep; the loop is unrolled by their common multiple
-  constexpr int WR = 3, XR = 2, UN = 6;
-  u32x4 wf[WR][TN], xst[XR][CPW];
-#define ROWS_FETCH_W(s_, kt_)                                                                            \
-  do {                                                                                                   \
-    const size_t k_ = (size_t)min(kt_, last) * 64;                                                       \
-    _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) wf[s_][tn] = __builtin_nontemporal_load(wp[tn] + k_); \
+  for (int j = 0; j < 2; ++j) wsrc[j] = (const u32x4*)W + (size_t)min(blockIdx.x * (2 * TN) + 2 * wave + j, ntiles - 1) * ktiles * 64 + lane;
+  const u32x4* xsrc = (const u32x4*)A + (size_t)(wave * CPW) * ktiles * 64 + lane;
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+#define ROWS_REQUEST(slot_, kt_)                                                                              \
+  do {                                                                                                        \
+    const size_t k_ = (size_t)min(kt_, last) * 64;                                                            \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                             \
+      __builtin_amdgcn_global_load_lds((gptr_t)(wsrc[j] + k_), (lptr_t)&ring[slot_][(2 * wave + j) * 64], 16, 0, 2); \
+    _Pragma("unroll") for (int c = 0; c < CPW; ++c)                                                           \
+      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + (size_t)c * ktiles * 64 + k_),                         \
+                                       (lptr_t)&ring[slot_][(2 * TN + wave * CPW + c) * 64], 16, 0, 0);       \
   } while (0)
-#define ROWS_FETCH_X(s_, kt_)                                                                            \
-  do {                                                                                                   \
-    const size_t k_ = (size_t)min(kt_, last) * 64;                                                       \
-    _Pragma("unroll") for (int c = 0; c < CPW; ++c) xst[s_][c] = xp[(size_t)c * ktiles * 64 + k_];      \
+#define ROWS_READ(buf_, slot_)                                                                               \
+  do {                                                                                                        \
+    const u32x4* wl_ = &ring[slot_][(nh * TN) * 64 + lane];                                                   \
+    const u32x4* xl_ = &ring[slot_][(2 * TN + mt0) * 64 + lane];                                              \
+    _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) wf[buf_][tn] = wl_[tn * 64];                            \
+    _Pragma("unroll") for (int mt = 0; mt < TMW; ++mt) xf[buf_][mt] = xl_[mt * 64];                           \
   } while (0)
-#define ROWS_DEPOSIT_X(slot_, s_)                                                                        \
-  do {                                                                                                   \
-    _Pragma("unroll") for (int c = 0; c < CPW; ++c) xs[slot_][(wave * CPW + c) * 64 + lane] = xst[s_][c]; \
-  } while (0)
-  // activations of k-tile kt live in register set kt%XR until deposited into LDS slot kt%2 one iteration ahead of use
+  u32x4 wf[2][TN], xf[2][TMW];      // fragments of the k-tile being multiplied and of the next one
 #pragma unroll
-  for (int j = 0; j < XR; ++j) ROWS_FETCH_X(j, kt0 + j);
+  for (int s = 0; s < S - 1; ++s) ROWS_REQUEST(s, kt0 + s);
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((S - 2) * L));
+  __builtin_amdgcn_s_barrier();
+  ROWS_READ(0, 0);
+  for (int kt = kt0; kt < kt1; kt += S) {
 #pragma unroll
-  for (int j = 0; j < WR; ++j) ROWS_FETCH_W(j, kt0 + j);
-  ROWS_DEPOSIT_X(0, 0);
-  ROWS_FETCH_X(0, kt0 + XR);
-  __syncthreads();
-  for (int kt = kt0; kt < kt1; kt += UN) {
-#pragma unroll
-    for (int j = 0; j < UN; ++j) {
-      ROWS_DEPOSIT_X((j + 1) & 1, (j + 1) % XR);
-      ROWS_FETCH_X((j + 1) % XR, kt + j + 1 + XR);
-      if (kt + j < kt1) {
-        // all activation fragments of the k-tile are read from LDS in one group (one exposed LDS latency
-        // per k-tile; the scheduling barrier keeps the compiler from sinking the reads next to their uses)
-        const u32x4* xl = xs[j & 1] + mt0 * 64 + lane;
-        u32x4 xf[TMW];
-#pragma unroll
-        for (int mt = 0; mt < TMW; ++mt) xf[mt] = xl[mt * 64];
-        __builtin_amdgcn_sched_barrier(0);
+    for (int u = 0; u < S; ++u) {
+      // own share of stage u+1 landed and own fragment reads done; then everybody's, and everybody is past
+      // the MFMAs of stage u-1, whose slot the next request overwrites
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((S - 3) * L));
+      __builtin_amdgcn_s_barrier();
+      ROWS_REQUEST((u + S - 1) % S, kt + u + S - 1);
+      ROWS_READ((u + 1) & 1, (u + 1) % S);        // lands under the MFMAs below
+      if (kt + u < kt1) {
 #pragma unroll
         for (int mt = 0; mt < TMW; ++mt)
 #pragma unroll
-          for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = mfma16(wf[j % WR][tn], xf[mt], acc[tn][mt]);
+          for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = mfma16(wf[u & 1][tn], xf[u & 1][mt], acc[tn][mt]);
       }
-      ROWS_FETCH_W(j % WR, kt + j + WR);
-      __syncthreads();
     }
   }
-#undef ROWS_FETCH_W
-#undef ROWS_FETCH_X
-#undef ROWS_DEPOSIT_X
+#undef ROWS_READ
+#undef ROWS_REQUEST
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));              // requests past the end have landed before the wave moves on
 
   const int mc = lane & 15;
   if (gridDim.y > 1) {
