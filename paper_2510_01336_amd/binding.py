@@ -367,10 +367,10 @@ class Session:
         ee_debug_enable_logits(self.handle, on)
 
     def last_logits(self, max_rows: Optional[int] = None) -> np.ndarray:
-        return ee_debug_last_logits(self.handle, max_rows or max(256, self.batch * self.max_rows), self.model.cfg.vocab)
+        return ee_debug_last_logits(self.handle, max_rows or max(512, self.batch * self.max_rows), self.model.cfg.vocab)
 
     def last_hidden(self, max_rows: Optional[int] = None) -> np.ndarray:
-        return ee_debug_last_hidden(self.handle, max_rows or max(256, self.batch * self.max_rows), self.model.cfg.d_model)
+        return ee_debug_last_hidden(self.handle, max_rows or max(512, self.batch * self.max_rows), self.model.cfg.d_model)
 
     def read_kv(self, seq: int, layer: int, pos0: int, n: int):
         return ee_debug_read_kv(self.handle, seq, layer, pos0, n, self.model.cfg.n_kv_heads, self.model.cfg.head_dim)

@@ -373,19 +373,21 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row-tiled GEMM for 64 < M <= 256 rows: weights still cross HBM once, but every weight fragment now
-// meets up to 16 row tiles, so the kernel sits near the machine's ridge (M flop per weight byte).
-// Workgroup = 4 waves on a group of 8 weight tiles (128 output features) and a share of K (grid.y);
-// wave (rh, nh) owns 4 of the tiles and half of the TMT row tiles: 2*TMT accumulators.
+// Row-tiled GEMM for 64 < M <= 512 rows: weights still cross HBM once, but every weight fragment now
+// meets up to 32 row tiles, so the kernel sits near the machine's ridge (M flop per weight byte).
+// Workgroup = 8 waves (two per SIMD: one wave alone does not keep a matrix pipe busy) on a group of
+// 8 weight tiles (128 output features) and a share of K (grid.y); wave (rq, nh) owns 4 of the tiles and a
+// quarter of the TMT row tiles: TMT accumulators.
 // Both operands reach LDS by direct global->LDS loads (no staging registers, no LDS store
 // instructions): a ring of S stages, one k-tile each (8 KiB of weights + TMT KiB of activations), as many
 // as LDS holds, of which up to S-2 are in flight: that is what covers the HBM latency with one workgroup
-// per compute unit.  Each wave requests a quarter of every stage; per k-tile it waits until its own share
-// of the next stage has landed (the load counter is in order), meets the other waves at a barrier --
-// which also says that everyone is past the MFMAs of the previous stage, whose slot the next request then
-// overwrites -- reads the next stage's fragments (1 KiB, lane-linear, conflict-free) into the second
-// register set and runs the 2*TMT MFMAs of the current one under them.  The loop is unrolled over the ring
-// so that every LDS address is a constant, and indices past the end are clamped (only the MFMAs are guarded).
+// per compute unit.  Each wave requests one weight tile and one or two row tiles of every stage; per
+// k-tile it waits until its own share of the next stage has landed (the load counter is in order), meets
+// the other waves at a barrier -- which also says that everyone is past the MFMAs of the previous stage,
+// whose slot the next request then overwrites -- reads the next stage's fragments (1 KiB, lane-linear,
+// conflict-free) into the second register set and runs the TMT MFMAs of the current one under them.  The
+// loop is unrolled over the ring so that every LDS address is a constant, and indices past the end are
+// clamped (only the MFMAs are guarded).
 // With grid.y == 1 the epilogue is fused; otherwise fp32 partial tiles go to scratch and
 // gemm_rows_reduce_kernel sums the K shares in a fixed order and runs the same epilogue.
 // ---------------------------------------------------------------------------------------------
@@ -394,20 +396,21 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 __host__ __device__ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
 template <int TMT, int EPI>
-__global__ __launch_bounds__(256) void gemm_rows_kernel(const uint4* __restrict__ W, int ktiles, int ntiles,
+__global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict__ W, int ktiles, int ntiles,
                                                         const uint4* __restrict__ A, int M, int N, GemmOut out,
                                                         int per, float* __restrict__ partial) {
   constexpr int TN = EE_ROWS_TN, NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
-  constexpr int CPW = TMT / 4, TMW = TMT / 2;       // activation tiles each wave requests per k-tile; row tiles per wave
-  static_assert(TMT % 4 == 0, "row tiles are requested four ways");
+  constexpr int TMW = TMT / 4;                      // row tiles per wave
+  static_assert(TMT % 4 == 0 && TMT >= 8 && TMT <= 32, "row tiles split four ways");
   constexpr int STAGE = (2 * TN + TMT) * 64;        // 16-byte units: weight tiles first, then row tiles
   constexpr int S = (160 / (2 * TN + TMT)) & ~1;    // stages in the ring: what 160 KiB of LDS holds (even: fragments alternate between two register sets)
-  constexpr int L = 2 + CPW;                        // requests per wave and stage
-  static_assert((S - 1) * L < 64, "the load counter has six bits");
+  constexpr int XHI = (TMT + 7) / 8, XLO = TMT / 8; // row tiles a wave requests per stage: wave, wave+8, ... below TMT
+  constexpr int LHI = 1 + XHI, LLO = 1 + XLO;       // requests per stage of the waves below TMT % 8 / of the others
+  static_assert((S - 1) * LHI < 64, "the load counter has six bits");
   __shared__ u32x4 ring[S][STAGE];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, rh = wave >> 1, nh = wave & 1;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, rq = wave >> 1, nh = wave & 1;
   const int nt0 = blockIdx.x * (2 * TN) + nh * TN;              // first weight tile of this wave
-  const int mt0 = rh * TMW;                                     // first row tile of this wave
+  const int mt0 = rq * TMW;                                     // first row tile of this wave
   const int kt0 = blockIdx.y * per, kt1 = min(ktiles, kt0 + per);
   if (kt0 >= kt1) return;                                       // whole workgroup (never with the launcher's shapes)
   const int last = kt1 - 1;
@@ -418,23 +421,29 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(const uint4* __restrict_
 #pragma unroll
     for (int mt = 0; mt < TMW; ++mt) acc[tn][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // this wave's share of a stage: weight tiles 2*wave, 2*wave+1 of the group and row tiles wave*CPW ..
-  // (every wave requests both kinds with the same lead: a wave's load counter is in order, so it could not
-  // wait for a recent request without draining all its older ones)
-  const u32x4* wsrc[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) wsrc[j] = (const u32x4*)W + (size_t)min(blockIdx.x * (2 * TN) + 2 * wave + j, ntiles - 1) * ktiles * 64 + lane;
-  const u32x4* xsrc = (const u32x4*)A + (size_t)(wave * CPW) * ktiles * 64 + lane;
+  // this wave's share of a stage: weight tile `wave` of the group and row tiles wave, wave+8, ... (every
+  // wave requests both kinds with the same lead: a wave's load counter is in order, so it could not wait
+  // for a recent request without draining all its older ones)
+  const bool two = wave + 8 * XLO < TMT;            // this wave has XHI row tiles, not XLO
+  const u32x4* wsrc = (const u32x4*)W + (size_t)min(blockIdx.x * (2 * TN) + wave, ntiles - 1) * ktiles * 64 + lane;
+  const u32x4* xsrc = (const u32x4*)A + (size_t)wave * ktiles * 64 + lane;
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
 #define ROWS_REQUEST(slot_, kt_)                                                                              \
   do {                                                                                                        \
     const size_t k_ = (size_t)min(kt_, last) * 64;                                                            \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                             \
-      __builtin_amdgcn_global_load_lds((gptr_t)(wsrc[j] + k_), (lptr_t)&ring[slot_][(2 * wave + j) * 64], 16, 0, 2); \
-    _Pragma("unroll") for (int c = 0; c < CPW; ++c)                                                           \
-      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + (size_t)c * ktiles * 64 + k_),                         \
-                                       (lptr_t)&ring[slot_][(2 * TN + wave * CPW + c) * 64], 16, 0, 0);       \
+    __builtin_amdgcn_global_load_lds((gptr_t)(wsrc + k_), (lptr_t)&ring[slot_][wave * 64], 16, 0, 2);         \
+    _Pragma("unroll") for (int j = 0; j < XLO; ++j)                                                           \
+      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + (size_t)(8 * j) * ktiles * 64 + k_),                   \
+                                       (lptr_t)&ring[slot_][(2 * TN + wave + 8 * j) * 64], 16, 0, 0);         \
+    if (XHI > XLO && two)                                                                                     \
+      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + (size_t)(8 * XLO) * ktiles * 64 + k_),                 \
+                                       (lptr_t)&ring[slot_][(2 * TN + wave + 8 * XLO) * 64], 16, 0, 0);       \
+  } while (0)
+#define ROWS_WAIT(stages_)                                                                                    \
+  do {                                                                                                        \
+    if (LHI == LLO || two) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * LHI));                     \
+    else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * LLO));                                       \
   } while (0)
 #define ROWS_READ(buf_, slot_)                                                                               \
   do {                                                                                                        \
@@ -446,27 +455,46 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(const uint4* __restrict_
   u32x4 wf[2][TN], xf[2][TMW];      // fragments of the k-tile being multiplied and of the next one
 #pragma unroll
   for (int s = 0; s < S - 1; ++s) ROWS_REQUEST(s, kt0 + s);
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((S - 2) * L));
+  ROWS_WAIT(S - 2);
   __builtin_amdgcn_s_barrier();
   ROWS_READ(0, 0);
-  for (int kt = kt0; kt < kt1; kt += S) {
+  // One k-tile: own share of stage u+1 landed and own fragment reads done; then everybody's, and everybody
+  // is past the MFMAs of stage u-1, whose slot the next request overwrites.  The requests and the reads of
+  // the next fragments do not depend on this k-tile's MFMAs and ride along with them, one row tile's four
+  // MFMAs at a time (the scheduling barriers pin that order): issued in one burst after the barrier, the
+  // eight waves' LDS reads would queue up while the matrix pipes sit idle.
+  static_assert(TN <= TMW + 2, "weight fragments are read in the first row-tile slices");
+#define ROWS_STEP(u_, guard_)                                                                                 \
+  do {                                                                                                        \
+    ROWS_WAIT(S - 3);                                                                                         \
+    __builtin_amdgcn_s_barrier();                                                                             \
+    const int cb_ = (u_) & 1, nb_ = cb_ ^ 1, ns_ = ((u_) + 1) % S;                                            \
+    ROWS_REQUEST(((u_) + S - 1) % S, kt + (u_) + S - 1);                                                      \
+    const u32x4* wl_ = &ring[ns_][(nh * TN) * 64 + lane];                                                     \
+    const u32x4* xl_ = &ring[ns_][(2 * TN + mt0) * 64 + lane];                                                \
+    const bool on_ = !(guard_) || kt + (u_) < kt1;                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                        \
+    _Pragma("unroll") for (int mt = 0; mt < TMW; ++mt) {                                                      \
+      _Pragma("unroll") for (int tn = mt * TN / TMW; tn < (mt + 1) * TN / TMW; ++tn) wf[nb_][tn] = wl_[tn * 64]; \
+      xf[nb_][mt] = xl_[mt * 64];                                                                             \
+      if (on_) {                                                                                              \
+        _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = mfma16(wf[cb_][tn], xf[cb_][mt], acc[tn][mt]); \
+      }                                                                                                       \
+      __builtin_amdgcn_sched_barrier(0);                                                                      \
+    }                                                                                                         \
+  } while (0)
+  int kt = kt0;
+  for (; kt + S <= kt1; kt += S) {
 #pragma unroll
-    for (int u = 0; u < S; ++u) {
-      // own share of stage u+1 landed and own fragment reads done; then everybody's, and everybody is past
-      // the MFMAs of stage u-1, whose slot the next request overwrites
-      __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((S - 3) * L));
-      __builtin_amdgcn_s_barrier();
-      ROWS_REQUEST((u + S - 1) % S, kt + u + S - 1);
-      ROWS_READ((u + 1) & 1, (u + 1) % S);        // lands under the MFMAs below
-      if (kt + u < kt1) {
-#pragma unroll
-        for (int mt = 0; mt < TMW; ++mt)
-#pragma unroll
-          for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = mfma16(wf[u & 1][tn], xf[u & 1][mt], acc[tn][mt]);
-      }
-    }
+    for (int u = 0; u < S; ++u) ROWS_STEP(u, false);
   }
+  if (kt < kt1) {                                  // fewer than S k-tiles left: same steps, MFMAs guarded
+#pragma unroll
+    for (int u = 0; u < S; ++u) ROWS_STEP(u, true);
+  }
+#undef ROWS_STEP
 #undef ROWS_READ
+#undef ROWS_WAIT
 #undef ROWS_REQUEST
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));              // requests past the end have landed before the wave moves on
 
@@ -552,14 +580,14 @@ static int rows_ksplit(int ntiles, int ktiles) {
 }
 size_t bf16_gemm_rows_scratch_floats(int ntiles, int ktiles) {
   const int ks = rows_ksplit(ntiles, ktiles);
-  return ks > 1 ? (size_t)ks * ntiles * 16 * 256 : 0;       // [k share][weight tile][16 row tiles][64 lanes x 4]
+  return ks > 1 ? (size_t)ks * ntiles * 32 * 256 : 0;       // [k share][weight tile][up to 32 row tiles][64 lanes x 4]
 }
 
 template <int TMT>
 static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int M, int N,
                              const GemmOut& out, float* scratch) {
   const int ks = rows_ksplit(ntiles, ktiles), per = ceil_div(ktiles, ks);
-  dim3 grid(ceil_div(ntiles, 2 * EE_ROWS_TN), ceil_div(ktiles, per)), blk(256);
+  dim3 grid(ceil_div(ntiles, 2 * EE_ROWS_TN), ceil_div(ktiles, per)), blk(512), rblk(256);
   const int ksr = grid.y;
   switch (epi) {
     case EPI_ADD: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ADD>), grid, blk, 0, st, W, ktiles, ntiles, A, M, N, out, per, scratch); break;
@@ -572,15 +600,15 @@ static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles
     const int units = (ntiles / nb) * ceil_div(M, 16);
     dim3 rgrid(ceil_div(units, 4));
     switch (epi) {
-      case EPI_ADD: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ADD>), rgrid, blk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
-      case EPI_SWIGLU: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_SWIGLU>), rgrid, blk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
-      case EPI_ROPE: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ROPE>), rgrid, blk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
-      default: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ARGMAX>), rgrid, blk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
+      case EPI_ADD: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ADD>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
+      case EPI_SWIGLU: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_SWIGLU>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
+      case EPI_ROPE: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ROPE>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
+      default: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ARGMAX>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
     }
   }
 }
 
-// 64 < M <= 256 rows from row 0 of the operand; out.nin.ssq, if set, is first reduced to per-row factors
+// 64 < M <= 512 rows from row 0 of the operand; out.nin.ssq, if set, is first reduced to per-row factors
 void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                     const GemmOut& out0, float* scratch, float* inv_rms) {
   GemmOut out = out0;
@@ -593,7 +621,9 @@ void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kt
   const uint4* Ac = (const uint4*)A;
   if (M <= 128) launch_gemm_rows<8>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
   else if (M <= 192) launch_gemm_rows<12>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
-  else launch_gemm_rows<16>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
+  else if (M <= 256) launch_gemm_rows<16>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
+  else if (M <= 384) launch_gemm_rows<24>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
+  else launch_gemm_rows<32>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
 }
 
 template <int MT, int U>

@@ -123,7 +123,7 @@ static size_t carve(ee_session* s, char* base) {
     for (const MatLoc* ml : {&m->L[0].qkv, &m->L[0].o, &m->L[0].gu, &m->L[0].down, &m->head})
       gp = std::max(gp, bf16_gemm_rows_scratch_floats(ml->ntiles(), ml->ktiles()));
     s->gemm_part = s->maxM > 64 ? cv.take<float>(gp) : nullptr;
-    s->inv_rms = cv.take<float>(256);
+    s->inv_rms = cv.take<float>(512);
   }
   s->slot[0].d = cv.take<int>(s->meta_ints);
   s->slot[1].d = cv.take<int>(s->meta_ints);
@@ -139,10 +139,10 @@ static int shape_session(ee_session* s, const ee_model* m, int batch, int max_ct
   s->B = batch; s->max_ctx = max_ctx; s->max_rows = max_rows;
   s->pps = ceil_div(max_ctx, EE_PAGE);
   s->n_pages = total_pages > 0 ? total_pages : batch * s->pps;
-  s->chunk = m->bf16 ? 256 : 64;                        // context-build rows per pass
+  s->chunk = m->bf16 ? 512 : 64;                        // context-build rows per pass
   s->maxM = std::max(batch * max_rows, s->chunk);
-  // activation rows padded to whole GEMM passes: 64 rows (skinny kernel), 256 (row-tiled kernel reads 16 row tiles)
-  s->Mp = s->maxM <= 64 ? 64 : std::max(256, ceil_div(s->maxM, 64) * 64);
+  // activation rows padded to whole GEMM passes: 64 rows (skinny kernel), 512 (the row-tiled kernel requests up to 32 row tiles)
+  s->Mp = s->maxM <= 64 ? 64 : std::max(512, ceil_div(s->maxM, 64) * 64);
   s->maxQT = ceil_div(s->maxM * rep, 16) + batch;
   layout_meta(s);
   return EE_OK;
@@ -313,11 +313,11 @@ static void reset_accounting(ee_session* s) {
 // ---------------------------------------------------------------------------------------------
 // forward pass pieces
 // ---------------------------------------------------------------------------------------------
-// weights cross HBM once per call: up to 64 rows the skinny kernel, up to 256 the row-tiled one (beyond that
+// weights cross HBM once per call: up to 64 rows the skinny kernel, up to 512 the row-tiled one (beyond that
 // the skinny kernel goes over the rows in passes of 64)
 static void gemm(ee_session* s, int epi, const MatLoc& ml, const bf16_t* A, int M, const GemmOut& o) {
   const bf16_t* W = (const bf16_t*)(s->m->base + ml.off);
-  if (M > 64 && M <= 256) bf16_gemm_rows(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o, s->gemm_part, s->inv_rms);
+  if (M > 64 && M <= 512) bf16_gemm_rows(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o, s->gemm_part, s->inv_rms);
   else bf16_gemm(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o);
 }
 
