@@ -65,8 +65,8 @@ struct GemmOut {
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out);
 void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                    const GemmOut& out, int nw, int ksplit, int U);
-// Row-tiled variant for 64 < M <= 512 rows (rows start at row 0 of the operand; the kernel reads whole row
-// tiles up to the next of 128, 192, 256, 384, 512 rows, which the operand buffer must hold).  scratch: bf16_gemm_rows_scratch_floats() floats for
+// Row-tiled variant for 16 < M <= 512 rows (rows start at row 0 of the operand; the kernel reads whole row
+// tiles up to the next of 64, 128, 192, 256, 384, 512 rows, which the operand buffer must hold).  scratch: bf16_gemm_rows_scratch_floats() floats for
 // this shape (may be null when that is 0); inv_rms: M floats of scratch for the deferred RMSNorm factors.
 size_t bf16_gemm_rows_scratch_floats(int ntiles, int ktiles);
 void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,

@@ -373,7 +373,7 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row-tiled GEMM for 64 < M <= 512 rows: weights still cross HBM once, but every weight fragment now
+// Row-tiled GEMM for 16 < M <= 512 rows: weights still cross HBM once, but every weight fragment now
 // meets up to 32 row tiles, so the kernel sits near the machine's ridge (M flop per weight byte).
 // Workgroup = 8 waves (two per SIMD: one wave alone does not keep a matrix pipe busy) on a group of
 // 8 weight tiles (128 output features) and a share of K (grid.y); wave (rq, nh) owns 4 of the tiles and a
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
                                                         int per, float* __restrict__ partial) {
   constexpr int TN = EE_ROWS_TN, NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
   constexpr int TMW = TMT / 4;                      // row tiles per wave
-  static_assert(TMT % 4 == 0 && TMT >= 8 && TMT <= 32, "row tiles split four ways");
+  static_assert(TMT % 4 == 0 && TMT >= 4 && TMT <= 32, "row tiles split four ways");
   constexpr int STAGE = (2 * TN + TMT) * 64;        // 16-byte units: weight tiles first, then row tiles
   constexpr int S = (160 / (2 * TN + TMT)) & ~1;    // stages in the ring: what 160 KiB of LDS holds (even: fragments alternate between two register sets)
   constexpr int XHI = (TMT + 7) / 8, XLO = TMT / 8; // row tiles a wave requests per stage: wave, wave+8, ... below TMT
@@ -463,7 +463,6 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   // the next fragments do not depend on this k-tile's MFMAs and ride along with them, one row tile's four
   // MFMAs at a time (the scheduling barriers pin that order): issued in one burst after the barrier, the
   // eight waves' LDS reads would queue up while the matrix pipes sit idle.
-  static_assert(TN <= TMW + 2, "weight fragments are read in the first row-tile slices");
 #define ROWS_STEP(u_, guard_)                                                                                 \
   do {                                                                                                        \
     ROWS_WAIT(S - 3);                                                                                         \
@@ -608,7 +607,7 @@ static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles
   }
 }
 
-// 64 < M <= 512 rows from row 0 of the operand; out.nin.ssq, if set, is first reduced to per-row factors
+// 16 < M <= 512 rows from row 0 of the operand; out.nin.ssq, if set, is first reduced to per-row factors
 void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                     const GemmOut& out0, float* scratch, float* inv_rms) {
   GemmOut out = out0;
@@ -619,7 +618,8 @@ void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kt
   }
   const uint4* Wc = (const uint4*)W;
   const uint4* Ac = (const uint4*)A;
-  if (M <= 128) launch_gemm_rows<8>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
+  if (M <= 64) launch_gemm_rows<4>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
+  else if (M <= 128) launch_gemm_rows<8>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
   else if (M <= 192) launch_gemm_rows<12>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
   else if (M <= 256) launch_gemm_rows<16>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
   else if (M <= 384) launch_gemm_rows<24>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);

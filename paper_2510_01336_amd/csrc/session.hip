@@ -313,11 +313,13 @@ static void reset_accounting(ee_session* s) {
 // ---------------------------------------------------------------------------------------------
 // forward pass pieces
 // ---------------------------------------------------------------------------------------------
-// weights cross HBM once per call: up to 64 rows the skinny kernel, up to 512 the row-tiled one (beyond that
-// the skinny kernel goes over the rows in passes of 64)
+// weights cross HBM once per call: up to 16 rows the skinny kernel, from 33 to 512 the row-tiled one, in
+// between the row-tiled one for matrices of 128 MB and more (measured: the small projections are quicker
+// without its K-share reduction pass); beyond 512 rows the skinny kernel goes over the rows in passes of 64
 static void gemm(ee_session* s, int epi, const MatLoc& ml, const bf16_t* A, int M, const GemmOut& o) {
   const bf16_t* W = (const bf16_t*)(s->m->base + ml.off);
-  if (M > 64 && M <= 512) bf16_gemm_rows(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o, s->gemm_part, s->inv_rms);
+  const bool big = (size_t)ml.ntiles() * ml.ktiles() * 1024 >= ((size_t)128 << 20);
+  if (M > (big ? 16 : 32) && M <= 512) bf16_gemm_rows(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o, s->gemm_part, s->inv_rms);
   else bf16_gemm(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o);
 }
 
