@@ -34,7 +34,7 @@ MODEL_SEED = 20251001
 # HBM traffic of one gate/up GEMM launch (8b_b1_ctx2048_k8) measured with two rocprofv3 --pmc runs
 # (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the calibration copy
 # below; the figures and the commands are in profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = 236_528_000
+MEASURED_TRAFFIC_BYTES = 236_569_000
 CALIBRATION_COPY_BYTES = 1 << 30
 
 def _ragged16():

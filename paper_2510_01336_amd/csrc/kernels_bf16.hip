@@ -558,16 +558,23 @@ __global__ __launch_bounds__(256) void gemm_rows_reduce_kernel(const float* __re
   epi_apply<EPI>(acc[0], acc[NB - 1], sc, pre, out, task, m, m < M, N, lane);
 }
 
-// per-row factor rsqrt(mean(x^2) + eps) from the producer's per-tile partial sums of squares, in a fixed order
+// per-row factor rsqrt(mean(x^2) + eps) from the producer's per-tile partial sums of squares, in a fixed order:
+// one wave per row, every lane taking each 64th partial with four loads in flight
 __global__ __launch_bounds__(256) void norm_factor_kernel(const float* __restrict__ ssq, int n_part, int stride, float inv_d, float eps,
                                                           float* __restrict__ inv_rms, int M) {
-  // 16 lanes per row, each taking every 16th partial
-  const int row = blockIdx.x * 16 + (threadIdx.x >> 4), t = threadIdx.x & 15;
-  float ss = 0.f;
-  if (row < M)
-    for (int i = t; i < n_part; i += 16) ss += ssq[(size_t)i * stride + row];
-  for (int sh = 1; sh < 16; sh <<= 1) ss += __shfl_xor(ss, sh, 64);
-  if (row < M && t == 0) inv_rms[row] = 1.0f / sqrtf(ss * inv_d + eps);
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), t = threadIdx.x & 63;
+  if (row >= M) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int i = t;
+  for (; i + 192 < n_part; i += 256) {
+    const float a = ssq[(size_t)i * stride + row], b = ssq[(size_t)(i + 64) * stride + row];
+    const float c = ssq[(size_t)(i + 128) * stride + row], d = ssq[(size_t)(i + 192) * stride + row];
+    s0 += a; s1 += b; s2 += c; s3 += d;
+  }
+  for (; i < n_part; i += 64) s0 += ssq[(size_t)i * stride + row];
+  float ss = (s0 + s1) + (s2 + s3);
+  for (int sh = 1; sh < 64; sh <<= 1) ss += __shfl_xor(ss, sh, 64);
+  if (t == 0) inv_rms[row] = 1.0f / sqrtf(ss * inv_d + eps);
 }
 
 // number of K shares the row-tiled GEMM runs with: enough workgroups for the chip, at least 16 k-tiles each
@@ -612,7 +619,7 @@ void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kt
                     const GemmOut& out0, float* scratch, float* inv_rms) {
   GemmOut out = out0;
   if (out.nin.ssq) {
-    hipLaunchKernelGGL(norm_factor_kernel, dim3(ceil_div(M, 16)), dim3(256), 0, st, out.nin.ssq, out.nin.n_part, out.nin.stride,
+    hipLaunchKernelGGL(norm_factor_kernel, dim3(ceil_div(M, 4)), dim3(256), 0, st, out.nin.ssq, out.nin.n_part, out.nin.stride,
                        out.nin.inv_d, out.nin.eps, inv_rms, M);
     out.nin.inv_rms = inv_rms;
   }
