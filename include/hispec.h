@@ -118,6 +118,13 @@ void ee_session_free(ee_session* s);
  * (the "Vanilla generation" step of Sec. 3.1).  first_token: host [batch]. */
 int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* lens, int32_t* first_token);
 
+/* Vanilla generation of Sec. 3.1 (the baseline the method is measured against and whose output it must
+ * reproduce): n greedy single-token steps through all L_f layers per sequence, each committing
+ * arg max at L_f.  Requires every sequence to be started with an empty tentative buffer and no pending
+ * draft block (EE_ERR_STATE otherwise); 1 <= n <= max_rows; EE_ERR_CAPACITY if positions would overflow.
+ * All three group lengths advance by n.  out: host [batch, n], the committed tokens. */
+int ee_decode_ar(ee_session* s, int n, int32_t* out);
+
 /* Generate(L_d, x||V, k) of Algorithm 2: k sequential single-row passes through G1 + exit head +
  * arg max per sequence, each appending one KV row per G1 layer and one H_d row (Sec. 3.2,
  * "expanding during draft generation").  With bonus_inter one more G1-only row is run for the

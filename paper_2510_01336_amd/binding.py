@@ -14,7 +14,7 @@ import numpy as np
 __all__ = [
     "lib", "lib_path", "EEError", "ee_config", "make_config", "Model", "Session",
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
-    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_draft", "ee_draft_inject",
+    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
@@ -27,7 +27,7 @@ TENSOR_IDS = {"emb": 0, "head": 1, "gfinal": 2, "g1": 3, "wq": 4, "wk": 5, "wv":
 
 EXPORTED_SYMBOLS = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
-    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_draft", "ee_draft_inject",
+    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
@@ -71,6 +71,7 @@ def _load():
         "ee_session_create": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t, vp, C.POINTER(vp)]),
         "ee_session_free": (None, [vp]),
         "ee_prefill": (C.c_int, [vp, i32p, i32p, i32p]),
+        "ee_decode_ar": (C.c_int, [vp, C.c_int, i32p]),
         "ee_draft": (C.c_int, [vp, C.c_int, i32p]),
         "ee_draft_inject": (C.c_int, [vp, C.c_int, i32p]),
         "ee_verify_intermediate": (C.c_int, [vp, i32p, i32p]),
@@ -200,6 +201,12 @@ def ee_prefill(session: int, tokens: np.ndarray, lens: np.ndarray) -> np.ndarray
     first = np.empty(len(l), np.int32)
     _chk(lib.ee_prefill(session, _p_i32(t), _p_i32(l), _p_i32(first)))
     return first
+
+
+def ee_decode_ar(session: int, batch: int, n: int) -> np.ndarray:
+    out = np.empty((batch, n), np.int32)
+    _chk(lib.ee_decode_ar(session, n, _p_i32(out)))
+    return out
 
 
 def ee_draft(session: int, batch: int, k: int) -> np.ndarray:
@@ -338,6 +345,9 @@ class Session:
     def prefill(self, prompts: Sequence[np.ndarray]) -> np.ndarray:
         lens = np.array([len(p) for p in prompts], np.int32)
         return ee_prefill(self.handle, np.concatenate([_i32(p) for p in prompts]), lens)
+
+    def decode_ar(self, n: int) -> np.ndarray:
+        return ee_decode_ar(self.handle, self.batch, n)
 
     def draft(self, k: int) -> np.ndarray:
         return ee_draft(self.handle, self.batch, k)

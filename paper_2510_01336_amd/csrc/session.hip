@@ -477,6 +477,48 @@ extern "C" int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* l
 }
 
 // ---------------------------------------------------------------------------------------------
+// C ABI: vanilla greedy generation at full depth (Sec. 3.1)
+// ---------------------------------------------------------------------------------------------
+extern "C" int ee_decode_ar(ee_session* s, int n, int32_t* out) {
+  if (!s || !out) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  const ee_config& c = s->m->cfg;
+  if (n < 1 || n > s->max_rows) { ee_set_error("%d tokens per call do not fit max_rows %d", n, s->max_rows); return EE_ERR_ARG; }
+  std::vector<int> want(s->B);
+  for (int b = 0; b < s->B; ++b) {
+    const SeqState& q = s->seq[b];
+    if (!q.started) { ee_set_error("sequence %d has no context (call ee_prefill)", b); return EE_ERR_STATE; }
+    if (q.n_hd || !q.V.empty()) { ee_set_error("sequence %d has unverified tokens", b); return EE_ERR_STATE; }
+    want[b] = (int)q.C.size() + n;
+  }
+  EE_TRY(check_capacity(s, want));
+  reset_accounting(s);
+  CallPlan p;
+  p.m.assign(s->B, 1); p.p0.resize(s->B);
+  for (int b = 0; b < s->B; ++b) {
+    p.p0[b] = (int)s->seq[b].C.size() - 1;          // the pending token's position
+    EE_TRY(grow_pages(s, b, want[b]));
+  }
+  EE_TRY(build_meta(s, 0, p, [&](int b, int, int& tok, int&, int&) { tok = s->seq[b].C.back(); }));
+  EE_TRY(upload_meta(s, 0));
+  CallMeta mt = meta_ptrs(s, s->slot[0].d);
+  for (int j = 0; j < n; ++j) {       // the next token stays on the device; positions advance through pos_add
+    KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, j == 0 ? mt.row_tok : s->tok_next, s->X, p.M, c.d_model));
+    run_layers(s, 0, c.n_layers, p, mt, j);
+    exit_head(s, p.M);
+    KF(KF_MISC, k_take_token(s->st, s->vtok, mt.row_seq, p.M, s->tok_next, s->draft_dev, s->max_rows, j));
+  }
+  int* dh = s->out_host + 2 * s->B;
+  HIP_TRY(hipMemcpyAsync(dh, s->draft_dev, (size_t)s->B * s->max_rows * sizeof(int), hipMemcpyDeviceToHost, s->st));
+  EE_TRY(finish(s));
+  for (int b = 0; b < s->B; ++b) {
+    SeqState& q = s->seq[b];
+    for (int j = 0; j < n; ++j) { out[b * n + j] = dh[b * s->max_rows + j]; q.C.push_back(dh[b * s->max_rows + j]); }
+    q.len[0] = q.len[1] = q.len[2] = (int)q.C.size() - 1;
+  }
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // C ABI: drafting at exit L_d
 // ---------------------------------------------------------------------------------------------
 static int draft_precheck(ee_session* s, int k, int rows) {

@@ -1,0 +1,63 @@
+"""Host policy around the library calls: the decoding loop of Algorithm 2 (hierarchical speculative decoding).
+
+Everything that computes runs in the library (ee_draft, ee_verify_intermediate, ee_verify_full); this
+module only decides when the full verification fires -- when the tentative buffer holds at least N_i
+tokens (Sec. 3.4) or after a fixed number of intermediate rounds -- and collects acceptance statistics
+(draft tokens accepted by L_i per round, tentative tokens accepted by L_f per full verification).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+
+@dataclass
+class LoopStats:
+    rounds: int = 0                 # draft + intermediate-verify rounds
+    full_verifies: int = 0
+    drafted: int = 0                # draft tokens proposed (per sequence summed)
+    accepted_inter: int = 0         # of those, accepted by the intermediate verifier
+    tentative: int = 0              # tentative tokens put to the full model
+    accepted_full: int = 0          # of those, accepted by the full model
+    committed: int = 0              # tokens committed (incl. the full model's own)
+    per_round_accept: List[int] = field(default_factory=list)
+
+
+def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, every: Optional[int] = None):
+    """Generate n_new tokens per sequence after the session's current context (ee_prefill done, nothing pending).
+
+    Exactly one of n_i (fire the full verification when every sequence's tentative buffer holds >= n_i
+    tokens) and every (fire after that many intermediate rounds) is given.  Returns (tokens [batch, n_new],
+    LoopStats).  The committed stream may run a few tokens past n_new inside the session; the returned
+    rows are cut to n_new.
+    """
+    assert (n_i is None) != (every is None)
+    B = sess.batch
+    out: List[List[int]] = [[] for _ in range(B)]
+    st = LoopStats()
+    while min(len(o) for o in out) < n_new:
+        rounds = 0
+        while True:
+            sess.draft(k)
+            a, _ = sess.verify_intermediate()
+            rounds += 1
+            st.rounds += 1
+            st.drafted += B * k
+            st.accepted_inter += int(a.sum())
+            st.per_round_accept.append(int(a.sum()))
+            _, nv = sess.counts()
+            if (n_i is not None and int(nv.min()) >= n_i) or (every is not None and rounds >= every):
+                break
+            if min(len(o) + int(v) for o, v in zip(out, nv)) >= n_new + k + 2:
+                break
+        _, nv = sess.counts()
+        f, _, com = sess.verify_full()
+        st.full_verifies += 1
+        st.tentative += int(nv.sum())
+        st.accepted_full += int(np.minimum(f, nv).sum())
+        for b in range(B):
+            out[b].extend(int(t) for t in com[b])
+            st.committed += len(com[b])
+    return np.array([o[:n_new] for o in out], np.int32), st

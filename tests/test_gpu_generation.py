@@ -1,0 +1,75 @@
+"""GPU: vanilla greedy generation (ee_decode_ar) against the oracle, and the method's invariant on the GPU
+itself -- the stream the hierarchical loop commits equals greedy decoding of the full-depth model
+(Sec. 3.1; Alg. 2 changes the speed, not the output)."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import ee_oracle as eo
+from hs_common import MARGIN, OracleSide, bf16_small, gpu_side
+
+pytestmark = pytest.mark.gpu
+
+SEED = 4242
+
+
+def _oracle_ar_with_margins(model, prompt, n_new):
+    """eo.ar_generate written out with the top-1/top-2 margin of every step."""
+    L = model.spec.n_layers
+    cache = eo.KVCache(model.spec, len(prompt) + n_new)
+    x = model.run_layers(range(L), model.embed(prompt), np.arange(len(prompt)), cache)
+    lg = model.exit_logits(x[-1:])
+    out, margins = [int(eo.argmax_rows(lg)[0])], [float(eo.top2_margin(lg)[0])]
+    while len(out) < n_new:
+        p = len(prompt) + len(out) - 1
+        x = model.run_layers(range(L), model.embed([out[-1]]), np.array([p]), cache)
+        lg = model.exit_logits(x)
+        out.append(int(eo.argmax_rows(lg)[0])); margins.append(float(eo.top2_margin(lg)[0]))
+    return out, margins
+
+
+@pytest.mark.parametrize("cfg", [synth.tiny_config(), bf16_small()], ids=["tiny_f32", "bf16_small"])
+def test_ar_decode_matches_oracle(cfg):
+    n_new, ctx = 24, [33, 20]
+    O = OracleSide(cfg, SEED)
+    prompts = [synth.gen_prompt(cfg.vocab, n, 70 + i) for i, n in enumerate(ctx)]
+    model, sess = gpu_side(cfg, SEED, len(ctx), max(ctx) + n_new + 8, n_new)
+    first = sess.prefill(prompts)
+    got = sess.decode_ar(n_new - 1)
+    assert sess.lengths().tolist() == [[n + n_new - 1] * 3 for n in ctx]
+    compared = 0
+    for b, p in enumerate(prompts):
+        ref, margins = _oracle_ar_with_margins(O.model, p, n_new)
+        stream = [int(first[b])] + got[b].tolist()
+        n_clear = next((i for i, m in enumerate(margins) if m <= MARGIN), n_new)   # equal up to the first near-tie
+        assert stream[:n_clear] == ref[:n_clear], b
+        compared += n_clear
+        assert sess.tokens(b).tolist()[len(p):] == stream
+    assert compared >= n_new
+    # state errors: a pending draft block forbids vanilla steps and leaves the session as it was
+    import paper_2510_01336_amd as hs
+    sess.draft(2)
+    before = sess.lengths().tolist()
+    with pytest.raises(hs.EEError):
+        sess.decode_ar(1)
+    assert sess.lengths().tolist() == before
+    sess.close(); model.close()
+
+
+@pytest.mark.parametrize("policy", [dict(n_i=6), dict(every=2)], ids=["n_i6", "every2"])
+def test_hispec_stream_equals_vanilla_stream_on_gpu(policy):
+    from paper_2510_01336_amd.loop import hispec_generate
+    cfg = synth.tiny_config(gamma=(1.0, 0.3, 0.3))       # damped upper groups: the exits agree often, not always
+    n_new, k, ctx = 48, 4, [32, 19]
+    prompts = [synth.gen_prompt(cfg.vocab, n, 11 + i) for i, n in enumerate(ctx)]
+    rows = 4 * (k + 1) + 2
+    model, sess = gpu_side(cfg, SEED, len(ctx), max(ctx) + n_new + 4 * rows, max(rows, n_new))
+    first = sess.prefill(prompts)
+    ar = np.concatenate([first[:, None], sess.decode_ar(n_new - 1)], axis=1)
+    sess.prefill(prompts)                                # restart from the prompts
+    toks, st = hispec_generate(sess, n_new - 1, k, **policy)
+    hs_stream = np.concatenate([first[:, None], toks], axis=1)
+    assert np.array_equal(hs_stream, ar)
+    # the loop did speculate: some draft tokens were accepted, some rejected
+    assert 0 < st.accepted_inter < st.drafted and st.full_verifies >= 1 and st.accepted_full <= st.tentative
+    sess.close(); model.close()
