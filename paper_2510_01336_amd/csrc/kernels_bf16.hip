@@ -673,10 +673,12 @@ void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kti
 // about two thousand waves are in flight.  M may exceed 64: rows go in passes of 64 (weights re-streamed).
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out) {
   const int ntasks = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? ntiles / 2 : ntiles;
-  int ksplit = ntasks >= 768 ? 1 : (ntasks >= 320 ? 4 : 8);
+  // launch shape by task count, from sweeps over the 8B and 70B matrix shapes at 9 rows
+  int ksplit = ntasks >= 4096 ? 4 : (ntasks >= 768 ? 1 : (ntasks >= 320 ? 4 : (ntasks >= 200 ? 8 : 4)));
+  int U = (ntasks >= 768 || ntasks < 200) ? 8 : 4;
   while (ksplit > 1 && ktiles / ksplit < 4) ksplit >>= 1;
   const int nw = ksplit > 4 ? ksplit : 4;
-  bf16_gemm_cfg(st, epi, W, ntiles, ktiles, A, M, N, out, nw, ksplit, ksplit == 1 ? 8 : 4);
+  bf16_gemm_cfg(st, epi, W, ntiles, ktiles, A, M, N, out, nw, ksplit, U);
 }
 
 __global__ void bf16_argmax_reduce_kernel(const float* pmax, const int* pidx, int ntiles, int pstride, int* v) {
