@@ -153,19 +153,26 @@ def build_workload(name, seed=MODEL_SEED):
     return dict(cfg=cfg, model=model, sess=sess, batch=batch, ctxs=ctxs, k=k, p=p, drafts=drafts, name=name)
 
 
-def one_step(w, collect=None):
+def one_step(w, collect=None, wall=None):
+    """One pass of the hot path.  wall, if given, receives the host wall time of the three calls (the two
+    verify calls return only after the stream has drained, so the inject call's time shows up in the next)."""
     sess = w["sess"]
+    t0 = time.perf_counter()
     sess.draft_inject(w["drafts"])
     if collect is not None:
         collect(sess.kernel_times(), "inject")
     a, nxt = sess.verify_intermediate()
+    t1 = time.perf_counter()
     if collect is not None:
         collect(sess.kernel_times(), "inter")
     f, fn, com = sess.verify_full()
+    t2 = time.perf_counter()
     if collect is not None:
         collect(sess.kernel_times(), "full")
     for b in range(w["batch"]):
         sess.rollback(b, 0b111, w["ctxs"][b])
+    if wall is not None:
+        wall.append((t1 - t0, t2 - t1))
     return a, f
 
 
@@ -251,10 +258,13 @@ def main():
         a, f = one_step(w)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    wall = []
     for _ in range(args.steps):
-        a, f = one_step(w)
+        a, f = one_step(w, wall=wall)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    t_i = float(np.median([x[0] for x in wall]))     # draft_inject (G1) + verify_intermediate (G2, head, accept)
+    t_f = float(np.median([x[1] for x in wall]))     # verify_full (catch-up row, G3, head, accept, commit)
     ms_per_step = 1e3 * elapsed / args.steps
     value = w["batch"] * w["k"] * args.steps / elapsed
 
@@ -297,6 +307,9 @@ def main():
                    "step": "draft_inject(G1) + verify_intermediate(G2) + verify_full(G1+G2 catch-up row, G3) + rollback",
                    "accepted_inter": [int(x) for x in a], "accepted_full": [int(x) for x in f]},
         "roofline": roofline,
+        "phase_ms_median": {"inject_plus_verify_intermediate": 1e3 * t_i, "verify_full": 1e3 * t_f},
+        "verified_tokens_per_s_by_stage": {"intermediate": w["batch"] * w["k"] / t_i,
+                                           "full": float(np.sum(np.asarray(a) + 1)) / t_f},
         "step_bytes": sb, "step_hbm_frac": sb / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms_per_step": kernel_ms,
     }

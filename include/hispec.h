@@ -172,6 +172,9 @@ int ee_debug_last_logits(ee_session* s, float* host_out, int max_rows, int32_t* 
 int ee_debug_last_hidden(ee_session* s, float* host_out, int max_rows, int32_t* n_rows);  /* [rows, d]     */
 /* K and V of `n` positions from pos0 of one layer, logical layout [n, n_kv_heads, head_dim]. */
 int ee_debug_read_kv(ee_session* s, int seq, int layer, int pos0, int n, float* k_out, float* v_out);
+/* The reverse, for tests that plant a KV context instead of building it (same layout, host in; values are
+ * rounded to the cache's element type; the range must lie in pages the sequence owns). */
+int ee_debug_write_kv(ee_session* s, int seq, int layer, int pos0, int n, const float* k_in, const float* v_in);
 /* Overwrite every dead KV entry (position >= the group's length, in owned pages) of a sequence
  * with NaN: a test that pruned entries can never leak into a later result. */
 int ee_debug_poison_dead_kv(ee_session* s, int seq);

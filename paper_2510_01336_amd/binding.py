@@ -16,7 +16,7 @@ __all__ = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
-    "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv",
+    "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
     "EE_F32", "EE_BF16", "TENSOR_IDS", "EXPORTED_SYMBOLS",
 ]
@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
-    "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv",
+    "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
 ]
 
@@ -84,6 +84,7 @@ def _load():
         "ee_debug_last_logits": (C.c_int, [vp, f32p, C.c_int, i32p]),
         "ee_debug_last_hidden": (C.c_int, [vp, f32p, C.c_int, i32p]),
         "ee_debug_read_kv": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, C.c_int, f32p, f32p]),
+        "ee_debug_write_kv": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, C.c_int, f32p, f32p]),
         "ee_debug_poison_dead_kv": (C.c_int, [vp, C.c_int]),
         "ee_debug_time_kernels": (C.c_int, [vp, C.c_int]),
         "ee_debug_kernel_times": (C.c_int, [vp, i32p, C.POINTER(C.c_char_p), f32p, i32p]),
@@ -282,6 +283,12 @@ def ee_debug_read_kv(session: int, seq: int, layer: int, pos0: int, n: int, n_kv
     return k, v
 
 
+def ee_debug_write_kv(session: int, seq: int, layer: int, pos0: int, k: np.ndarray, v: np.ndarray) -> None:
+    k, v = np.ascontiguousarray(k, np.float32), np.ascontiguousarray(v, np.float32)
+    assert k.shape == v.shape and k.ndim == 3
+    _chk(lib.ee_debug_write_kv(session, seq, layer, pos0, k.shape[0], _p_f32(k), _p_f32(v)))
+
+
 def ee_debug_poison_dead_kv(session: int, seq: int) -> None:
     _chk(lib.ee_debug_poison_dead_kv(session, seq))
 
@@ -384,6 +391,9 @@ class Session:
 
     def read_kv(self, seq: int, layer: int, pos0: int, n: int):
         return ee_debug_read_kv(self.handle, seq, layer, pos0, n, self.model.cfg.n_kv_heads, self.model.cfg.head_dim)
+
+    def write_kv(self, seq: int, layer: int, pos0: int, k: np.ndarray, v: np.ndarray) -> None:
+        ee_debug_write_kv(self.handle, seq, layer, pos0, k, v)
 
     def poison_dead_kv(self, seq: int) -> None:
         ee_debug_poison_dead_kv(self.handle, seq)

@@ -18,6 +18,8 @@ void k_fill_nan_dead_kv(hipStream_t st, bool bf16, void* kv, const int* pages, i
                         int layer0, int layer1, int n_pages, int n_kv, int D);
 void k_read_kv(hipStream_t st, bool bf16, const void* kv, const int* pages, int layer, int pos0, int n,
                int n_pages, int n_kv, int D, float* k_out, float* v_out);
+void k_write_kv(hipStream_t st, bool bf16, void* kv, const int* pages, int layer, int pos0, int n, int n_pages, int n_kv, int D,
+                const float* k_in, const float* v_in);
 
 // ---- fp32 reference-precision path (EE_F32 models) -----------------------------------------
 void f32_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, float* out, int M, int d);

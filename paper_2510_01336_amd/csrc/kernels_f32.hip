@@ -122,6 +122,23 @@ void k_read_kv(hipStream_t st, bool bf16, const void* kv, const int* pages, int 
                      n_pages, n_kv, D, k_out, v_out);
 }
 
+__global__ void write_kv_kernel(void* kv, int bf16, const int* pages, int layer, int pos0, int n, int n_pages, int n_kv, int D,
+                                const float* k_in, const float* v_in) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n * n_kv * D) return;
+  int d = i % D, kvh = (i / D) % n_kv, p = pos0 + i / (D * n_kv);
+  size_t slab = kv_slab(layer, pages[p / EE_PAGE], kvh, n_pages, n_kv, D);
+  size_t ko = slab + k_page_off(p % EE_PAGE, d, D), vo = slab + EE_PAGE * D + v_page_off(p % EE_PAGE, d, D);
+  if (bf16) { ((bf16_t*)kv)[ko] = f32_to_bf16(k_in[i]); ((bf16_t*)kv)[vo] = f32_to_bf16(v_in[i]); }
+  else { ((float*)kv)[ko] = k_in[i]; ((float*)kv)[vo] = v_in[i]; }
+}
+void k_write_kv(hipStream_t st, bool bf16, void* kv, const int* pages, int layer, int pos0, int n, int n_pages, int n_kv, int D,
+                const float* k_in, const float* v_in) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(write_kv_kernel, dim3(ceil_div(n * n_kv * D, 256)), dim3(256), 0, st, kv, (int)bf16, pages, layer, pos0, n,
+                     n_pages, n_kv, D, k_in, v_in);
+}
+
 // Plain streaming copy (16 bytes per lane, grid-stride): the known-size kernel against which hardware
 // byte counters are calibrated when HBM traffic of the other kernels is measured.
 __global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {

@@ -845,6 +845,29 @@ extern "C" int ee_debug_read_kv(ee_session* s, int seq, int layer, int pos0, int
   (void)hipFree(stage);
   return rc;
 }
+extern "C" int ee_debug_write_kv(ee_session* s, int seq, int layer, int pos0, int n, const float* k_in, const float* v_in) {
+  if (!s || !k_in || !v_in || seq < 0 || seq >= s->B) { ee_set_error("bad argument"); return EE_ERR_ARG; }
+  const ee_config& c = s->m->cfg;
+  const SeqState& q = s->seq[seq];
+  if (layer < 0 || layer >= c.n_layers || pos0 < 0 || n < 0 || pos0 + n > (int)q.pages.size() * EE_PAGE) { ee_set_error("KV range not owned by the sequence"); return EE_ERR_ARG; }
+  if (!n) return EE_OK;
+  size_t cnt = (size_t)n * c.n_kv_heads * c.head_dim;
+  float* stage = nullptr;
+  HIP_TRY(hipMalloc(&stage, 2 * cnt * sizeof(float)));
+  int rc = upload_pages(s, seq);
+  if (rc == EE_OK) {
+    hipError_t e = hipMemcpy(stage, k_in, cnt * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(stage + cnt, v_in, cnt * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess) {
+      k_write_kv(s->st, s->m->bf16, s->kv, s->page_scratch, layer, pos0, n, s->n_pages, c.n_kv_heads, c.head_dim, stage, stage + cnt);
+      e = hipStreamSynchronize(s->st);
+    }
+    if (e != hipSuccess) { ee_set_error("write_kv: %s", hipGetErrorString(e)); rc = EE_ERR_HIP; }
+  }
+  (void)hipFree(stage);
+  return rc;
+}
+
 extern "C" int ee_debug_poison_dead_kv(ee_session* s, int seq) {
   if (!s || seq < 0 || seq >= s->B) { ee_set_error("bad argument"); return EE_ERR_ARG; }
   const ee_config& c = s->m->cfg;
