@@ -196,14 +196,19 @@ def cpu_baseline(w):
     cache.K[l, :ctx] = eo.round_bf16(rng.normal(size=(ctx, cfg.n_kv_heads, cfg.head_dim)))
     cache.V[l, :ctx] = eo.round_bf16(rng.normal(size=(ctx, cfg.n_kv_heads, cfg.head_dim)))
     x = rng.normal(size=(rows, cfg.d_model))
-    t0 = time.perf_counter()
-    for _ in range(batch):
-        y = model.layer(l, x, ctx + np.arange(rows), cache)
-    t_layer = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    for _ in range(batch):
-        eo.argmax_rows(model.exit_logits(y))
-    t_head = time.perf_counter() - t0
+    # repeated until about ten seconds of layer passes and five of exit heads have been timed
+    reps_l, t0 = 0, time.perf_counter()
+    while reps_l < 3 or time.perf_counter() - t0 < 10.0:
+        for _ in range(batch):
+            y = model.layer(l, x, ctx + np.arange(rows), cache)
+        reps_l += 1
+    t_layer = (time.perf_counter() - t0) / reps_l
+    reps_h, t0 = 0, time.perf_counter()
+    while reps_h < 3 or time.perf_counter() - t0 < 5.0:
+        for _ in range(batch):
+            eo.argmax_rows(model.exit_logits(y))
+        reps_h += 1
+    t_head = (time.perf_counter() - t0) / reps_h
     layers = cfg.n_layers + cfg.exit_inter      # G1 + G2 + G3 + catch-up row through G1+G2
     t_step = layers * t_layer + 2 * t_head
     try:
@@ -212,9 +217,9 @@ def cpu_baseline(w):
     except Exception:
         cores = os.cpu_count() or 1
     return {"value": batch * k / t_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"1 of {layers} layer passes ({rows} rows, KV context {ctx}, random KV) timed at "
-                      f"{t_layer:.2f} s + 1 of 2 exit heads at {t_head:.2f} s, scaled to a full step "
-                      f"({t_step:.1f} s); float64 numpy"}
+            "sample": f"1 of {layers} layer passes ({rows} rows, KV context {ctx}, random KV) timed {reps_l} times at "
+                      f"{t_layer:.2f} s each + 1 of 2 exit heads {reps_h} times at {t_head:.2f} s each, scaled to a full "
+                      f"step ({t_step:.1f} s); float64 numpy"}
 
 
 def calibration_copy(stream_ptr):

@@ -25,15 +25,41 @@ class LoopStats:
     per_round_accept: List[int] = field(default_factory=list)
 
 
-def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, every: Optional[int] = None):
+def adapt_step(value: int, rate: float, tau_low: float, tau_high: float, lo: int, hi: int) -> int:
+    """One update of the adaptive hyper-parameter rule (App. J, the N_d and N_i update equations, which
+    differ only in their thresholds and bounds): one up at an acceptance rate of tau_high or more, one down
+    below tau_low, unchanged in between, clamped to [lo, hi]."""
+    if rate >= tau_high:
+        return min(hi, value + 1)
+    if rate < tau_low:
+        return max(lo, value - 1)
+    return value
+
+
+@dataclass
+class AdaptivePolicy:
+    """App. J: N_d follows the intermediate verifier's acceptance rate of the last round (thresholds 0.5 / 0.8),
+    N_i the full model's acceptance rate of the last full verification (0.3 / 0.8)."""
+    nd_min: int = 1
+    nd_max: int = 3
+    ni_min: int = 3
+    ni_max: int = 8
+    nd_tau: tuple = (0.5, 0.8)
+    ni_tau: tuple = (0.3, 0.8)
+
+
+def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, every: Optional[int] = None,
+                    adaptive: Optional[AdaptivePolicy] = None):
     """Generate n_new tokens per sequence after the session's current context (ee_prefill done, nothing pending).
 
     Exactly one of n_i (fire the full verification when every sequence's tentative buffer holds >= n_i
-    tokens) and every (fire after that many intermediate rounds) is given.  Returns (tokens [batch, n_new],
-    LoopStats).  The committed stream may run a few tokens past n_new inside the session; the returned
-    rows are cut to n_new.
+    tokens) and every (fire after that many intermediate rounds) is given.  With `adaptive` (needs n_i), k
+    and n_i are the starting values of N_d and N_i and move by the rule of App. J.  Returns (tokens
+    [batch, n_new], LoopStats).  The committed stream may run a few tokens past n_new inside the session;
+    the returned rows are cut to n_new.
     """
     assert (n_i is None) != (every is None)
+    assert adaptive is None or n_i is not None
     B = sess.batch
     out: List[List[int]] = [[] for _ in range(B)]
     st = LoopStats()
@@ -47,6 +73,9 @@ def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, ever
             st.drafted += B * k
             st.accepted_inter += int(a.sum())
             st.per_round_accept.append(int(a.sum()))
+            if adaptive is not None:
+                k_used = k
+                k = adapt_step(k, float(a.sum()) / (B * k_used), *adaptive.nd_tau, adaptive.nd_min, adaptive.nd_max)
             _, nv = sess.counts()
             if (n_i is not None and int(nv.min()) >= n_i) or (every is not None and rounds >= every):
                 break
@@ -57,6 +86,9 @@ def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, ever
         st.full_verifies += 1
         st.tentative += int(nv.sum())
         st.accepted_full += int(np.minimum(f, nv).sum())
+        if adaptive is not None:
+            n_i = adapt_step(n_i, float(np.minimum(f, nv).sum()) / max(1, int(nv.sum())), *adaptive.ni_tau,
+                             adaptive.ni_min, adaptive.ni_max)
         for b in range(B):
             out[b].extend(int(t) for t in com[b])
             st.committed += len(com[b])

@@ -56,9 +56,16 @@ def test_ar_decode_matches_oracle(cfg):
     sess.close(); model.close()
 
 
-@pytest.mark.parametrize("policy", [dict(n_i=6), dict(every=2)], ids=["n_i6", "every2"])
+def _adaptive():
+    from paper_2510_01336_amd.loop import AdaptivePolicy
+    return dict(n_i=4, adaptive=AdaptivePolicy(nd_max=4))
+
+
+@pytest.mark.parametrize("policy", [dict(n_i=6), dict(every=2), "adaptive"], ids=["n_i6", "every2", "adaptive"])
 def test_hispec_stream_equals_vanilla_stream_on_gpu(policy):
     from paper_2510_01336_amd.loop import hispec_generate
+    if policy == "adaptive":
+        policy = _adaptive()
     cfg = synth.tiny_config(gamma=(1.0, 0.3, 0.3))       # damped upper groups: the exits agree often, not always
     n_new, k, ctx = 48, 4, [32, 19]
     prompts = [synth.gen_prompt(cfg.vocab, n, 11 + i) for i, n in enumerate(ctx)]
