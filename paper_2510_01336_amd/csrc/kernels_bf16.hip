@@ -681,18 +681,28 @@ void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles,
   bf16_gemm_cfg(st, epi, W, ntiles, ktiles, A, M, N, out, nw, ksplit, U);
 }
 
-__global__ void bf16_argmax_reduce_kernel(const float* pmax, const int* pidx, int ntiles, int pstride, int* v) {
-  __shared__ float bv[256];
-  __shared__ int bi[256];
-  int m = blockIdx.x;
+// one workgroup of 1024 threads per row; eight independent partials per thread are requested at once (the
+// partials of a row lie a row-stride apart, one cache line each, so the kernel is a chain of load latencies)
+__global__ __launch_bounds__(1024) void bf16_argmax_reduce_kernel(const float* __restrict__ pmax, const int* __restrict__ pidx,
+                                                                   int ntiles, int pstride, int* v) {
+  __shared__ float bv[1024];
+  __shared__ int bi[1024];
+  const int m = blockIdx.x;
   float best = -INFINITY; int idx = 0x7fffffff;
-  for (int t = threadIdx.x; t < ntiles; t += blockDim.x) {
-    float x = pmax[(size_t)t * pstride + m]; int xi = pidx[(size_t)t * pstride + m];
-    if (x > best || (x == best && xi < idx)) { best = x; idx = xi; }
+  for (int t0 = threadIdx.x; t0 < ntiles; t0 += 8 * 1024) {
+    float x[8]; int xi[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int t = min(t0 + j * 1024, ntiles - 1);
+      x[j] = pmax[(size_t)t * pstride + m]; xi[j] = pidx[(size_t)t * pstride + m];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)      // a clamped duplicate carries the same (value, index): harmless
+      if (x[j] > best || (x[j] == best && xi[j] < idx)) { best = x[j]; idx = xi[j]; }
   }
   bv[threadIdx.x] = best; bi[threadIdx.x] = idx;
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
+  for (int s = 512; s > 0; s >>= 1) {
     if (threadIdx.x < s) {
       float o = bv[threadIdx.x + s]; int oi = bi[threadIdx.x + s];
       if (o > bv[threadIdx.x] || (o == bv[threadIdx.x] && oi < bi[threadIdx.x])) { bv[threadIdx.x] = o; bi[threadIdx.x] = oi; }
@@ -702,7 +712,7 @@ __global__ void bf16_argmax_reduce_kernel(const float* pmax, const int* pidx, in
   if (threadIdx.x == 0) v[m] = bi[0];
 }
 void bf16_argmax_reduce(hipStream_t st, const float* pmax, const int* pidx, int ntiles, int pstride, int M, int* v) {
-  hipLaunchKernelGGL(bf16_argmax_reduce_kernel, dim3(M), dim3(256), 0, st, pmax, pidx, ntiles, pstride, v);
+  hipLaunchKernelGGL(bf16_argmax_reduce_kernel, dim3(M), dim3(1024), 0, st, pmax, pidx, ntiles, pstride, v);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -397,10 +397,13 @@ static void exit_head(ee_session* s, int M) {
     GemmOut o;
     const int Mp = s->Mp;
     o.nin.ssq = s->ssq; o.nin.n_part = c.d_model / 16; o.nin.stride = Mp; o.nin.inv_d = 1.0f / (float)c.d_model; o.nin.eps = c.rms_eps;
-    o.pmax = s->pmax; o.pidx = s->pidx; o.pstride = Mp;
+    // (max, arg max) partials [tile][row] with the rows packed to the call's row tiles: the reduction then walks
+    // a compact array instead of one memory page per tile
+    const int pstride = ceil_div(M, 16) * 16;
+    o.pmax = s->pmax; o.pidx = s->pidx; o.pstride = pstride;
     if (s->debug_logits) { o.Y = s->LOGITS; o.ldy = c.vocab; }
     KF(KF_GEMM_HEAD, gemm(s, EPI_ARGMAX, m->head, (const bf16_t*)s->XN, M, o));
-    KF(KF_ARGMAX, bf16_argmax_reduce(st, s->pmax, s->pidx, m->head.ntiles(), Mp, M, s->vtok));
+    KF(KF_ARGMAX, bf16_argmax_reduce(st, s->pmax, s->pidx, m->head.ntiles(), pstride, M, s->vtok));
   } else {
     KF(KF_NORM, f32_rmsnorm(st, s->X, gf, c.rms_eps, (float*)s->XN, M, c.d_model));
     KF(KF_GEMM_HEAD, f32_gemm(st, (const float*)s->XN, c.d_model, (const float*)(m->base + m->head.off), s->LOGITS, c.vocab, M,
