@@ -248,6 +248,54 @@ def leading_substring_verify(S: Sequence[int], v: Sequence[int]) -> Tuple[int, L
 # decoding state machine (Algorithm 2 with the cache management of Sec. 3.2)
 # ----------------------------------------------------------------------------
 
+def softmax_rows(logits: np.ndarray) -> np.ndarray:
+    """p = softmax(logits) per row (the exit distributions p_L of Sec. 3.1)."""
+    x = np.asarray(logits, F64)
+    e = np.exp(x - x.max(axis=-1, keepdims=True))
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def sample_inverse_cdf(w: np.ndarray, u: float) -> Tuple[int, float]:
+    """Token drawn from the distribution proportional to the non-negative weights w with the uniform
+    number u in [0, 1): the first index whose cumulative weight exceeds u * sum(w).  Also returns how far
+    u * sum(w) is from the nearest boundary of that index's interval, relative to sum(w) (a margin for
+    comparisons against implementations that add in another order)."""
+    c = np.cumsum(np.asarray(w, F64))
+    total = c[-1]
+    assert total > 0
+    t = u * total
+    idx = int(np.searchsorted(c, t, side="right"))
+    last = int(np.nonzero(w)[0][-1])
+    idx = min(idx, last)
+    lo = c[idx - 1] if idx > 0 else 0.0
+    return idx, float(min(t - lo, c[idx] - t) / total)
+
+
+def rejection_verify(S: Sequence[int], P_draft: np.ndarray, P_target: np.ndarray, u_acc: Sequence[float],
+                     u_res: float) -> Tuple[int, List[int], float]:
+    """The acceptance rule of App. G for one block: draft token S[j], drawn from row j of P_draft, is accepted
+    when u_acc[j] < min(1, P_target[j, S[j]] / P_draft[j, S[j]]); at the first rejection the block is cut and
+    a replacement is drawn (with u_res) from the residual distribution max(0, P_target[j] - P_draft[j])
+    normalised.  When every token is accepted and P_target has one more row, the next token is drawn from that
+    row (the target's own token after a fully accepted block).  Returns (number accepted, accepted tokens plus
+    the drawn one, smallest margin of the decisions taken: |u - ratio| of the accept tests and the interval
+    margin of the draw)."""
+    k = len(S)
+    margin = np.inf
+    for j in range(k):
+        s = int(S[j])
+        ratio = min(1.0, float(P_target[j, s] / P_draft[j, s]))
+        margin = min(margin, abs(float(u_acc[j]) - ratio) if ratio < 1.0 else np.inf)
+        if float(u_acc[j]) < ratio:
+            continue
+        tok, mg = sample_inverse_cdf(np.maximum(0.0, P_target[j] - P_draft[j]), u_res)
+        return j, [int(t) for t in S[:j]] + [tok], float(min(margin, mg))
+    if len(P_target) > k:
+        tok, mg = sample_inverse_cdf(P_target[k], u_res)
+        return k, [int(t) for t in S] + [tok], float(min(margin, mg))
+    return k, [int(t) for t in S], float(margin)
+
+
 class Sequence_:
     """One sequence: committed tokens C, tentative buffer V, shared KV cache with three
     group lengths, and the buffered exit hidden states H_d (draft) and H_i (intermediate).
@@ -265,6 +313,8 @@ class Sequence_:
         self.len = [0, 0, 0]
         self.H_d: List[np.ndarray] = []
         self.H_i: List[np.ndarray] = []
+        self.P_d: List[np.ndarray] = []      # rejection sampling only: the distributions the draft tokens were drawn from
+        self.P_i: List[np.ndarray] = []      # ... and the L_i distributions of the tokens in V
         self.prompt_len = 0
 
     @property
@@ -282,6 +332,7 @@ class HiSpecOracle:
         self.bonus_inter, self.bonus_full, self.poison = bonus_inter, bonus_full, poison
         self.last_logits: Optional[np.ndarray] = None
         self.last_hidden: Optional[np.ndarray] = None
+        self.last_margin: float = np.inf     # rejection sampling: smallest decision margin of the last call
 
     # -- cache pruning -------------------------------------------------------
     def _set_len(self, seq: Sequence_, g: int, new_len: int) -> None:
@@ -301,7 +352,7 @@ class HiSpecOracle:
         reaches into the committed tokens, V is emptied and G3 (bit 2) must be cut to the same
         length.  G3 alone can never shrink: its KV for committed positions could not be rebuilt.
         """
-        seq.H_d, seq.S = [], []
+        seq.H_d, seq.S, seq.P_d = [], [], []
         self._set_len(seq, 0, seq.len[1])
         m12 = group_mask & 0b011
         if m12 not in (0, 0b011):
@@ -316,12 +367,13 @@ class HiSpecOracle:
         if n_t <= len(seq.C):
             if new_len < seq.len[2] and not (group_mask & 0b100):
                 raise ValueError("cut reaches committed tokens: G3 must roll back too")
-            seq.C, seq.V, seq.H_i = seq.C[:n_t], [], []
+            seq.C, seq.V, seq.H_i, seq.P_i = seq.C[:n_t], [], [], []
             self._set_len(seq, 2, new_len)
             seq.prompt_len = min(seq.prompt_len, new_len)
         else:
             seq.V = seq.V[:n_t - len(seq.C)]
             seq.H_i = seq.H_i[:len(seq.V)]
+            seq.P_i = seq.P_i[:len(seq.V)]
         self._set_len(seq, 0, new_len)
         self._set_len(seq, 1, new_len)
 
@@ -339,10 +391,13 @@ class HiSpecOracle:
         return c0
 
     # -- drafting at exit L_d ------------------------------------------------
-    def draft(self, seq: Sequence_, k: int) -> List[int]:
+    def draft(self, seq: Sequence_, k: int, u: Optional[Sequence[float]] = None) -> List[int]:
         """Generate(L_d, x||V, k): k sequential shallow passes (plus, in bonus mode, one more
-        G1-only pass so the last draft token also owns an L_d hidden row)."""
+        G1-only pass so the last draft token also owns an L_d hidden row).  With uniform numbers u[0..k-1]
+        the tokens are drawn from p_{L_d} (App. G) instead of taken as its arg max, and the
+        distributions are kept for the acceptance tests."""
         assert not seq.H_d
+        seq.P_d = []
         G1 = self.spec.group_layers(0)
         p0 = len(seq.T) - 1
         assert seq.len[0] == p0
@@ -354,7 +409,13 @@ class HiSpecOracle:
             if j < k:
                 lg = self.m.exit_logits(x)
                 logs.append(lg[0])
-                tok = int(argmax_rows(lg)[0])
+                if u is None:
+                    tok = int(argmax_rows(lg)[0])
+                else:
+                    pd = softmax_rows(lg)[0]
+                    tok, mg = sample_inverse_cdf(pd, float(u[j]))
+                    seq.P_d.append(pd)
+                    self.last_margin = min(self.last_margin, mg) if j else mg
                 S.append(tok)
         seq.len[0] = p0 + rows
         seq.S = S
@@ -378,7 +439,7 @@ class HiSpecOracle:
         self.last_hidden = x
 
     # -- intermediate verification at exit L_i ---------------------------------
-    def verify_intermediate(self, seq: Sequence_) -> Tuple[int, int]:
+    def verify_intermediate(self, seq: Sequence_, rs: Optional[Tuple[Sequence[float], float]] = None) -> Tuple[int, int]:
         """LeadingSubstringVerify(S, L_i, x||V); appends the result to V, keeps the hidden rows of
         surviving positions in H_i and prunes G1/G2 KV.  Returns (a, next_token); next_token is
         -1 when everything matched and no bonus row exists."""
@@ -390,8 +451,14 @@ class HiSpecOracle:
         Y = self.m.run_layers(G2, np.stack(seq.H_d), p0 + np.arange(rows), seq.cache)
         seq.len[1] = p0 + rows
         logits = self.m.exit_logits(Y)
-        v = argmax_rows(logits)
-        a, vhat = leading_substring_verify(seq.S, v)
+        if rs is None:
+            v = argmax_rows(logits)
+            a, vhat = leading_substring_verify(seq.S, v)
+        else:       # App. G: rs = (u_acc[k], u_res); the tokens kept are distributed as p_{L_i}
+            P = softmax_rows(logits)
+            a, vhat, self.last_margin = rejection_verify(seq.S, np.stack(seq.P_d), P, rs[0], rs[1])
+            seq.P_i = seq.P_i + [P[r] for r in range(len(vhat))]
+            seq.P_d = []
         keep = len(vhat)                       # rows whose input token is now in T
         seq.V = seq.V + vhat
         seq.H_i = seq.H_i + [Y[r] for r in range(keep)]
@@ -402,7 +469,7 @@ class HiSpecOracle:
         return a, (vhat[-1] if len(vhat) > a else -1)
 
     # -- full verification at L_f ----------------------------------------------
-    def verify_full(self, seq: Sequence_) -> Tuple[int, int, List[int]]:
+    def verify_full(self, seq: Sequence_, rs: Optional[Tuple[Sequence[float], float]] = None) -> Tuple[int, int, List[int]]:
         """LeadingSubstringVerify(V, L_f, x): consumes the buffered L_i hidden rows, commits the
         accepted prefix (+ the target's own token) and prunes all three groups.
         Returns (f, next_token, committed_tokens)."""
@@ -423,10 +490,14 @@ class HiSpecOracle:
         Z = self.m.run_layers(sp.group_layers(2), np.stack(rows_h), (nc - 1) + np.arange(rows), seq.cache)
         seq.len[2] = nc - 1 + rows
         logits = self.m.exit_logits(Z)
-        w = argmax_rows(logits)
-        f, F = leading_substring_verify(seq.V, w)
+        if rs is None:
+            w = argmax_rows(logits)
+            f, F = leading_substring_verify(seq.V, w)
+        else:       # App. G, second stage: V (distributed as p_{L_i}) is the draft, p_{L_f} the target
+            assert len(seq.P_i) == nv
+            f, F, self.last_margin = rejection_verify(seq.V, np.stack(seq.P_i), softmax_rows(logits), rs[0], rs[1])
         seq.C = seq.C + F
-        seq.V, seq.H_i = [], []
+        seq.V, seq.H_i, seq.P_i = [], [], []
         for g in range(3):
             self._set_len(seq, g, len(seq.C) - 1)
         self.last_logits, self.last_hidden = logits, Z
