@@ -86,6 +86,17 @@ def run_e2e(args):
     toks, st = hispec_generate(sess, n_new, k, n_i=n_i)
     torch.cuda.synchronize()
     t_hs = time.perf_counter() - t0
+    # the same loop under the rejection-sampling acceptance of App. G (full distributions at all three exits)
+    from paper_2510_01336_amd.loop import hispec_generate_sampling
+    sess.enable_sampling()
+    sess.prefill(prompt)
+    hispec_generate_sampling(sess, 2 * k, k, n_i, np.random.default_rng(1))      # warm-up
+    sess.prefill(prompt)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    _, st_rs = hispec_generate_sampling(sess, n_new, k, n_i, np.random.default_rng(2))
+    torch.cuda.synchronize()
+    t_rs = time.perf_counter() - t0
     sess.prefill(prompt)
     sess.decode_ar(4)                                             # warm-up
     sess.prefill(prompt)
@@ -110,7 +121,13 @@ def run_e2e(args):
                    "draft_accept_rate_at_L_i": st.accepted_inter / max(1, st.drafted),
                    "tentative_accept_rate_at_L_f": st.accepted_full / max(1, st.tentative),
                    "tokens_per_round": st.committed / max(1, st.rounds),
-                   "leading_tokens_equal_to_vanilla_stream": same},
+                   "reject_rate_at_L_i": 1.0 - st.accepted_inter / max(1, st.drafted),
+                   "false_accept_rate": (st.tentative - st.accepted_full) / max(1, st.drafted),
+                   "leading_tokens_equal_to_vanilla_stream": same,
+                   "rejection_sampling": {"tokens_per_s": n_new / t_rs, "speedup_vs_vanilla": t_ar / t_rs,
+                                          "draft_accept_rate_at_L_i": st_rs.accepted_inter / max(1, st_rs.drafted),
+                                          "tentative_accept_rate_at_L_f": st_rs.accepted_full / max(1, st_rs.tentative),
+                                          "tokens_per_round": st_rs.committed / max(1, st_rs.rounds)}},
     }
     print(json.dumps(out))
 

@@ -162,6 +162,33 @@ int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_accept, int3
  * EE_ERR_ARG if new_len exceeds the current length or the mask is inconsistent. */
 int kv_rollback(ee_session* s, int seq, int group_mask, int new_len);
 
+/* ---- rejection-sampling acceptance (App. G) --------------------------------------------------
+ * The same three steps with the stochastic acceptance rule in place of arg max comparison: draft tokens
+ * are drawn from p_{L_d}; a token S_j is accepted at a verifier with distribution p when
+ * u < min(1, p(S_j) / q(S_j)), q being the distribution it was drawn from; at the first rejection the block
+ * is cut and a replacement is drawn from max(0, p - q) normalised; after a fully accepted block the verifier's
+ * extra row (if the block has one) supplies the next token, drawn from p.  The full verification applies the
+ * rule again with V as the draft and its stored p_{L_i} rows as q.  All uniform numbers are inputs: host
+ * arrays of floats in [0, 1) (EE_ERR_ARG otherwise).  Draws are by inverse CDF over the token ids in order.
+ * The distributions are kept in a caller-owned device arena of ee_sampling_bytes() bytes (2 * batch *
+ * max_rows * vocab floats and the uniform numbers), attached once per session; 256-byte aligned.
+ * The sampling calls and the arg max calls may not be mixed within one round (EE_ERR_STATE). */
+size_t ee_sampling_bytes(const ee_session* s);
+int ee_sampling_attach(ee_session* s, void* dev_arena, size_t arena_bytes);
+/* u: host [batch, k], one number per drafted token.  Otherwise as ee_draft. */
+int ee_draft_sample(ee_session* s, int k, const float* u, int32_t* draft);
+/* u_acc: host [batch, u_stride], number j tests draft token j (u_stride >= k); u_res: host [batch], the
+ * replacement / next-token draw.  Outputs and state transition as ee_verify_intermediate. */
+int ee_verify_intermediate_rs(ee_session* s, const float* u_acc, int u_stride, const float* u_res,
+                              int32_t* n_accept, int32_t* next_token);
+/* u_acc: host [batch, u_stride] (u_stride >= the longest tentative buffer).  Otherwise as ee_verify_full. */
+int ee_verify_full_rs(ee_session* s, const uint8_t* active, const float* u_acc, int u_stride, const float* u_res,
+                      int32_t* n_accept, int32_t* next_token, int32_t* committed, int32_t* n_committed);
+/* Test support: n rows from row0 of one sequence's stored distributions (which = 0: the draft distributions of
+ * the pending block, 1: the L_i distributions of the tentative tokens), host out [n, vocab].  After a sampling
+ * verify call ee_debug_last_logits returns that call's target distributions instead of logits. */
+int ee_debug_read_dist(ee_session* s, int which, int seq, int row0, int n, float* host_out);
+
 /* ---- introspection (parity tests; not part of the timed path) ---------------------------- */
 int ee_get_lengths(const ee_session* s, int32_t* len_3_by_batch);           /* host [batch,3]      */
 int ee_get_counts(const ee_session* s, int32_t* n_committed, int32_t* n_tentative); /* [batch] each */

@@ -15,7 +15,8 @@ __all__ = [
     "lib", "lib_path", "EEError", "ee_config", "make_config", "Model", "Session",
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_decode_ar", "ee_draft", "ee_draft_inject",
-    "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
+    "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
+    "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
     "EE_F32", "EE_BF16", "TENSOR_IDS", "EXPORTED_SYMBOLS",
@@ -28,7 +29,8 @@ TENSOR_IDS = {"emb": 0, "head": 1, "gfinal": 2, "g1": 3, "wq": 4, "wk": 5, "wv":
 EXPORTED_SYMBOLS = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_decode_ar", "ee_draft", "ee_draft_inject",
-    "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
+    "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
+    "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
 ]
@@ -77,6 +79,12 @@ def _load():
         "ee_verify_intermediate": (C.c_int, [vp, i32p, i32p]),
         "ee_verify_full": (C.c_int, [vp, C.POINTER(C.c_uint8), i32p, i32p, i32p, i32p]),
         "kv_rollback": (C.c_int, [vp, C.c_int, C.c_int, C.c_int]),
+        "ee_sampling_bytes": (C.c_size_t, [vp]),
+        "ee_sampling_attach": (C.c_int, [vp, vp, C.c_size_t]),
+        "ee_draft_sample": (C.c_int, [vp, C.c_int, f32p, i32p]),
+        "ee_debug_read_dist": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, C.c_int, f32p]),
+        "ee_verify_intermediate_rs": (C.c_int, [vp, f32p, C.c_int, f32p, i32p, i32p]),
+        "ee_verify_full_rs": (C.c_int, [vp, C.POINTER(C.c_uint8), f32p, C.c_int, f32p, i32p, i32p, i32p, i32p]),
         "ee_get_lengths": (C.c_int, [vp, i32p]),
         "ee_get_counts": (C.c_int, [vp, i32p, i32p]),
         "ee_get_tokens": (C.c_int, [vp, C.c_int, i32p, C.c_int, i32p]),
@@ -239,6 +247,52 @@ def ee_verify_full(session: int, batch: int, max_rows: int, active: Optional[Seq
     return a, n, [com[b, :nc[b]].tolist() for b in range(batch)]
 
 
+def _f32c(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def ee_sampling_bytes(session: int) -> int:
+    return int(lib.ee_sampling_bytes(session))
+
+
+def ee_sampling_attach(session: int, dev_ptr: int, nbytes: int) -> None:
+    _chk(lib.ee_sampling_attach(session, dev_ptr, nbytes))
+
+
+def ee_debug_read_dist(session: int, which: int, seq: int, row0: int, n: int, vocab: int) -> np.ndarray:
+    out = np.empty((n, vocab), np.float32)
+    _chk(lib.ee_debug_read_dist(session, which, seq, row0, n, _p_f32(out)))
+    return out
+
+
+def ee_draft_sample(session: int, batch: int, k: int, u: np.ndarray) -> np.ndarray:
+    u = _f32c(u).reshape(batch, k)
+    out = np.empty((batch, k), np.int32)
+    _chk(lib.ee_draft_sample(session, k, _p_f32(u), _p_i32(out)))
+    return out
+
+
+def ee_verify_intermediate_rs(session: int, batch: int, u_acc: np.ndarray, u_res: np.ndarray):
+    u_acc, u_res = _f32c(u_acc).reshape(batch, -1), _f32c(u_res).reshape(batch)
+    a, n = np.empty(batch, np.int32), np.empty(batch, np.int32)
+    _chk(lib.ee_verify_intermediate_rs(session, _p_f32(u_acc), u_acc.shape[1], _p_f32(u_res), _p_i32(a), _p_i32(n)))
+    return a, n
+
+
+def ee_verify_full_rs(session: int, batch: int, max_rows: int, u_acc: np.ndarray, u_res: np.ndarray,
+                      active: Optional[Sequence[int]] = None):
+    u_acc, u_res = _f32c(u_acc).reshape(batch, -1), _f32c(u_res).reshape(batch)
+    a, n, nc = np.empty(batch, np.int32), np.empty(batch, np.int32), np.empty(batch, np.int32)
+    com = np.zeros((batch, max_rows + 1), np.int32)
+    act = None
+    if active is not None:
+        act_arr = np.ascontiguousarray(active, dtype=np.uint8)
+        act = act_arr.ctypes.data_as(C.POINTER(C.c_uint8))
+    _chk(lib.ee_verify_full_rs(session, act, _p_f32(u_acc), u_acc.shape[1], _p_f32(u_res), _p_i32(a), _p_i32(n), _p_i32(com),
+                               _p_i32(nc)))
+    return a, n, [com[b, :nc[b]].tolist() for b in range(batch)]
+
+
 def kv_rollback(session: int, seq: int, group_mask: int, new_len: int) -> None:
     _chk(lib.kv_rollback(session, seq, group_mask, new_len))
 
@@ -367,6 +421,24 @@ class Session:
 
     def verify_full(self, active=None):
         return ee_verify_full(self.handle, self.batch, self.max_rows, active)
+
+    def enable_sampling(self) -> None:
+        """Allocate and attach the buffers of the rejection-sampling calls."""
+        n = ee_sampling_bytes(self.handle)
+        self._sampling_buf, ptr = _arena(n)
+        ee_sampling_attach(self.handle, ptr, n)
+
+    def read_dist(self, which: int, seq: int, row0: int, n: int) -> np.ndarray:
+        return ee_debug_read_dist(self.handle, which, seq, row0, n, self.model.cfg.vocab)
+
+    def draft_sample(self, k: int, u: np.ndarray) -> np.ndarray:
+        return ee_draft_sample(self.handle, self.batch, k, u)
+
+    def verify_intermediate_rs(self, u_acc: np.ndarray, u_res: np.ndarray):
+        return ee_verify_intermediate_rs(self.handle, self.batch, u_acc, u_res)
+
+    def verify_full_rs(self, u_acc: np.ndarray, u_res: np.ndarray, active=None):
+        return ee_verify_full_rs(self.handle, self.batch, self.max_rows, u_acc, u_res, active)
 
     def rollback(self, seq: int, group_mask: int, new_len: int) -> None:
         kv_rollback(self.handle, seq, group_mask, new_len)

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhispec.so")
-SOURCES = ["weights.hip", "kernels_f32.hip", "kernels_bf16.hip", "session.hip"]
+SOURCES = ["weights.hip", "kernels_f32.hip", "kernels_bf16.hip", "kernels_sample.hip", "session.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

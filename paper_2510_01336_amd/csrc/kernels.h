@@ -83,3 +83,12 @@ void bf16_attention(hipStream_t st, const bf16_t* Q, const bf16_t* kv, const Cal
                     int total_qt, int max_kv_end, int Hq, int Hkv, int D, int layer, int n_pages, int pages_per_seq,
                     const AttnScratch& scr, bf16_t* out, int out_ktiles, int per);
 void bf16_argmax_reduce(hipStream_t st, const float* pmax, const int* pidx, int ntiles, int pstride, int M, int* v);
+
+// ---- rejection-sampling acceptance (kernels_sample.hip) ----
+void k_softmax_rows(hipStream_t st, const float* in, size_t in_stride, float* out, const int* out_idx, int out_add, int M, int vocab);
+void k_rs_accept(hipStream_t st, const float* Pt, const float* Pd, int pd_rows_per_seq, int vocab, const CallMeta& meta,
+                 int cand_stride, int B, const float* u_acc, int u_stride, int* n_accept);
+void k_draw_rows(hipStream_t st, const float* P, int rows_per_seq, int j, int vocab, const float* u, int u_stride, int B,
+                 int* tok_next, int* draft_out, int stride);
+void k_rs_draw(hipStream_t st, const float* Pt, const float* Pd, int pd_rows_per_seq, int vocab, const CallMeta& meta, int B,
+               const int* n_accept, const float* u_res, int* next_tok);

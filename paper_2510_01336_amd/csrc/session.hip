@@ -9,6 +9,8 @@ struct SeqState {
   std::vector<int> C, V, S;   // committed, tentative, pending draft block
   int len[3] = {0, 0, 0};     // KV length per layer group
   int n_hd = 0;               // buffered L_d hidden rows (pending draft block incl. bonus row)
+  int n_pi = 0;               // rejection sampling: tokens of V whose L_i distribution is stored
+  bool sampled = false;       // the pending draft block was drawn from p_{L_d} (its distributions are stored)
   std::vector<int> pages;     // block table
   bool started = false;
 };
@@ -34,6 +36,10 @@ struct ee_session {
   void *XN = nullptr, *Qb = nullptr, *AO = nullptr, *H = nullptr;
   float2* cs = nullptr;
   int *vtok = nullptr, *tok_next = nullptr, *draft_dev = nullptr, *out_dev = nullptr, *page_scratch = nullptr;
+  // rejection-sampling acceptance (attached separately): the distributions the draft tokens were drawn from,
+  // the L_i distributions of the tokens in V (rows [batch][max_rows][vocab]), and the call's uniform numbers
+  float *Pd = nullptr, *Pi = nullptr, *u_dev = nullptr;
+  bool need_logits = false;
   float *part_o = nullptr, *part_ml = nullptr, *pmax = nullptr, *ssq = nullptr, *gemm_part = nullptr, *inv_rms = nullptr;
   size_t part_units = 0;        // capacity of the attention split scratch in (q-tile, split) units per KV head
   int* pidx = nullptr;
@@ -401,7 +407,7 @@ static void exit_head(ee_session* s, int M) {
     // a compact array instead of one memory page per tile
     const int pstride = ceil_div(M, 16) * 16;
     o.pmax = s->pmax; o.pidx = s->pidx; o.pstride = pstride;
-    if (s->debug_logits) { o.Y = s->LOGITS; o.ldy = c.vocab; }
+    if (s->debug_logits || s->need_logits) { o.Y = s->LOGITS; o.ldy = c.vocab; }
     KF(KF_GEMM_HEAD, gemm(s, EPI_ARGMAX, m->head, (const bf16_t*)s->XN, M, o));
     KF(KF_ARGMAX, bf16_argmax_reduce(st, s->pmax, s->pidx, m->head.ntiles(), pstride, M, s->vtok));
   } else {
@@ -538,12 +544,24 @@ static int draft_precheck(ee_session* s, int k, int rows) {
   return check_capacity(s, want);
 }
 
-extern "C" int ee_draft(ee_session* s, int k, int32_t* draft) {
+// uniform numbers of a call: host -> the session's device buffer (sampling attached)
+static int upload_uniforms(ee_session* s, const float* u, size_t n, size_t at) {
+  for (size_t i = 0; i < n; ++i)
+    if (!(u[i] >= 0.0f && u[i] < 1.0f)) { ee_set_error("uniform numbers must lie in [0, 1)"); return EE_ERR_ARG; }
+  HIP_TRY(hipMemcpyAsync(s->u_dev + at, u, n * sizeof(float), hipMemcpyHostToDevice, s->st));
+  return EE_OK;
+}
+
+// u == null: arg max of p_{L_d} (Alg. 2); otherwise token j of sequence b is drawn from p_{L_d} with u[b*k + j] (App. G)
+static int draft_impl(ee_session* s, int k, int32_t* draft, const float* u) {
   if (!s || !draft) { ee_set_error("null argument"); return EE_ERR_ARG; }
   const ee_config& c = s->m->cfg;
   const int rows = k + (c.bonus_inter ? 1 : 0);
+  if (u && !s->Pd) { ee_set_error("sampling buffers are not attached (ee_sampling_attach)"); return EE_ERR_STATE; }
   EE_TRY(draft_precheck(s, k, rows));
+  if (u) EE_TRY(upload_uniforms(s, u, (size_t)s->B * k, 0));
   reset_accounting(s);
+  s->need_logits = u != nullptr;
   CallPlan p;
   p.m.assign(s->B, 1); p.p0.resize(s->B);
   for (int b = 0; b < s->B; ++b) {
@@ -564,9 +582,15 @@ extern "C" int ee_draft(ee_session* s, int k, int32_t* draft) {
     KF(KF_COPY, k_copy_rows(s->st, s->Hd, mt.row_dst, j, s->X, nullptr, p.M, c.d_model));
     if (j < k) {
       exit_head(s, p.M);
-      KF(KF_MISC, k_take_token(s->st, s->vtok, mt.row_seq, p.M, s->tok_next, s->draft_dev, s->max_rows, j));
+      if (u) {      // p_{L_d} of this position into the draft-distribution store, then the draw (row r = sequence r here)
+        KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->Pd, mt.row_dst, j, p.M, c.vocab));
+        KF(KF_MISC, k_draw_rows(s->st, s->Pd, s->max_rows, j, c.vocab, s->u_dev, k, s->B, s->tok_next, s->draft_dev, s->max_rows));
+      } else {
+        KF(KF_MISC, k_take_token(s->st, s->vtok, mt.row_seq, p.M, s->tok_next, s->draft_dev, s->max_rows, j));
+      }
     }
   }
+  s->need_logits = false;
   int* dh = s->out_host + 2 * s->B;
   HIP_TRY(hipMemcpyAsync(dh, s->draft_dev, (size_t)s->B * s->max_rows * sizeof(int), hipMemcpyDeviceToHost, s->st));
   EE_TRY(finish(s));
@@ -574,10 +598,18 @@ extern "C" int ee_draft(ee_session* s, int k, int32_t* draft) {
     SeqState& q = s->seq[b];
     q.S.assign(dh + b * s->max_rows, dh + b * s->max_rows + k);
     q.n_hd = rows;
+    q.sampled = u != nullptr;
     q.len[0] = p.p0[b] + rows;
     for (int j = 0; j < k; ++j) draft[b * k + j] = q.S[j];
   }
   return EE_OK;
+}
+
+extern "C" int ee_draft(ee_session* s, int k, int32_t* draft) { return draft_impl(s, k, draft, nullptr); }
+
+extern "C" int ee_draft_sample(ee_session* s, int k, const float* u, int32_t* draft) {
+  if (!u) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  return draft_impl(s, k, draft, u);
 }
 
 extern "C" int ee_draft_inject(ee_session* s, int k, const int32_t* draft) {
@@ -610,6 +642,7 @@ extern "C" int ee_draft_inject(ee_session* s, int k, const int32_t* draft) {
     SeqState& q = s->seq[b];
     q.S.assign(draft + b * k, draft + b * k + k);
     q.n_hd = rows;
+    q.sampled = false;
     q.len[0] = p.p0[b] + rows;
   }
   return EE_OK;
@@ -618,19 +651,33 @@ extern "C" int ee_draft_inject(ee_session* s, int k, const int32_t* draft) {
 // ---------------------------------------------------------------------------------------------
 // C ABI: intermediate verification at exit L_i
 // ---------------------------------------------------------------------------------------------
-extern "C" int ee_verify_intermediate(ee_session* s, int32_t* n_accept, int32_t* next_token) {
+// u_acc == null: LeadingSubstringVerify on arg max tokens (Alg. 2); otherwise the acceptance rule of App. G with the
+// uniform numbers u_acc [batch, u_stride] (one per draft token) and u_res [batch] (the replacement / next-token draw)
+static int verify_intermediate_impl(ee_session* s, int32_t* n_accept, int32_t* next_token, const float* u_acc, int u_stride,
+                                    const float* u_res) {
   if (!s || !n_accept || !next_token) { ee_set_error("null argument"); return EE_ERR_ARG; }
   const ee_config& c = s->m->cfg;
+  const bool rs = u_acc != nullptr;
   CallPlan p;
   p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
   int any = 0;
   for (int b = 0; b < s->B; ++b) {
     const SeqState& q = s->seq[b];
     if (!q.n_hd) continue;
+    if (rs && (!q.sampled || q.n_pi != (int)q.V.size())) {
+      ee_set_error("sequence %d: the pending block or the tentative tokens were not produced by the sampling calls", b);
+      return EE_ERR_STATE;
+    }
     p.m[b] = q.n_hd; p.p0[b] = (int)(q.C.size() + q.V.size()) - 1;
     any++;
   }
   if (!any) { ee_set_error("no draft block is pending"); return EE_ERR_STATE; }
+  if (rs) {
+    if (!s->Pd) { ee_set_error("sampling buffers are not attached (ee_sampling_attach)"); return EE_ERR_STATE; }
+    if (u_stride < 1 || u_stride > s->max_rows) { ee_set_error("bad stride of the uniform numbers"); return EE_ERR_ARG; }
+    for (int b = 0; b < s->B; ++b) EE_TRY(upload_uniforms(s, u_acc + (size_t)b * u_stride, u_stride, (size_t)b * s->max_rows));
+    EE_TRY(upload_uniforms(s, u_res, s->B, (size_t)s->B * s->max_rows));
+  }
   reset_accounting(s);
   EE_TRY(build_meta(s, 0, p, [&](int b, int r, int&, int& src, int& dst) {
     src = b * s->max_rows + r;                               // H_d row
@@ -647,9 +694,19 @@ extern "C" int ee_verify_intermediate(ee_session* s, int32_t* n_accept, int32_t*
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
   KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, s->Hd, mt.row_src, p.M, c.d_model));       // a1: consume buffered H_d
   run_layers(s, c.exit_draft, c.exit_inter, p, mt, 0);
+  s->need_logits = rs;
   exit_head(s, p.M);
+  s->need_logits = false;
   KF(KF_COPY, k_copy_rows(s->st, s->Hi, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));       // keep L_i hidden rows
-  KF(KF_ACCEPT, k_accept(s->st, s->vtok, mt, s->cand_stride, s->B, s->out_dev, s->out_dev + s->B));
+  if (rs) {
+    KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->LOGITS, nullptr, 0, p.M, c.vocab));          // p_{L_i}, in place
+    KF(KF_ACCEPT, k_rs_accept(s->st, s->LOGITS, s->Pd, s->max_rows, c.vocab, mt, s->cand_stride, s->B, s->u_dev, s->max_rows, s->out_dev));
+    KF(KF_ACCEPT, k_rs_draw(s->st, s->LOGITS, s->Pd, s->max_rows, c.vocab, mt, s->B, s->out_dev, s->u_dev + (size_t)s->B * s->max_rows,
+                            s->out_dev + s->B));
+    KF(KF_COPY, k_copy_rows(s->st, s->Pi, mt.row_dst, 0, s->LOGITS, nullptr, p.M, c.vocab));  // p_{L_i} of the rows that may stay
+  } else {
+    KF(KF_ACCEPT, k_accept(s->st, s->vtok, mt, s->cand_stride, s->B, s->out_dev, s->out_dev + s->B));
+  }
   HIP_TRY(hipMemcpyAsync(s->out_host, s->out_dev, 2 * (size_t)s->B * sizeof(int), hipMemcpyDeviceToHost, s->st));
   EE_TRY(finish(s));
   for (int b = 0; b < s->B; ++b) {
@@ -661,20 +718,32 @@ extern "C" int ee_verify_intermediate(ee_session* s, int32_t* n_accept, int32_t*
     int keep = a;
     if (a < p.m[b]) { q.V.push_back(next_token[b]); keep = a + 1; }
     q.len[0] = q.len[1] = p.p0[b] + keep;                    // prune rejected rows (lengths only)
-    q.n_hd = 0; q.S.clear();
+    q.n_hd = 0; q.S.clear(); q.sampled = false;
+    if (rs) q.n_pi = (int)q.V.size();
     trim_pages(s, b);
   }
   return EE_OK;
 }
 
+extern "C" int ee_verify_intermediate(ee_session* s, int32_t* n_accept, int32_t* next_token) {
+  return verify_intermediate_impl(s, n_accept, next_token, nullptr, 0, nullptr);
+}
+
+extern "C" int ee_verify_intermediate_rs(ee_session* s, const float* u_acc, int u_stride, const float* u_res, int32_t* n_accept,
+                                         int32_t* next_token) {
+  if (!u_acc || !u_res) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  return verify_intermediate_impl(s, n_accept, next_token, u_acc, u_stride, u_res);
+}
+
 // ---------------------------------------------------------------------------------------------
 // C ABI: full verification at L_f
 // ---------------------------------------------------------------------------------------------
-extern "C" int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
-                              int32_t* committed, int32_t* n_committed) {
+static int verify_full_impl(ee_session* s, const uint8_t* active, int32_t* n_accept, int32_t* next_token, int32_t* committed,
+                            int32_t* n_committed, const float* u_acc, int u_stride, const float* u_res) {
   if (!s || !n_accept || !next_token || !committed || !n_committed) { ee_set_error("null argument"); return EE_ERR_ARG; }
   const ee_config& c = s->m->cfg;
   const int bonus = c.bonus_full ? 1 : 0;
+  const bool rs = u_acc != nullptr;
   std::vector<int> act(s->B, 0);
   int any = 0;
   for (int b = 0; b < s->B; ++b) {
@@ -682,9 +751,19 @@ extern "C" int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_a
     if (active && !active[b]) continue;
     if (q.V.empty()) continue;
     if (q.n_hd) { ee_set_error("sequence %d still has an unverified draft block", b); return EE_ERR_STATE; }
+    if (rs && q.n_pi != (int)q.V.size()) {
+      ee_set_error("sequence %d: the tentative tokens were not produced by the sampling calls", b);
+      return EE_ERR_STATE;
+    }
     act[b] = 1; any++;
   }
   if (!any) { ee_set_error("no sequence has tentative tokens to verify"); return EE_ERR_STATE; }
+  if (rs) {
+    if (!s->Pi) { ee_set_error("sampling buffers are not attached (ee_sampling_attach)"); return EE_ERR_STATE; }
+    if (u_stride < 1 || u_stride > s->max_rows) { ee_set_error("bad stride of the uniform numbers"); return EE_ERR_ARG; }
+    for (int b = 0; b < s->B; ++b) EE_TRY(upload_uniforms(s, u_acc + (size_t)b * u_stride, u_stride, (size_t)b * s->max_rows));
+    EE_TRY(upload_uniforms(s, u_res, s->B, (size_t)s->B * s->max_rows));
+  }
   reset_accounting(s);
   if (bonus) {
     // the pending token V[-1] owns no hidden state yet: one row per sequence through G1 and G2
@@ -725,8 +804,17 @@ extern "C" int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_a
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
   KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, s->Hi, mt.row_src, p.M, c.d_model));       // consume buffered H_i
   run_layers(s, c.exit_inter, c.n_layers, p, mt, 0);
+  s->need_logits = rs;
   exit_head(s, p.M);
-  KF(KF_ACCEPT, k_accept(s->st, s->vtok, mt, s->cand_stride, s->B, s->out_dev, s->out_dev + s->B));
+  s->need_logits = false;
+  if (rs) {      // second stage of App. G: V, distributed as p_{L_i}, is the draft; p_{L_f} the target
+    KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->LOGITS, nullptr, 0, p.M, c.vocab));
+    KF(KF_ACCEPT, k_rs_accept(s->st, s->LOGITS, s->Pi, s->max_rows, c.vocab, mt, s->cand_stride, s->B, s->u_dev, s->max_rows, s->out_dev));
+    KF(KF_ACCEPT, k_rs_draw(s->st, s->LOGITS, s->Pi, s->max_rows, c.vocab, mt, s->B, s->out_dev, s->u_dev + (size_t)s->B * s->max_rows,
+                            s->out_dev + s->B));
+  } else {
+    KF(KF_ACCEPT, k_accept(s->st, s->vtok, mt, s->cand_stride, s->B, s->out_dev, s->out_dev + s->B));
+  }
   HIP_TRY(hipMemcpyAsync(s->out_host, s->out_dev, 2 * (size_t)s->B * sizeof(int), hipMemcpyDeviceToHost, s->st));
   EE_TRY(finish(s));
   for (int b = 0; b < s->B; ++b) {
@@ -741,10 +829,39 @@ extern "C" int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_a
     if (f < p.m[b]) out[n++] = next_token[b];
     n_committed[b] = n;
     q.C.insert(q.C.end(), out, out + n);
-    q.V.clear();
+    q.V.clear(); q.n_pi = 0;
     q.len[0] = q.len[1] = q.len[2] = (int)q.C.size() - 1;
     trim_pages(s, b);
   }
+  return EE_OK;
+}
+
+extern "C" int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
+                              int32_t* committed, int32_t* n_committed) {
+  return verify_full_impl(s, active, n_accept, next_token, committed, n_committed, nullptr, 0, nullptr);
+}
+
+extern "C" int ee_verify_full_rs(ee_session* s, const uint8_t* active, const float* u_acc, int u_stride, const float* u_res,
+                                 int32_t* n_accept, int32_t* next_token, int32_t* committed, int32_t* n_committed) {
+  if (!u_acc || !u_res) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  return verify_full_impl(s, active, n_accept, next_token, committed, n_committed, u_acc, u_stride, u_res);
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI: buffers of the rejection-sampling acceptance (caller-owned, like the session arena)
+// ---------------------------------------------------------------------------------------------
+static size_t sampling_floats(const ee_session* s) {
+  const size_t rows = (size_t)s->B * s->max_rows;
+  return 2 * rows * s->m->cfg.vocab + rows + s->B + 64;
+}
+extern "C" size_t ee_sampling_bytes(const ee_session* s) { return s ? sampling_floats(s) * sizeof(float) : 0; }
+
+extern "C" int ee_sampling_attach(ee_session* s, void* dev_arena, size_t arena_bytes) {
+  if (!s || !dev_arena || ((uintptr_t)dev_arena & 255)) { ee_set_error("arena must be non-null and 256-byte aligned"); return EE_ERR_ARG; }
+  if (arena_bytes < sampling_floats(s) * sizeof(float)) { ee_set_error("sampling arena too small"); return EE_ERR_ARG; }
+  const size_t rows = (size_t)s->B * s->max_rows;
+  float* f = (float*)dev_arena;
+  s->Pd = f; s->Pi = f + rows * s->m->cfg.vocab; s->u_dev = s->Pi + rows * s->m->cfg.vocab;
   return EE_OK;
 }
 
@@ -760,7 +877,7 @@ extern "C" int kv_rollback(ee_session* s, int seq, int group_mask, int new_len) 
   if (group_mask & ~7) { ee_set_error("bad group mask"); return EE_ERR_ARG; }
   if (m12 == 0) {
     if ((group_mask & 4) && new_len != q.len[2]) { ee_set_error("G3 cannot roll back alone"); return EE_ERR_ARG; }
-    q.n_hd = 0; q.S.clear(); q.len[0] = q.len[1];
+    q.n_hd = 0; q.S.clear(); q.sampled = false; q.len[0] = q.len[1];
     trim_pages(s, seq);
     return EE_OK;
   }
@@ -773,7 +890,8 @@ extern "C" int kv_rollback(ee_session* s, int seq, int group_mask, int new_len) 
   } else {
     q.V.resize(nT - q.C.size());
   }
-  q.n_hd = 0; q.S.clear();
+  q.n_pi = std::min(q.n_pi, (int)q.V.size());
+  q.n_hd = 0; q.S.clear(); q.sampled = false;
   q.len[0] = q.len[1] = new_len;
   trim_pages(s, seq);
   return EE_OK;
@@ -822,6 +940,17 @@ extern "C" int ee_debug_last_hidden(ee_session* s, float* host_out, int max_rows
   *n_rows = n;
   return EE_OK;
 }
+extern "C" int ee_debug_read_dist(ee_session* s, int which, int seq, int row0, int n, float* host_out) {
+  if (!s || !host_out || seq < 0 || seq >= s->B || (which != 0 && which != 1)) { ee_set_error("bad argument"); return EE_ERR_ARG; }
+  if (!s->Pd) { ee_set_error("sampling buffers are not attached"); return EE_ERR_STATE; }
+  if (row0 < 0 || n < 0 || row0 + n > s->max_rows) { ee_set_error("rows outside the store"); return EE_ERR_ARG; }
+  const size_t V = s->m->cfg.vocab;
+  const float* src = (which == 0 ? s->Pd : s->Pi) + ((size_t)seq * s->max_rows + row0) * V;
+  HIP_TRY(hipStreamSynchronize(s->st));
+  HIP_TRY(hipMemcpy(host_out, src, (size_t)n * V * sizeof(float), hipMemcpyDeviceToHost));
+  return EE_OK;
+}
+
 static int upload_pages(ee_session* s, int seq) {
   const SeqState& q = s->seq[seq];
   if (q.pages.empty()) return EE_OK;

@@ -93,3 +93,32 @@ def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, ever
             out[b].extend(int(t) for t in com[b])
             st.committed += len(com[b])
     return np.array([o[:n_new] for o in out], np.int32), st
+
+
+def hispec_generate_sampling(sess, n_new: int, k: int, n_i: int, rng: np.random.Generator):
+    """The same loop with the rejection-sampling acceptance of App. G (ee_draft_sample, ee_verify_intermediate_rs,
+    ee_verify_full_rs; the session's sampling buffers must be attached).  rng supplies the uniform numbers.
+    Returns (tokens [batch, n_new], LoopStats)."""
+    B = sess.batch
+    out: List[List[int]] = [[] for _ in range(B)]
+    st = LoopStats()
+    while min(len(o) for o in out) < n_new:
+        while True:
+            sess.draft_sample(k, rng.random((B, k), np.float32))
+            a, _ = sess.verify_intermediate_rs(rng.random((B, k), np.float32), rng.random(B, np.float32))
+            st.rounds += 1
+            st.drafted += B * k
+            st.accepted_inter += int(a.sum())
+            st.per_round_accept.append(int(a.sum()))
+            _, nv = sess.counts()
+            if int(nv.min()) >= n_i or min(len(o) + int(v) for o, v in zip(out, nv)) >= n_new + k + 2:
+                break
+        _, nv = sess.counts()
+        f, _, com = sess.verify_full_rs(rng.random((B, sess.max_rows), np.float32), rng.random(B, np.float32))
+        st.full_verifies += 1
+        st.tentative += int(nv.sum())
+        st.accepted_full += int(np.minimum(f, nv).sum())
+        for b in range(B):
+            out[b].extend(int(t) for t in com[b])
+            st.committed += len(com[b])
+    return np.array([o[:n_new] for o in out], np.int32), st

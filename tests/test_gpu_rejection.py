@@ -1,0 +1,181 @@
+"""GPU: rejection-sampling acceptance (App. G) through the C ABI against the oracle, with the same uniform numbers
+on both sides.  Decisions (accept counts, drawn tokens) must be equal whenever the oracle's decision margin --
+the distance of a uniform number from the accept threshold or from the edge of the drawn token's interval of
+the CDF -- exceeds what fp32 summation order can move; rounds below the margin are redrawn."""
+import copy
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import ee_oracle as eo
+from hs_common import OracleSide, bf16_small, gpu_side
+
+pytestmark = pytest.mark.gpu
+
+RS_MARGIN = {"f32": 2e-5}
+
+
+def _trial(O, seq, k, u_d, u_a, u_r, full, uf_a=None, uf_r=None):
+    t = copy.deepcopy(seq)
+    O.o.draft(t, k, u_d)
+    m = O.o.last_margin
+    O.o.verify_intermediate(t, (u_a, u_r))
+    m = min(m, O.o.last_margin)
+    if full:
+        O.o.verify_full(t, (uf_a, uf_r))
+        m = min(m, O.o.last_margin)
+    return m
+
+
+def test_rejection_sampling_rounds_match_oracle():
+    cfg = synth.tiny_config(gamma=(1.0, 0.3, 0.3))
+    k, ctxs = 4, [40, 23]
+    B = len(ctxs)
+    rows = 3 * (k + 1) + 2
+    margin = RS_MARGIN["f32"]
+    O = OracleSide(cfg, 77)
+    prompts = [synth.gen_prompt(cfg.vocab, n, 300 + b) for b, n in enumerate(ctxs)]
+    model, sess = gpu_side(cfg, 77, B, max(ctxs) + 8 * rows, rows)
+    sess.enable_sampling()
+    first = sess.prefill(prompts)
+    for p in prompts:
+        s = eo.Sequence_(O.model.spec, max(ctxs) + 8 * rows)
+        O.o.prefill(s, p)
+        O.seqs.append(s)
+    for b, s in enumerate(O.seqs):
+        s.C[-1] = int(first[b])
+    rng = np.random.default_rng(5)
+    compared = accepted = rejected = 0
+    for rnd in range(8):
+        full = rnd % 2 == 1
+        for _ in range(40):      # redraw the round's uniform numbers until every decision clears the margin
+            u_d, u_a, u_r = rng.random((B, k), np.float32), rng.random((B, k), np.float32), rng.random(B, np.float32)
+            uf_a, uf_r = rng.random((B, rows), np.float32), rng.random(B, np.float32)
+            if all(_trial(O, s, k, u_d[b], u_a[b], float(u_r[b]), full, uf_a[b], float(uf_r[b])) > margin
+                   for b, s in enumerate(O.seqs)):
+                break
+        else:
+            pytest.fail("no draw cleared the margin")
+        gS = sess.draft_sample(k, u_d)
+        ga, gn = sess.verify_intermediate_rs(u_a, u_r)
+        for b, s in enumerate(O.seqs):
+            assert gS[b].tolist() == O.o.draft(s, k, u_d[b]), (rnd, b)
+            a, nxt = O.o.verify_intermediate(s, (u_a[b], float(u_r[b])))
+            assert (int(ga[b]), int(gn[b])) == (a, nxt), (rnd, b)
+            accepted += a; rejected += k - a
+        if full:
+            gf, gfn, gcom = sess.verify_full_rs(uf_a, uf_r)
+            for b, s in enumerate(O.seqs):
+                f, nxt, F = O.o.verify_full(s, (uf_a[b], float(uf_r[b])))
+                assert (int(gf[b]), int(gfn[b]), gcom[b]) == (f, nxt, F), (rnd, b)
+        lens = sess.lengths()
+        for b, s in enumerate(O.seqs):
+            assert list(lens[b]) == s.len and sess.tokens(b).tolist() == s.T
+        compared += 1
+    assert compared == 8 and accepted > 0 and rejected > 0      # both outcomes of the accept test were exercised
+    # the two acceptance rules may not be mixed within a round
+    import paper_2510_01336_amd as hs
+    sess.draft(k)
+    with pytest.raises(hs.EEError):
+        sess.verify_intermediate_rs(rng.random((B, k), np.float32), rng.random(B, np.float32))
+    with pytest.raises(hs.EEError):
+        sess.draft_sample(k, np.full((B, k), 1.0, np.float32))  # (also: a block is pending)
+    sess.close(); model.close()
+
+
+def test_sampling_needs_attached_buffers_and_valid_uniforms():
+    import paper_2510_01336_amd as hs
+    cfg = synth.tiny_config()
+    model, sess = gpu_side(cfg, 3, 1, 96, 12)
+    sess.prefill([synth.gen_prompt(cfg.vocab, 16, 1)])
+    with pytest.raises(hs.EEError):
+        sess.draft_sample(4, np.zeros((1, 4), np.float32))       # nothing attached
+    sess.enable_sampling()
+    with pytest.raises(hs.EEError):
+        sess.draft_sample(4, np.array([[0.1, 0.2, 1.0, 0.3]], np.float32))   # 1.0 is outside [0, 1)
+    assert sess.lengths().tolist() == [[16, 16, 16]]
+    S = sess.draft_sample(4, np.array([[0.1, 0.2, 0.9, 0.3]], np.float32))
+    assert S.shape == (1, 4) and (S >= 0).all() and (S < cfg.vocab).all()
+    sess.close(); model.close()
+
+
+def test_bf16_distributions_and_decisions():
+    """bf16 model: token probabilities carry the model's ~1e-2 relative error, more than the width of a token's
+    interval of the CDF, so drawn tokens cannot be compared with the oracle's directly.  Checked instead: (1) the
+    distributions the GPU forms (p_{L_d} per drafted position, p_{L_i} per verified row) against the oracle's on the
+    same tokens, within the bf16 tolerance; (2) every decision of the GPU against the oracle's acceptance rule
+    applied to the GPU's own distributions with the same uniform numbers (same inputs, so only the summation
+    order differs: fp32 margin)."""
+    from hs_common import TOL
+    cfg = bf16_small()
+    k, ctxs = 5, [37, 70]
+    B, rows = len(ctxs), 3 * (k + 1) + 2
+    O = OracleSide(cfg, 78)
+    prompts = [synth.gen_prompt(cfg.vocab, n, 400 + b) for b, n in enumerate(ctxs)]
+    model, sess = gpu_side(cfg, 78, B, max(ctxs) + 8 * rows, rows)
+    sess.enable_sampling()
+    sess.enable_logits(True)
+    first = sess.prefill(prompts)
+    for b, p in enumerate(prompts):
+        s = eo.Sequence_(O.model.spec, max(ctxs) + 8 * rows)
+        O.o.prefill(s, p)
+        s.C[-1] = int(first[b])
+        O.seqs.append(s)
+    rng = np.random.default_rng(9)
+    checked = skipped = 0
+    for rnd in range(6):
+        u_d, u_a, u_r = rng.random((B, k), np.float32), rng.random((B, k), np.float32), rng.random(B, np.float32)
+        nv = sess.counts()[1]
+        S = sess.draft_sample(k, u_d)
+        Pd = [sess.read_dist(0, b, 0, k).astype(np.float64) for b in range(B)]
+        ga, gn = sess.verify_intermediate_rs(u_a, u_r)
+        Pt = sess.last_logits().astype(np.float64)                # this call's p_{L_i}, rows packed sequence by sequence
+        for b in range(B):
+            assert np.allclose(Pd[b].sum(axis=1), 1.0, atol=1e-4) and (Pd[b] >= 0).all()
+            for j in range(k):                                    # the drafted tokens, from the GPU's own p_{L_d}
+                tok, mg = eo.sample_inverse_cdf(Pd[b][j], float(u_d[b, j]))
+                if mg > RS_MARGIN["f32"]:
+                    assert int(S[b, j]) == tok, (rnd, b, j)
+                    checked += 1
+                else:
+                    skipped += 1
+            pt = Pt[b * (k + 1):(b + 1) * (k + 1)]
+            a, out, mg = eo.rejection_verify(S[b].tolist(), Pd[b], pt, u_a[b], float(u_r[b]))
+            if mg > RS_MARGIN["f32"]:
+                assert (int(ga[b]), int(gn[b])) == (a, out[-1]), (rnd, b)
+                checked += 1
+            else:
+                skipped += 1
+            # the stored p_{L_i} rows of the tokens now in V are the rows of this call
+            keep = int(ga[b]) + 1
+            Pi = sess.read_dist(1, b, int(nv[b]), keep)
+            assert np.array_equal(Pi, pt[:keep].astype(np.float32))
+        if rnd == 0:      # distributions against the oracle on the same tokens (fresh from the context build)
+            for b, s in enumerate(O.seqs):
+                O.o.draft_inject(s, S[b])
+                pd_ref = eo.softmax_rows(O.model.exit_logits(np.stack(s.H_d[:k])))
+                s.P_d = list(pd_ref)
+                assert np.max(np.abs(Pd[b] - pd_ref)) / np.max(pd_ref) <= TOL["bf16"]
+                O.o.verify_intermediate(s, (u_a[b], float(u_r[b])))
+                pi_ref = eo.softmax_rows(O.o.last_logits)
+                assert np.max(np.abs(Pt[b * (k + 1):(b + 1) * (k + 1)] - pi_ref)) / np.max(pi_ref) <= TOL["bf16"]
+        if rnd % 2 == 1:
+            nv = sess.counts()[1]
+            Pi = [sess.read_dist(1, b, 0, int(nv[b])).astype(np.float64) for b in range(B)]
+            V = [sess.tokens(b)[-int(nv[b]):].tolist() for b in range(B)]
+            uf_a, uf_r = rng.random((B, rows), np.float32), rng.random(B, np.float32)
+            gf, gfn, gcom = sess.verify_full_rs(uf_a, uf_r)
+            Pf = sess.last_logits().astype(np.float64)
+            r0 = 0
+            for b in range(B):
+                n = int(nv[b]) + 1
+                f, out, mg = eo.rejection_verify(V[b], Pi[b], Pf[r0:r0 + n], uf_a[b], float(uf_r[b]))
+                if mg > RS_MARGIN["f32"]:
+                    assert (int(gf[b]), int(gfn[b]), gcom[b]) == (f, out[-1], out), (rnd, b)
+                    checked += 1
+                else:
+                    skipped += 1
+                r0 += n
+    assert checked > 10 * max(1, skipped)
+    sess.close(); model.close()
