@@ -42,7 +42,7 @@ def _ragged16():
 
 
 WORKLOADS = {
-    # name: (config factory, per-sequence KV context lengths, k, agreement p)
+    # name: (config factory, per-sequence KV context lengths, k, agreement p[, intermediate rounds per full verification])
     # the default is the configuration the metric is quoted on; the others are the remaining single-GPU
     # configurations, kept runnable for profiling (their parity is covered by the GPU tests)
     "8b_b1_ctx2048_k8": (synth.llama8b_config, [2048], 8, 0.8),
@@ -50,6 +50,10 @@ WORKLOADS = {
     "8b_b1_ctx32768_k16": (synth.llama8b_config, [32768], 16, 0.9),
     "8b_b1_ctx32768_k16_li8": (lambda: synth.llama8b_config(exit_inter=8), [32768], 16, 0.9),
     "8b_b1_ctx32768_k16_li24": (lambda: synth.llama8b_config(exit_inter=24), [32768], 16, 0.9),
+    "8b_b1_ctx32768_k16_r2": (synth.llama8b_config, [32768], 16, 0.9, 2),
+    "8b_b1_ctx32768_k16_r4": (synth.llama8b_config, [32768], 16, 0.9, 4),
+    "8b_b1_ctx32768_k16_li8_r4": (lambda: synth.llama8b_config(exit_inter=8), [32768], 16, 0.9, 4),
+    "8b_b1_ctx32768_k16_li24_r4": (lambda: synth.llama8b_config(exit_inter=24), [32768], 16, 0.9, 4),
     "70b_b4_ctx1024_k8": (synth.llama70b_config, [1024] * 4, 8, 0.75),
     "tiny_b1_ctx32_k4": (lambda: synth.tiny_config(gamma=(1.0, 0.3, 0.3)), [32], 4, 0.8),
     "8b_reduced_b1_ctx2048_k8": (lambda: synth.llama8b_config(n_layers=8, exit_draft=1, exit_inter=4), [2048], 8, 0.8),
@@ -132,42 +136,57 @@ def run_e2e(args):
     print(json.dumps(out))
 
 
-def step_bytes(cfg, ctxs, k, rows_full):
-    """Algorithmic HBM bytes of one step: every weight of the layers run once, the two exit heads,
-    and the KV context once per layer pass (activations are negligible and left out)."""
+def step_bytes(cfg, ctxs, k, rows_full, rounds=1):
+    """Algorithmic HBM bytes of one step: every weight of the layers run once per pass (G1 and G2 once per
+    intermediate round), one exit head per verification, and the KV context once per layer pass (activations
+    are negligible and left out)."""
     es = 2 if cfg.dtype == "bf16" else 4
     d, D, Hq, Hkv, F = cfg.d_model, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads, cfg.d_ffn
     per_layer = ((Hq + 2 * Hkv) * D * d + d * Hq * D + 3 * F * d) * es
     head = cfg.vocab * d * es
     kv_layer = sum(ctxs) * 2 * Hkv * D * es
-    layers = cfg.n_layers + (cfg.exit_inter if rows_full else 0)   # G1+G2+G3, + catch-up row through G1+G2
-    return layers * (per_layer + kv_layer) + 2 * head
+    # rounds x (G1 + G2), G3, + catch-up row through G1+G2
+    layers = rounds * cfg.exit_inter + (cfg.n_layers - cfg.exit_inter) + (cfg.exit_inter if rows_full else 0)
+    return layers * (per_layer + kv_layer) + (rounds + 1) * head
 
 
 def build_workload(name, seed=MODEL_SEED):
     import paper_2510_01336_amd as hs
-    factory, ctxs, k, p = WORKLOADS[name]
+    factory, ctxs, k, p = WORKLOADS[name][:4]
+    R = WORKLOADS[name][4] if len(WORKLOADS[name]) > 4 else 1
     ctxs = list(ctxs() if callable(ctxs) else ctxs)
     batch = len(ctxs)
     cfg = factory()
     model = hs.Model(cfg, seed)
-    sess = hs.Session(model, batch, max(ctxs) + 64, 2 * (k + 1) + 2)
+    sess = hs.Session(model, batch, max(ctxs) + R * (k + 1) + 64, (R + 1) * (k + 1) + 2)
     prompts = [synth.gen_prompt(cfg.vocab, c, 7 + b) for b, c in enumerate(ctxs)]
     sess.prefill(prompts)
-    # teacher-forced greedy continuation of the intermediate verifier, found with the library itself
-    # (k untimed rounds), then a block agreeing with it with probability p per position
+    # For each of the R rounds: the teacher-forced greedy continuation of the intermediate verifier from the state
+    # the earlier rounds leave, found with the library itself (k untimed sub-rounds, each cut back again), then a
+    # block agreeing with it with probability p per position, injected and verified so the state moves on.  The
+    # recorded blocks replay the same state sequence in every timed step.
     rng = np.random.default_rng(11)
-    greedy = np.zeros((batch, k), np.int64)
-    for j in range(k):
-        S = rng.integers(0, cfg.vocab, size=(batch, k))
-        S[:, :j] = greedy[:, :j]
-        sess.draft_inject(S)
-        a, nxt = sess.verify_intermediate()
-        greedy[:, j] = np.where(a > j, S[:, j], nxt)      # (a random token may match by chance)
-        for b in range(batch):
-            sess.rollback(b, 0b111, ctxs[b])
-    drafts = np.stack([synth.make_draft_block(greedy[b], k, p, cfg.vocab, rng) for b in range(batch)])
-    return dict(cfg=cfg, model=model, sess=sess, batch=batch, ctxs=ctxs, k=k, p=p, drafts=drafts, name=name)
+    blocks = []
+    for r in range(R):
+        base = sess.lengths()[:, 1].copy()
+        greedy = np.zeros((batch, k), np.int64)
+        for j in range(k):
+            S = rng.integers(0, cfg.vocab, size=(batch, k))
+            S[:, :j] = greedy[:, :j]
+            sess.draft_inject(S)
+            a, nxt = sess.verify_intermediate()
+            greedy[:, j] = np.where(a > j, S[:, j], nxt)      # (a random token may match by chance)
+            for b in range(batch):
+                sess.rollback(b, 0b011 if r else 0b111, int(base[b]))
+        drafts = np.stack([synth.make_draft_block(greedy[b], k, p, cfg.vocab, rng) for b in range(batch)])
+        blocks.append(drafts)
+        if r + 1 < R:
+            sess.draft_inject(drafts)
+            sess.verify_intermediate()
+    for b in range(batch):
+        sess.rollback(b, 0b111, ctxs[b])
+    return dict(cfg=cfg, model=model, sess=sess, batch=batch, ctxs=ctxs, k=k, p=p, drafts=blocks[0], blocks=blocks, rounds=R,
+                name=name)
 
 
 def one_step(w, collect=None, wall=None):
@@ -175,13 +194,17 @@ def one_step(w, collect=None, wall=None):
     verify calls return only after the stream has drained, so the inject call's time shows up in the next)."""
     sess = w["sess"]
     t0 = time.perf_counter()
-    sess.draft_inject(w["drafts"])
-    if collect is not None:
-        collect(sess.kernel_times(), "inject")
-    a, nxt = sess.verify_intermediate()
+    a_sum = 0
+    for drafts in w["blocks"]:
+        sess.draft_inject(drafts)
+        if collect is not None:
+            collect(sess.kernel_times(), "inject")
+        a, nxt = sess.verify_intermediate()
+        a_sum = a_sum + a
+        if collect is not None:
+            collect(sess.kernel_times(), "inter")
+    a = a_sum
     t1 = time.perf_counter()
-    if collect is not None:
-        collect(sess.kernel_times(), "inter")
     f, fn, com = sess.verify_full()
     t2 = time.perf_counter()
     if collect is not None:
@@ -288,7 +311,7 @@ def main():
     t_i = float(np.median([x[0] for x in wall]))     # draft_inject (G1) + verify_intermediate (G2, head, accept)
     t_f = float(np.median([x[1] for x in wall]))     # verify_full (catch-up row, G3, head, accept, commit)
     ms_per_step = 1e3 * elapsed / args.steps
-    value = w["batch"] * w["k"] * args.steps / elapsed
+    value = w["batch"] * w["k"] * w["rounds"] * args.steps / elapsed
 
     # instrumented pass: HIP events around every launch on the library's stream
     acc = {}
@@ -315,7 +338,7 @@ def main():
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": gu_bytes, "avg_launch_us": gu_avg_s * 1e6,
                 "launches": gu_n}
-    sb = step_bytes(cfg, w["ctxs"], w["k"], True)
+    sb = step_bytes(cfg, w["ctxs"], w["k"], True, w["rounds"])
     kernel_ms = {k2: round(v[0] / args.steps, 4) for k2, v in acc.items()}
 
     out = {
@@ -326,12 +349,13 @@ def main():
         "config": {"workload": args.workload, "batch": w["batch"],
                    "kv_context": w["ctxs"][0] if w["batch"] == 1 else w["ctxs"], "k": w["k"],
                    "draft_agreement_p": w["p"], "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers],
-                   "step": "draft_inject(G1) + verify_intermediate(G2) + verify_full(G1+G2 catch-up row, G3) + rollback",
+                   "intermediate_rounds_per_full_verification": w["rounds"],
+                   "step": "rounds x [draft_inject(G1) + verify_intermediate(G2)] + verify_full(G1+G2 catch-up row, G3) + rollback",
                    "accepted_inter": [int(x) for x in a], "accepted_full": [int(x) for x in f]},
         "roofline": roofline,
         "phase_ms_median": {"inject_plus_verify_intermediate": 1e3 * t_i, "verify_full": 1e3 * t_f},
-        "verified_tokens_per_s_by_stage": {"intermediate": w["batch"] * w["k"] / t_i,
-                                           "full": float(np.sum(np.asarray(a) + 1)) / t_f},
+        "verified_tokens_per_s_by_stage": {"intermediate": w["batch"] * w["k"] * w["rounds"] / t_i,
+                                           "full": float(np.sum(np.asarray(a) + w["rounds"])) / t_f},
         "step_bytes": sb, "step_hbm_frac": sb / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms_per_step": kernel_ms,
     }
