@@ -118,6 +118,12 @@ void ee_session_free(ee_session* s);
  * (the "Vanilla generation" step of Sec. 3.1).  first_token: host [batch]. */
 int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* lens, int32_t* first_token);
 
+/* The same for one sequence while the others keep their state (a finished request leaves, a new one takes its
+ * slot): the sequence's pages return to the shared pool, then its new prompt (host, len >= 1 tokens) is built.
+ * EE_ERR_CAPACITY if the pool cannot hold it; the session is unchanged then.  Calls that step the whole batch
+ * (draft, verify) require every sequence to be started. */
+int ee_prefill_seq(ee_session* s, int seq, const int32_t* tokens, int len, int32_t* first_token);
+
 /* Vanilla generation of Sec. 3.1 (the baseline the method is measured against and whose output it must
  * reproduce): n greedy single-token steps through all L_f layers per sequence, each committing
  * arg max at L_f.  Requires every sequence to be started with an empty tentative buffer and no pending

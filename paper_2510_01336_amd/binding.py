@@ -14,7 +14,7 @@ import numpy as np
 __all__ = [
     "lib", "lib_path", "EEError", "ee_config", "make_config", "Model", "Session",
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
-    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_decode_ar", "ee_draft", "ee_draft_inject",
+    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
@@ -28,7 +28,7 @@ TENSOR_IDS = {"emb": 0, "head": 1, "gfinal": 2, "g1": 3, "wq": 4, "wk": 5, "wv":
 
 EXPORTED_SYMBOLS = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
-    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_decode_ar", "ee_draft", "ee_draft_inject",
+    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
@@ -74,6 +74,7 @@ def _load():
         "ee_session_free": (None, [vp]),
         "ee_prefill": (C.c_int, [vp, i32p, i32p, i32p]),
         "ee_decode_ar": (C.c_int, [vp, C.c_int, i32p]),
+        "ee_prefill_seq": (C.c_int, [vp, C.c_int, i32p, C.c_int, i32p]),
         "ee_draft": (C.c_int, [vp, C.c_int, i32p]),
         "ee_draft_inject": (C.c_int, [vp, C.c_int, i32p]),
         "ee_verify_intermediate": (C.c_int, [vp, i32p, i32p]),
@@ -210,6 +211,13 @@ def ee_prefill(session: int, tokens: np.ndarray, lens: np.ndarray) -> np.ndarray
     first = np.empty(len(l), np.int32)
     _chk(lib.ee_prefill(session, _p_i32(t), _p_i32(l), _p_i32(first)))
     return first
+
+
+def ee_prefill_seq(session: int, seq: int, tokens: np.ndarray) -> int:
+    t = _i32(tokens)
+    out = np.empty(1, np.int32)
+    _chk(lib.ee_prefill_seq(session, seq, _p_i32(t), len(t), _p_i32(out)))
+    return int(out[0])
 
 
 def ee_decode_ar(session: int, batch: int, n: int) -> np.ndarray:
@@ -406,6 +414,9 @@ class Session:
     def prefill(self, prompts: Sequence[np.ndarray]) -> np.ndarray:
         lens = np.array([len(p) for p in prompts], np.int32)
         return ee_prefill(self.handle, np.concatenate([_i32(p) for p in prompts]), lens)
+
+    def prefill_seq(self, seq: int, prompt: np.ndarray) -> int:
+        return ee_prefill_seq(self.handle, seq, prompt)
 
     def decode_ar(self, n: int) -> np.ndarray:
         return ee_decode_ar(self.handle, self.batch, n)

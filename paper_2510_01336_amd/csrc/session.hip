@@ -429,28 +429,40 @@ static int finish(ee_session* s) {
 // ---------------------------------------------------------------------------------------------
 // C ABI: prefill
 // ---------------------------------------------------------------------------------------------
-extern "C" int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* lens, int32_t* first_token) {
-  if (!s || !tokens || !lens || !first_token) { ee_set_error("null argument"); return EE_ERR_ARG; }
+// (Re)start the sequences with lens[b] > 0 from their prompts (tokens: those prompts packed in sequence order);
+// sequences with lens[b] == 0 keep their state.  Pages of a restarted sequence go back to the pool first.
+static int prefill_impl(ee_session* s, const int32_t* tokens, const int32_t* lens, int32_t* first_token) {
   const ee_config& c = s->m->cfg;
   std::vector<int> want(s->B);
   size_t total = 0;
   for (int b = 0; b < s->B; ++b) {
-    if (lens[b] < 1) { ee_set_error("prompt %d is empty", b); return EE_ERR_ARG; }
-    want[b] = lens[b] + 1;
+    const SeqState& q = s->seq[b];
+    want[b] = lens[b] > 0 ? lens[b] + 1 : (q.started ? std::max(q.len[0], std::max(q.len[1], q.len[2])) : 0);
     total += lens[b];
   }
   for (size_t i = 0; i < total; ++i)
     if (tokens[i] < 0 || tokens[i] >= c.vocab) { ee_set_error("token id out of range"); return EE_ERR_ARG; }
-  // restart every sequence from scratch
+  // capacity is checked against the pool as it will be once the restarted sequences have given their pages back
+  {
+    size_t freed = 0, need = 0;
+    for (int b = 0; b < s->B; ++b) {
+      if (lens[b] <= 0) continue;
+      if (want[b] > s->max_ctx) { ee_set_error("sequence %d would need %d positions (max_ctx %d)", b, want[b], s->max_ctx); return EE_ERR_CAPACITY; }
+      freed += s->seq[b].pages.size();
+      need += (size_t)ceil_div(want[b], EE_PAGE);
+    }
+    if (need > s->free_pages.size() + freed) { ee_set_error("KV page pool exhausted"); return EE_ERR_CAPACITY; }
+  }
   for (int b = 0; b < s->B; ++b) {
+    if (lens[b] <= 0) continue;
     SeqState& q = s->seq[b];
     for (int pg : q.pages) s->free_pages.push_back(pg);
     q = SeqState();
   }
-  EE_TRY(check_capacity(s, want));
   reset_accounting(s);
   size_t off = 0;
   for (int b = 0; b < s->B; ++b) {
+    if (lens[b] <= 0) continue;
     EE_TRY(grow_pages(s, b, want[b]));
     const int n = lens[b];
     for (int r0 = 0, ci = 0; r0 < n; r0 += s->chunk, ++ci) {
@@ -474,6 +486,7 @@ extern "C" int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* l
   EE_TRY(finish(s));
   off = 0;
   for (int b = 0; b < s->B; ++b) {
+    if (lens[b] <= 0) continue;
     SeqState& q = s->seq[b];
     q.C.assign(tokens + off, tokens + off + lens[b]);
     q.C.push_back(s->out_host[b]);
@@ -482,6 +495,23 @@ extern "C" int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* l
     first_token[b] = s->out_host[b];
     off += lens[b];
   }
+  return EE_OK;
+}
+
+extern "C" int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* lens, int32_t* first_token) {
+  if (!s || !tokens || !lens || !first_token) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  for (int b = 0; b < s->B; ++b)
+    if (lens[b] < 1) { ee_set_error("prompt %d is empty", b); return EE_ERR_ARG; }
+  return prefill_impl(s, tokens, lens, first_token);
+}
+
+extern "C" int ee_prefill_seq(ee_session* s, int seq, const int32_t* tokens, int len, int32_t* first_token) {
+  if (!s || !tokens || !first_token || seq < 0 || seq >= s->B) { ee_set_error("bad argument"); return EE_ERR_ARG; }
+  if (len < 1) { ee_set_error("prompt is empty"); return EE_ERR_ARG; }
+  std::vector<int32_t> lens(s->B, 0), first(s->B, -1);
+  lens[seq] = len;
+  EE_TRY(prefill_impl(s, tokens, lens.data(), first.data()));
+  *first_token = first[seq];
   return EE_OK;
 }
 

@@ -409,3 +409,44 @@ def test_error_codes_leave_state_untouched():
     with pytest.raises(hs.EEError) as e:
         hs.Session(model, 1, 100000, 12)            # fp32 sessions are limited to 8192 positions
     small.close(); sess.close(); model.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# one sequence leaves, another takes its slot
+# ------------------------------------------------------------------------------------------------
+def test_sequence_restart_keeps_the_others():
+    import paper_2510_01336_amd as hs
+    cfg = bf16_small()
+    k = 6
+    O, model, sess, first, gfirst = _setup(cfg, 31, [90, 40, 130], 3 * (k + 1) + 2)
+    assert gfirst.tolist() == first.tolist()
+    rng = np.random.default_rng(8)
+    _round(O, sess, k, 0.7, rng, True, TOL["bf16"])
+    before = [(sess.lengths()[b].tolist(), sess.tokens(b).tolist(), sess.read_kv(b, 3, 0, int(sess.lengths()[b][0]))) for b in (0, 2)]
+    # sequence 1 is replaced by a longer prompt; the margin of its first token is checked like any other
+    for attempt in range(20):
+        prompt = synth.gen_prompt(cfg.vocab, 150, 900 + attempt)
+        s_new = eo.Sequence_(O.model.spec, O.seqs[0].cache.capacity)
+        f_new = O.o.prefill(s_new, prompt)
+        if eo.top2_margin(O.o.last_logits)[0] > MARGIN:
+            break
+    assert sess.prefill_seq(1, prompt) == f_new
+    O.seqs[1] = s_new
+    for (lens, toks, (kk, vv)), b in zip(before, (0, 2)):
+        assert sess.lengths()[b].tolist() == lens and sess.tokens(b).tolist() == toks
+        k2, v2 = sess.read_kv(b, 3, 0, lens[0])
+        assert np.array_equal(kk, k2) and np.array_equal(vv, v2)
+    _check_state(O, sess)
+    _round(O, sess, k, 0.7, rng, True, TOL["bf16"])          # all three go on together
+    sess.close(); model.close()
+    # a pool too small for the newcomer: refused, nothing changes
+    model, sess = gpu_side(cfg, 31, 2, 400, 3 * (k + 1) + 2)
+    sess.close()
+    sess = hs.Session(model, 2, 400, 3 * (k + 1) + 2, total_pages=5)
+    sess.prefill([synth.gen_prompt(cfg.vocab, 100, 1), synth.gen_prompt(cfg.vocab, 100, 2)])      # 2 + 2 pages
+    lens = sess.lengths().tolist()
+    with pytest.raises(hs.EEError):
+        sess.prefill_seq(0, synth.gen_prompt(cfg.vocab, 300, 3))                                   # would need 5 of 3 + 2 free
+    assert sess.lengths().tolist() == lens
+    assert isinstance(sess.prefill_seq(0, synth.gen_prompt(cfg.vocab, 150, 3)), int)               # 3 pages fit
+    sess.close(); model.close()
