@@ -140,13 +140,18 @@ class ModelSpec:
     rope_theta: float
     rms_eps: float
     round_mode: str = "none"
+    head_rank: int = 0       # > 0: low-rank adapters in front of the shared head at L_d and L_i (App. I)
 
     @classmethod
     def from_config(cls, cfg, round_mode: Optional[str] = None) -> "ModelSpec":
         rm = round_mode if round_mode is not None else ("bf16" if getattr(cfg, "dtype", "f32") == "bf16" else "none")
         return cls(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
                    cfg.d_ffn, cfg.vocab, cfg.exit_draft, cfg.exit_inter,
-                   float(cfg.rope_theta), float(cfg.rms_eps), rm)
+                   float(cfg.rope_theta), float(cfg.rms_eps), rm, int(getattr(cfg, "head_rank", 0)))
+
+    def exit_index(self, exit_layer: int) -> int:
+        """0 for L_d, 1 for L_i, 2 for any other depth (the shared head alone)."""
+        return 0 if exit_layer == self.exit_draft else (1 if exit_layer == self.exit_inter else 2)
 
     def group_layers(self, g: int) -> range:
         b = (0, self.exit_draft, self.exit_inter, self.n_layers)
@@ -201,8 +206,18 @@ class EEModel:
             x = self.layer(l, x, pos, cache)
         return x
 
-    def exit_logits(self, x: np.ndarray) -> np.ndarray:
-        """Shared final norm + shared LM head applied to hidden rows of any exit layer."""
+    def exit_logits(self, x: np.ndarray, which: int = 2) -> np.ndarray:
+        """Prediction head of exit `which` (0 = L_d, 1 = L_i, 2 = L_f) on hidden rows x.
+
+        The final layer, and every exit of a model without auxiliary heads, uses the shared final
+        norm + shared LM head.  With head_rank = r > 0 (the post-training conversion of App. I,
+        "low-rank prediction heads") the early exits first pass the hidden state through their own
+        rank-r residual adapter,  z = x + B_e (A_e RMSNorm(x; g_e)),  and feed z to the shared norm
+        and head: the reading that fits the appendix's bound on added parameters."""
+        if self.spec.head_rank > 0 and which < 2:
+            n = self.rnd(rmsnorm(x, self._w("aux_g", which), self.spec.rms_eps))
+            t = self.rnd(n @ self._w("aux_a", which).T)
+            x = x + t @ self._w("aux_b", which).T
         n = self.rnd(rmsnorm(x, self._w("gfinal"), self.spec.rms_eps))
         return n @ self._w("head").T
 
@@ -213,7 +228,7 @@ class EEModel:
         scratch = KVCache(self.spec, t)
         pos = np.arange(t)
         x = self.run_layers(range(n_layers), self.embed(tokens), pos, scratch)
-        return x, self.exit_logits(x)
+        return x, self.exit_logits(x, self.spec.exit_index(n_layers))
 
 
 def argmax_rows(logits: np.ndarray) -> np.ndarray:
@@ -407,7 +422,7 @@ class HiSpecOracle:
             x = self.m.run_layers(G1, self.m.embed([tok]), np.array([p0 + j]), seq.cache)
             seq.H_d.append(x[0])
             if j < k:
-                lg = self.m.exit_logits(x)
+                lg = self.m.exit_logits(x, 0)
                 logs.append(lg[0])
                 if u is None:
                     tok = int(argmax_rows(lg)[0])
@@ -450,7 +465,7 @@ class HiSpecOracle:
         assert seq.len[1] == p0 and seq.len[0] == p0 + rows
         Y = self.m.run_layers(G2, np.stack(seq.H_d), p0 + np.arange(rows), seq.cache)
         seq.len[1] = p0 + rows
-        logits = self.m.exit_logits(Y)
+        logits = self.m.exit_logits(Y, 1)
         if rs is None:
             v = argmax_rows(logits)
             a, vhat = leading_substring_verify(seq.S, v)
@@ -548,11 +563,12 @@ def ar_generate(model: EEModel, prompt: Sequence[int], n_new: int, exit_layer: O
     L = exit_layer or model.spec.n_layers
     cache = KVCache(model.spec, len(prompt) + n_new)
     x = model.run_layers(range(L), model.embed(prompt), np.arange(len(prompt)), cache)
-    out = [int(argmax_rows(model.exit_logits(x[-1:]))[0])]
+    which = model.spec.exit_index(L)
+    out = [int(argmax_rows(model.exit_logits(x[-1:], which))[0])]
     while len(out) < n_new:
         p = len(prompt) + len(out) - 1
         x = model.run_layers(range(L), model.embed([out[-1]]), np.array([p]), cache)
-        out.append(int(argmax_rows(model.exit_logits(x))[0]))
+        out.append(int(argmax_rows(model.exit_logits(x, which))[0]))
     return out
 
 

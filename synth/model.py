@@ -39,11 +39,15 @@ TENSOR_IDS: Dict[str, int] = {
     "emb": 0, "head": 1, "gfinal": 2,
     "g1": 3, "wq": 4, "wk": 5, "wv": 6, "wo": 7,
     "g2": 8, "wgate": 9, "wup": 10, "wdown": 11,
+    "aux_g": 12, "aux_a": 13, "aux_b": 14,
 }
 GLOBAL_TENSORS = ("emb", "head", "gfinal")
 LAYER_TENSORS = ("g1", "wq", "wk", "wv", "wo", "g2", "wgate", "wup", "wdown")
-GAIN_TENSORS = ("gfinal", "g1", "g2")
-DAMPED_TENSORS = ("wo", "wdown")  # scaled by gamma[group of the layer]
+# auxiliary low-rank exit heads (cfg.head_rank > 0): one set per early exit, looked up with the exit
+# index in the layer slot (0 = L_d, 1 = L_i)
+EXIT_TENSORS = ("aux_g", "aux_a", "aux_b")
+GAIN_TENSORS = ("gfinal", "g1", "g2", "aux_g")
+DAMPED_TENSORS = ("wo", "wdown")  # scaled by gamma[group of the layer]; aux_b by gamma[exit index]
 
 
 @dataclasses.dataclass(frozen=True)
@@ -62,12 +66,14 @@ class EEConfig:
     dtype: str = "f32"       # "f32" | "bf16"
     sigma: float = 0.02
     gamma: Tuple[float, float, float] = (1.0, 1.0, 1.0)
+    head_rank: int = 0       # > 0: the exits L_d and L_i carry a low-rank adapter of this rank in front of the shared head
 
     def __post_init__(self):
         assert 0 < self.exit_draft < self.exit_inter < self.n_layers
         assert self.n_q_heads % self.n_kv_heads == 0
         assert self.head_dim % 2 == 0
         assert self.dtype in ("f32", "bf16")
+        assert self.head_rank >= 0 and (self.dtype == "f32" or self.head_rank % 32 == 0)
 
     @property
     def exit_full(self) -> int:
@@ -113,7 +119,9 @@ def llama70b_config(**kw) -> EEConfig:
 def tensor_shape(cfg: EEConfig, name: str) -> Tuple[int, ...]:
     d, hq, hkv, D, F, V = (cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads,
                            cfg.head_dim, cfg.d_ffn, cfg.vocab)
+    r = cfg.head_rank
     return {
+        "aux_g": (d,), "aux_a": (r, d), "aux_b": (d, r),
         "emb": (V, d), "head": (V, d), "gfinal": (d,),
         "g1": (d,), "g2": (d,),
         "wq": (hq * D, d), "wk": (hkv * D, d), "wv": (hkv * D, d),
@@ -172,13 +180,15 @@ def _lane_sum(key: int, e: np.ndarray) -> np.ndarray:
 
 def tensor_scale(cfg: EEConfig, name: str, layer: int) -> np.float32:
     gamma = cfg.gamma[cfg.group_of_layer(layer)] if name in DAMPED_TENSORS else 1.0
+    if name == "aux_b":
+        gamma = cfg.gamma[layer]
     s1 = np.float32(cfg.sigma) * np.float32(gamma)
     return np.float32(s1) * np.float32(2.0 ** -16)
 
 
 def gen_flat(cfg: EEConfig, seed: int, name: str, layer: int, e0: int, count: int) -> np.ndarray:
     """`count` consecutive elements (row-major index e0..) of a tensor, as float32."""
-    key = stream_key(seed, TENSOR_IDS[name], layer if name in LAYER_TENSORS else 0)
+    key = stream_key(seed, TENSOR_IDS[name], layer if name in LAYER_TENSORS + EXIT_TENSORS else 0)
     e = np.arange(e0, e0 + count, dtype=np.uint64)
     v = _lane_sum(key, e).astype(np.float32) * tensor_scale(cfg, name, layer)
     if name in GAIN_TENSORS:
@@ -234,7 +244,7 @@ class WeightStore:
         self._mem: Dict[Tuple[str, int], np.ndarray] = {}
 
     def get(self, name: str, layer: int = 0) -> np.ndarray:
-        k = (name, layer if name in LAYER_TENSORS else 0)
+        k = (name, layer if name in LAYER_TENSORS + EXIT_TENSORS else 0)
         if k in self._mem:
             return self._mem[k]
         t = gen_tensor(self.cfg, self.seed, name, k[1])
@@ -245,4 +255,4 @@ class WeightStore:
     def override(self, name: str, layer: int, value: np.ndarray) -> None:
         """Replace a tensor (tests that need hand-made weights)."""
         assert tuple(value.shape) == tensor_shape(self.cfg, name)
-        self._mem[(name, layer if name in LAYER_TENSORS else 0)] = np.asarray(value, np.float32)
+        self._mem[(name, layer if name in LAYER_TENSORS + EXIT_TENSORS else 0)] = np.asarray(value, np.float32)

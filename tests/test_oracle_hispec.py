@@ -219,3 +219,17 @@ def test_generate_truncates_to_requested_length():
     for n in (1, 2, 7):
         out = eo.HiSpecOracle(m).generate(prompt, n, 4, n_i=4)
         assert len(out) == n and out == eo.ar_generate(m, prompt, n)
+
+
+@pytest.mark.parametrize("round_mode", ["none", "bf16"])
+def test_hispec_stream_equals_ar_with_low_rank_exit_heads(round_mode):
+    """The early exits' own heads change what is drafted and what survives L_i, never the output."""
+    cfg = _cfg(exit_draft=2, exit_inter=4, head_rank=32, dtype="bf16" if round_mode == "bf16" else "f32")
+    m = _model(cfg, round_mode=round_mode)
+    plain = _model(_cfg(exit_draft=2, exit_inter=4, dtype=cfg.dtype), round_mode=round_mode)
+    prompt = synth.gen_prompt(cfg.vocab, 11, 7)
+    want = eo.ar_generate(m, prompt, 40)
+    assert want == eo.ar_generate(plain, prompt, 40)            # the final exit has no adapter
+    log = []
+    assert eo.HiSpecOracle(m, True, True).generate(prompt, 40, 3, n_i=4, log=log) == want
+    assert eo.ar_generate(m, prompt, 12, cfg.exit_draft) != eo.ar_generate(plain, prompt, 12, cfg.exit_draft)

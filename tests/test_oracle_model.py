@@ -106,3 +106,70 @@ def test_damping_makes_exits_identical():
     hf_, lf = m.forward_nocache(toks, cfg.n_layers)
     np.testing.assert_array_equal(hi, hf_)
     np.testing.assert_array_equal(li, lf)
+
+
+# --- auxiliary low-rank exit heads (App. I) -------------------------------------------------------
+
+def _aux_cfg(**kw):
+    return _small_cfg(head_rank=8, rms_eps=1e-12, **kw)
+
+
+def test_low_rank_head_with_zero_up_projection_is_the_shared_head():
+    cfg = _aux_cfg()
+    m, W = _model(cfg)
+    for e in (0, 1):
+        W.override("aux_b", e, np.zeros(synth.tensor_shape(cfg, "aux_b")))
+    x = np.random.default_rng(0).standard_normal((5, cfg.d_model))
+    for e in (0, 1):
+        np.testing.assert_array_equal(m.exit_logits(x, e), m.exit_logits(x, 2))
+
+
+def test_low_rank_head_leaves_the_final_exit_alone_and_changes_the_early_ones():
+    cfg = _aux_cfg()
+    m, _ = _model(cfg)
+    m0, _ = _model(_small_cfg(rms_eps=1e-12))
+    x = np.random.default_rng(1).standard_normal((4, cfg.d_model))
+    np.testing.assert_array_equal(m.exit_logits(x, 2), m0.exit_logits(x, 2))
+    assert np.max(np.abs(m.exit_logits(x, 0) - m0.exit_logits(x, 0))) > 1e-3
+    assert np.max(np.abs(m.exit_logits(x, 0) - m.exit_logits(x, 1))) > 1e-3      # each exit has its own adapter
+
+
+def test_full_rank_identity_adapter_only_rescales_the_hidden_state():
+    """A = I, B = c I, unit gain: z = x (1 + c / rms(x)) is a positive multiple of x, which the
+    shared RMSNorm removes again, so the logits are those of the shared head."""
+    cfg = _small_cfg(head_rank=64, rms_eps=1e-12)
+    m, W = _model(cfg)
+    d = cfg.d_model
+    W.override("aux_g", 0, np.ones(d))
+    W.override("aux_a", 0, np.eye(d))
+    W.override("aux_b", 0, 0.37 * np.eye(d))
+    x = np.random.default_rng(2).standard_normal((6, d))
+    np.testing.assert_allclose(m.exit_logits(x, 0), m.exit_logits(x, 2), rtol=1e-9, atol=1e-9)
+
+
+def test_single_entry_adapter_moves_one_coordinate_by_one_normalised_feature():
+    """A = e_i e_j^T, B = e_k e_i^T  =>  z = x + e_k * RMSNorm(x; g)_j: pins which index of each
+    factor is the input and which the output."""
+    cfg = _aux_cfg()
+    m, W = _model(cfg)
+    d, r = cfg.d_model, cfg.head_rank
+    i, j, k = 5, 17, 40
+    A = np.zeros((r, d)); A[i, j] = 1.0
+    B = np.zeros((d, r)); B[k, i] = 1.0
+    W.override("aux_a", 1, A)
+    W.override("aux_b", 1, B)
+    x = np.random.default_rng(3).standard_normal((3, d))
+    g = np.asarray(W.get("aux_g", 1), np.float64)
+    z = x.copy()
+    z[:, k] += x[:, j] * g[j] / np.sqrt(np.mean(x * x, axis=1))
+    np.testing.assert_allclose(m.exit_logits(x, 1), m.exit_logits(z, 2), rtol=1e-9, atol=1e-9)
+
+
+def test_low_rank_head_rounds_its_matrix_operands_in_bf16_mode():
+    cfg = _small_cfg(head_rank=32, dtype="bf16")
+    m, W = _model(cfg)
+    x = np.random.default_rng(4).standard_normal((2, cfg.d_model))
+    n = eo.round_bf16(eo.rmsnorm(x, np.asarray(W.get("aux_g", 0), np.float64), cfg.rms_eps))
+    t = eo.round_bf16(n @ np.asarray(W.get("aux_a", 0), np.float64).T)
+    z = x + t @ np.asarray(W.get("aux_b", 0), np.float64).T
+    np.testing.assert_array_equal(m.exit_logits(x, 0), m.exit_logits(z, 2))
