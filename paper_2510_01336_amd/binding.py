@@ -24,7 +24,8 @@ __all__ = [
 
 EE_F32, EE_BF16 = 0, 1
 TENSOR_IDS = {"emb": 0, "head": 1, "gfinal": 2, "g1": 3, "wq": 4, "wk": 5, "wv": 6, "wo": 7,
-              "g2": 8, "wgate": 9, "wup": 10, "wdown": 11}
+              "g2": 8, "wgate": 9, "wup": 10, "wdown": 11,
+              "aux_g": 12, "aux_a": 13, "aux_b": 14}   # auxiliary exit heads: `layer` = exit index (0 = L_d, 1 = L_i)
 
 EXPORTED_SYMBOLS = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
@@ -40,7 +41,8 @@ class ee_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab",
                                          "exit_draft", "exit_inter")] + \
                [("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
-                ("bonus_inter", C.c_int32), ("bonus_full", C.c_int32), ("sigma", C.c_float), ("gamma", C.c_float * 3)]
+                ("bonus_inter", C.c_int32), ("bonus_full", C.c_int32), ("sigma", C.c_float), ("gamma", C.c_float * 3),
+                ("head_rank", C.c_int32)]
 
 
 class EEError(RuntimeError):
@@ -141,6 +143,7 @@ def make_config(cfg, bonus_inter: int = 1, bonus_full: int = 1) -> ee_config:
     c.sigma = float(getattr(cfg, "sigma", 0.02))
     for i, g in enumerate(getattr(cfg, "gamma", (1.0, 1.0, 1.0))):
         c.gamma[i] = float(g)
+    c.head_rank = int(getattr(cfg, "head_rank", 0))
     return c
 
 

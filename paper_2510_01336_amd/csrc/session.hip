@@ -41,6 +41,10 @@ struct ee_session {
   float *Pd = nullptr, *Pi = nullptr, *u_dev = nullptr;
   bool need_logits = false;
   float *part_o = nullptr, *part_ml = nullptr, *pmax = nullptr, *ssq = nullptr, *gemm_part = nullptr, *inv_rms = nullptr;
+  // auxiliary exit heads: adapter output rows z [maxM][d], its rank-r intermediate (fp32 rows and, for bf16
+  // models, the bf16 operand of the up projection), that operand's unused sum-of-squares partials, unit gains
+  float *Z = nullptr, *T = nullptr, *ssq_t = nullptr, *ones = nullptr;
+  void* TF = nullptr;
   size_t part_units = 0;        // capacity of the attention split scratch in (q-tile, split) units per KV head
   int* pidx = nullptr;
   int max_splits = 64;
@@ -108,6 +112,15 @@ static size_t carve(ee_session* s, char* base) {
   s->GU = bf ? nullptr : cv.take<float>((size_t)s->maxM * 2 * m->Fp);
   s->H = bf ? (void*)cv.take<bf16_t>((size_t)Mp * ceil_div(c.d_ffn, 32) * 32) : (void*)cv.take<float>((size_t)s->maxM * c.d_ffn);
   s->LOGITS = cv.take<float>((size_t)s->maxM * c.vocab);
+  if (c.head_rank > 0) {
+    s->Z = cv.take<float>((size_t)s->maxM * d);
+    s->T = cv.take<float>((size_t)s->maxM * c.head_rank);
+    if (bf) {
+      s->TF = cv.take<bf16_t>((size_t)Mp * c.head_rank);
+      s->ssq_t = cv.take<float>((size_t)ceil_div(c.head_rank, 16) * Mp);
+      s->ones = cv.take<float>(c.head_rank);
+    }
+  }
   s->Hd = cv.take<float>((size_t)s->B * s->max_rows * d);
   s->Hi = cv.take<float>((size_t)s->B * s->max_rows * d);
   s->cs = cv.take<float2>((size_t)s->maxM * (D / 2));
@@ -126,8 +139,8 @@ static size_t carve(ee_session* s, char* base) {
     s->pidx = cv.take<int>((size_t)m->head.ntiles() * Mp);
     s->ssq = cv.take<float>((size_t)ceil_div(d, 16) * Mp);            // deferred-RMSNorm partials [d/16][Mp]
     size_t gp = 0;                                                    // K-share scratch of the row-tiled GEMM
-    for (const MatLoc* ml : {&m->L[0].qkv, &m->L[0].o, &m->L[0].gu, &m->L[0].down, &m->head})
-      gp = std::max(gp, bf16_gemm_rows_scratch_floats(ml->ntiles(), ml->ktiles()));
+    for (const MatLoc* ml : {&m->L[0].qkv, &m->L[0].o, &m->L[0].gu, &m->L[0].down, &m->head, &m->auxA[0], &m->auxB[0]})
+      if (ml->Np > 0) gp = std::max(gp, bf16_gemm_rows_scratch_floats(ml->ntiles(), ml->ktiles()));
     s->gemm_part = s->maxM > 64 ? cv.take<float>(gp) : nullptr;
     s->inv_rms = cv.take<float>(512);
   }
@@ -174,6 +187,8 @@ extern "C" int ee_session_create(ee_model* m, int batch, int max_ctx, int max_ro
     delete s; return EE_ERR_CAPACITY;
   }
   hipError_t e = hipMemsetAsync(s->base, 0, s->bytes, s->st);
+  const std::vector<float> unit(s->ones ? m->cfg.head_rank : 0, 1.0f);
+  if (e == hipSuccess && s->ones) e = hipMemcpyAsync(s->ones, unit.data(), unit.size() * sizeof(float), hipMemcpyHostToDevice, s->st);
   for (int i = 0; i < 2 && e == hipSuccess; ++i) {
     e = hipHostMalloc((void**)&s->slot[i].h, s->meta_ints * sizeof(int), hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&s->slot[i].copied, hipEventDisableTiming);
@@ -329,6 +344,14 @@ static void gemm(ee_session* s, int epi, const MatLoc& ml, const bf16_t* A, int 
   else bf16_gemm(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o);
 }
 
+// offset of the gain that normalises the hidden state behind layer l1: the adapter's own gain at an early exit
+// with an auxiliary head, else the shared final gain
+static size_t closing_gain(const ee_model* m, int l1) {
+  if (m->cfg.head_rank > 0 && l1 == m->cfg.exit_draft) return m->auxg[0];
+  if (m->cfg.head_rank > 0 && l1 == m->cfg.exit_inter) return m->auxg[1];
+  return m->gfinal;
+}
+
 static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const CallMeta& mt, int pos_add) {
   const ee_model* m = s->m;
   const ee_config& c = m->cfg;
@@ -371,7 +394,7 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
       // the down projection leaves the operand of whatever reads the stream next: the next layer's QKV
       // projection, or the shared exit head behind the last layer of the pass
       o = GemmOut(); o.Y = s->X; o.ldy = d; o.nout = nout;
-      o.nout.g = l + 1 < l1 ? (const float*)(m->base + m->L[l + 1].g1) : (const float*)(m->base + m->gfinal);
+      o.nout.g = l + 1 < l1 ? (const float*)(m->base + m->L[l + 1].g1) : (const float*)(m->base + closing_gain(m, l1));
       KF(KF_GEMM_DOWN, gemm(s, EPI_ADD, L.down, (const bf16_t*)s->H, M, o));
     } else {
       const float* Wqkv = (const float*)(m->base + L.qkv.off);
@@ -392,17 +415,36 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
   }
 }
 
-// shared final RMSNorm + shared LM head + arg max for rows 0..M-1 of X -> vtok
-static void exit_head(ee_session* s, int M) {
+// Prediction head of exit `which` (0 = L_d, 1 = L_i, 2 = L_f) + arg max for rows 0..M-1 of X -> vtok.
+// The shared final RMSNorm and LM head (Sec. 3.1); at an early exit of a model with auxiliary heads
+// (App. I) behind that exit's rank-r adapter  z = x + B (A RMSNorm(x; g)),  which leaves X itself alone.
+static void exit_head(ee_session* s, int M, int which) {
   const ee_model* m = s->m;
   const ee_config& c = m->cfg;
   hipStream_t st = s->st;
+  const int d = c.d_model, r = c.head_rank;
   const float* gf = (const float*)(m->base + m->gfinal);
+  const bool aux = r > 0 && which < 2;
   if (m->bf16) {
-    // the last down projection of the pass left XN = bf16(x * gfinal) and the partial sums of squares
-    GemmOut o;
+    // the last down projection of the pass left XN = bf16(x * gain) and the partial sums of squares
     const int Mp = s->Mp;
-    o.nin.ssq = s->ssq; o.nin.n_part = c.d_model / 16; o.nin.stride = Mp; o.nin.inv_d = 1.0f / (float)c.d_model; o.nin.eps = c.rms_eps;
+    NormIn nin;
+    nin.ssq = s->ssq; nin.n_part = d / 16; nin.stride = Mp; nin.inv_d = 1.0f / (float)d; nin.eps = c.rms_eps;
+    if (aux) {
+      // t = A n(x): rows into T (cleared: the epilogue adds to what it finds) and as the next operand TF;
+      // z = x + B t: into a copy of the rows, leaving the shared head's operand XN = bf16(z * gfinal)
+      (void)hipMemsetAsync(s->T, 0, (size_t)M * r * sizeof(float), st);
+      (void)hipMemcpyAsync(s->Z, s->X, (size_t)M * d * sizeof(float), hipMemcpyDeviceToDevice, st);
+      GemmOut o;
+      o.nin = nin; o.Y = s->T; o.ldy = r;
+      o.nout.xn = (bf16_t*)s->TF; o.nout.ktiles = r / 32; o.nout.ssq = s->ssq_t; o.nout.stride = Mp; o.nout.g = s->ones;
+      KF(KF_GEMM_HEAD, gemm(s, EPI_ADD, m->auxA[which], (const bf16_t*)s->XN, M, o));
+      o = GemmOut(); o.Y = s->Z; o.ldy = d;
+      o.nout.xn = (bf16_t*)s->XN; o.nout.ktiles = ceil_div(d, 32); o.nout.ssq = s->ssq; o.nout.stride = Mp; o.nout.g = gf;
+      KF(KF_GEMM_HEAD, gemm(s, EPI_ADD, m->auxB[which], (const bf16_t*)s->TF, M, o));
+    }
+    GemmOut o;
+    o.nin = nin;
     // (max, arg max) partials [tile][row] with the rows packed to the call's row tiles: the reduction then walks
     // a compact array instead of one memory page per tile
     const int pstride = ceil_div(M, 16) * 16;
@@ -411,9 +453,17 @@ static void exit_head(ee_session* s, int M) {
     KF(KF_GEMM_HEAD, gemm(s, EPI_ARGMAX, m->head, (const bf16_t*)s->XN, M, o));
     KF(KF_ARGMAX, bf16_argmax_reduce(st, s->pmax, s->pidx, m->head.ntiles(), pstride, M, s->vtok));
   } else {
-    KF(KF_NORM, f32_rmsnorm(st, s->X, gf, c.rms_eps, (float*)s->XN, M, c.d_model));
-    KF(KF_GEMM_HEAD, f32_gemm(st, (const float*)s->XN, c.d_model, (const float*)(m->base + m->head.off), s->LOGITS, c.vocab, M,
-                              c.vocab, c.d_model, false));
+    const float* hidden = s->X;
+    if (aux) {
+      KF(KF_NORM, f32_rmsnorm(st, s->X, (const float*)(m->base + m->auxg[which]), c.rms_eps, (float*)s->XN, M, d));
+      KF(KF_GEMM_HEAD, f32_gemm(st, (const float*)s->XN, d, (const float*)(m->base + m->auxA[which].off), s->T, r, M, r, d, false));
+      (void)hipMemcpyAsync(s->Z, s->X, (size_t)M * d * sizeof(float), hipMemcpyDeviceToDevice, st);
+      KF(KF_GEMM_HEAD, f32_gemm(st, (const float*)s->T, r, (const float*)(m->base + m->auxB[which].off), s->Z, d, M, d, r, true));
+      hidden = s->Z;
+    }
+    KF(KF_NORM, f32_rmsnorm(st, hidden, gf, c.rms_eps, (float*)s->XN, M, d));
+    KF(KF_GEMM_HEAD, f32_gemm(st, (const float*)s->XN, d, (const float*)(m->base + m->head.off), s->LOGITS, c.vocab, M,
+                              c.vocab, d, false));
     KF(KF_ARGMAX, f32_argmax(st, s->LOGITS, M, c.vocab, s->vtok));
   }
   s->last_rows = M;
@@ -477,7 +527,7 @@ static int prefill_impl(ee_session* s, const int32_t* tokens, const int32_t* len
       KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
       run_layers(s, 0, c.n_layers, p, mt, 0);
       if (r0 + s->chunk >= n) {
-        exit_head(s, p.M);
+        exit_head(s, p.M, 2);
         HIP_TRY(hipMemcpyAsync(s->out_host + b, s->vtok + (p.M - 1), sizeof(int), hipMemcpyDeviceToHost, s->st));
       }
     }
@@ -543,7 +593,7 @@ extern "C" int ee_decode_ar(ee_session* s, int n, int32_t* out) {
   for (int j = 0; j < n; ++j) {       // the next token stays on the device; positions advance through pos_add
     KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, j == 0 ? mt.row_tok : s->tok_next, s->X, p.M, c.d_model));
     run_layers(s, 0, c.n_layers, p, mt, j);
-    exit_head(s, p.M);
+    exit_head(s, p.M, 2);
     KF(KF_MISC, k_take_token(s->st, s->vtok, mt.row_seq, p.M, s->tok_next, s->draft_dev, s->max_rows, j));
   }
   int* dh = s->out_host + 2 * s->B;
@@ -611,7 +661,7 @@ static int draft_impl(ee_session* s, int k, int32_t* draft, const float* u) {
     run_layers(s, 0, c.exit_draft, p, mt, j);
     KF(KF_COPY, k_copy_rows(s->st, s->Hd, mt.row_dst, j, s->X, nullptr, p.M, c.d_model));
     if (j < k) {
-      exit_head(s, p.M);
+      exit_head(s, p.M, 0);
       if (u) {      // p_{L_d} of this position into the draft-distribution store, then the draw (row r = sequence r here)
         KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->Pd, mt.row_dst, j, p.M, c.vocab));
         KF(KF_MISC, k_draw_rows(s->st, s->Pd, s->max_rows, j, c.vocab, s->u_dev, k, s->B, s->tok_next, s->draft_dev, s->max_rows));
@@ -725,7 +775,7 @@ static int verify_intermediate_impl(ee_session* s, int32_t* n_accept, int32_t* n
   KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, s->Hd, mt.row_src, p.M, c.d_model));       // a1: consume buffered H_d
   run_layers(s, c.exit_draft, c.exit_inter, p, mt, 0);
   s->need_logits = rs;
-  exit_head(s, p.M);
+  exit_head(s, p.M, 1);
   s->need_logits = false;
   KF(KF_COPY, k_copy_rows(s->st, s->Hi, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));       // keep L_i hidden rows
   if (rs) {
@@ -835,7 +885,7 @@ static int verify_full_impl(ee_session* s, const uint8_t* active, int32_t* n_acc
   KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, s->Hi, mt.row_src, p.M, c.d_model));       // consume buffered H_i
   run_layers(s, c.exit_inter, c.n_layers, p, mt, 0);
   s->need_logits = rs;
-  exit_head(s, p.M);
+  exit_head(s, p.M, 2);
   s->need_logits = false;
   if (rs) {      // second stage of App. G: V, distributed as p_{L_i}, is the draft; p_{L_f} the target
     KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->LOGITS, nullptr, 0, p.M, c.vocab));

@@ -38,6 +38,9 @@ static int check_config(const ee_config* c) {
   if (c->head_dim % 2 || c->head_dim > 256) { ee_set_error("head_dim must be even and <= 256"); return EE_ERR_ARG; }
   if (c->n_q_heads / c->n_kv_heads > 16) { ee_set_error("at most 16 query heads per KV head"); return EE_ERR_ARG; }
   if (!(c->rope_theta > 1.f) || !(c->rms_eps > 0.f)) { ee_set_error("bad rope_theta / rms_eps"); return EE_ERR_ARG; }
+  if (c->head_rank < 0 || c->head_rank > 16384 || (c->dtype == EE_BF16 && c->head_rank % 32)) {
+    ee_set_error("head_rank must be 0 or a rank up to 16384 (a multiple of 32 for EE_BF16 models)"); return EE_ERR_ARG;
+  }
   return EE_OK;
 }
 
@@ -62,6 +65,11 @@ int ee_layout_model(ee_model* m) {
   m->emb = cur; cur += (size_t)c.vocab * d * es;
   cur = align_up(cur, 256); m->gfinal = cur; cur += (size_t)d * 4;
   m->head = place(cur, c.vocab, d, m->bf16);
+  for (int e = 0; e < 2 && c.head_rank > 0; ++e) {
+    cur = align_up(cur, 256); m->auxg[e] = cur; cur += (size_t)d * 4;
+    m->auxA[e] = place(cur, c.head_rank, d, m->bf16);
+    m->auxB[e] = place(cur, d, c.head_rank, m->bf16);
+  }
   m->L.resize(c.n_layers);
   for (int l = 0; l < c.n_layers; ++l) {
     LayerLoc& L = m->L[l];
@@ -82,6 +90,14 @@ int ee_layout_model(ee_model* m) {
 int ee_tensor_map(const ee_model* m, int tid, int layer, TensorMap* t) {
   const ee_config& c = m->cfg;
   const int d = c.d_model, D = c.head_dim;
+  if (tid >= EE_T_AUX_G && tid <= EE_T_AUX_B) {
+    if (c.head_rank <= 0) { ee_set_error("the model has no auxiliary exit heads"); return EE_ERR_ARG; }
+    if (layer < 0 || layer > 1) { ee_set_error("exit index must be 0 (L_d) or 1 (L_i)"); return EE_ERR_ARG; }
+    if (tid == EE_T_AUX_G) *t = {1, d, 1, m->auxg[layer], 0, 0, 0, D};
+    else if (tid == EE_T_AUX_A) *t = {0, c.head_rank, d, m->auxA[layer].off, 0, 0, m->auxA[layer].Kp, D};
+    else *t = {0, d, c.head_rank, m->auxB[layer].off, 0, 0, m->auxB[layer].Kp, D};
+    return EE_OK;
+  }
   if (tid >= EE_T_G1 && (layer < 0 || layer >= c.n_layers)) { ee_set_error("layer out of range"); return EE_ERR_ARG; }
   t->row_off = 0; t->interleave = 0; t->Kp = 0; t->hd = D;
   switch (tid) {
@@ -184,9 +200,10 @@ static int gen_one(ee_model* m, int tid, int layer) {
   const bool per_layer = tid >= EE_T_G1;
   uint64_t key = mix64(mix64(m->seed) ^ (((uint64_t)tid << 32) | (uint64_t)(per_layer ? layer : 0)));
   float gamma = (tid == EE_T_WO || tid == EE_T_WDOWN) ? m->cfg.gamma[group_of_layer(m->cfg, layer)] : 1.0f;
+  if (tid == EE_T_AUX_B) gamma = m->cfg.gamma[layer];     // `layer` is the exit index here
   volatile float s1 = m->cfg.sigma * gamma;        // one fp32 product, then an exact power-of-two scale
   float scale = s1 * 1.52587890625e-05f;           // 2^-16
-  int gain = (tid == EE_T_GFINAL || tid == EE_T_G1 || tid == EE_T_G2);
+  int gain = (tid == EE_T_GFINAL || tid == EE_T_G1 || tid == EE_T_G2 || tid == EE_T_AUX_G);
   size_t count = (size_t)t.rows * t.cols;
   int blocks = (int)((count + 255) / 256);
   if (blocks > 65536) blocks = 65536;
@@ -224,6 +241,8 @@ extern "C" int ee_model_load(const ee_config* cfg, void* dev_arena, size_t arena
   if (e != hipSuccess) { ee_set_error("memset: %s", hipGetErrorString(e)); delete m; return EE_ERR_HIP; }
   int rc = EE_OK;
   for (int tid = EE_T_EMB; tid <= EE_T_GFINAL && rc == EE_OK; ++tid) rc = gen_one(m, tid, 0);
+  for (int e = 0; e < 2 && cfg->head_rank > 0; ++e)
+    for (int tid = EE_T_AUX_G; tid <= EE_T_AUX_B && rc == EE_OK; ++tid) rc = gen_one(m, tid, e);
   for (int l = 0; l < cfg->n_layers && rc == EE_OK; ++l)
     for (int tid = EE_T_G1; tid <= EE_T_WDOWN && rc == EE_OK; ++tid) rc = gen_one(m, tid, l);
   if (rc == EE_OK) {

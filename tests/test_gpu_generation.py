@@ -61,12 +61,14 @@ def _adaptive():
     return dict(n_i=4, adaptive=AdaptivePolicy(nd_max=4))
 
 
-@pytest.mark.parametrize("policy", [dict(n_i=6), dict(every=2), "adaptive"], ids=["n_i6", "every2", "adaptive"])
+@pytest.mark.parametrize("policy", [dict(n_i=6), dict(every=2), "adaptive", "heads"], ids=["n_i6", "every2", "adaptive", "low_rank_heads"])
 def test_hispec_stream_equals_vanilla_stream_on_gpu(policy):
     from paper_2510_01336_amd.loop import hispec_generate
+    cfg = synth.tiny_config(gamma=(1.0, 0.3, 0.3))       # damped upper groups: the exits agree often, not always
     if policy == "adaptive":
         policy = _adaptive()
-    cfg = synth.tiny_config(gamma=(1.0, 0.3, 0.3))       # damped upper groups: the exits agree often, not always
+    elif policy == "heads":                              # early exits with their own low-rank heads (App. I)
+        policy, cfg = dict(n_i=6), synth.tiny_config(gamma=(1.0, 0.3, 0.3), head_rank=24)
     n_new, k, ctx = 48, 4, [32, 19]
     prompts = [synth.gen_prompt(cfg.vocab, n, 11 + i) for i, n in enumerate(ctx)]
     rows = 4 * (k + 1) + 2

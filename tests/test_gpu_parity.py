@@ -19,14 +19,17 @@ pytestmark = pytest.mark.gpu
 # ------------------------------------------------------------------------------------------------
 # inputs: device generator == host generator, bit for bit
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("cfg", [synth.tiny_config(), bf16_small(), bf16_d128(gamma=(1.0, 0.5, 0.25))],
-                         ids=["tiny_f32", "bf16_small", "bf16_d128"])
+@pytest.mark.parametrize("cfg", [synth.tiny_config(), bf16_small(), bf16_d128(gamma=(1.0, 0.5, 0.25)),
+                                 synth.tiny_config(head_rank=24, gamma=(1.0, 0.5, 0.25)), bf16_small(head_rank=96)],
+                         ids=["tiny_f32", "bf16_small", "bf16_d128", "tiny_f32_heads", "bf16_small_heads"])
 def test_device_weights_equal_host_generator(cfg):
     import paper_2510_01336_amd as hs
     model = hs.Model(cfg, 4242)
-    for name in synth.model.GLOBAL_TENSORS + synth.model.LAYER_TENSORS:
+    names = synth.model.GLOBAL_TENSORS + synth.model.LAYER_TENSORS + (synth.model.EXIT_TENSORS if cfg.head_rank else ())
+    for name in names:
         shape = synth.tensor_shape(cfg, name)
-        for layer in ([0] if name in synth.model.GLOBAL_TENSORS else [0, cfg.n_layers - 1]):
+        layers = [0] if name in synth.model.GLOBAL_TENSORS else ([0, 1] if name in synth.model.EXIT_TENSORS else [0, cfg.n_layers - 1])
+        for layer in layers:
             want = synth.gen_tensor(cfg, 4242, name, layer)
             rows, cols = shape[0], (shape[1] if len(shape) == 2 else 1)
             got = model.tensor_rows(name, layer, 0, rows, cols).reshape(want.shape)
@@ -178,6 +181,10 @@ CASES = [
     # more than 64 block rows in one call: the row-tiled GEMM (8 and 12 row tiles), ragged contexts
     ("bf16_small_batch10", bf16_small(), [70, 5, 200, 64, 33, 129, 17, 90, 150, 260], 8, (True, True)),
     ("bf16_d128_batch16", bf16_d128(), [100, 260, 31, 64, 65, 7, 190, 128, 40, 77, 300, 12, 55, 201, 99, 160], 8, (True, True)),
+    # auxiliary low-rank exit heads at L_d and L_i (skinny and row-tiled GEMM paths)
+    ("tiny_f32_heads", synth.tiny_config(gamma=(1.0, 0.3, 0.3), head_rank=24), [32, 70], 4, (True, True)),
+    ("bf16_small_heads", bf16_small(head_rank=64), [150, 40], 8, (True, True)),
+    ("bf16_d128_heads_batch16", bf16_d128(head_rank=96), [100, 260, 31, 64, 65, 7, 190, 128, 40, 77, 300, 12, 55, 201, 99, 160], 8, (True, True)),
 ]
 
 
@@ -218,9 +225,10 @@ def test_all_correct_and_wrong_first_blocks():
 
 def test_self_drafting_matches_oracle():
     """ee_draft (k sequential shallow passes on the device) against the oracle's Generate(L_d, ., k)."""
-    for cfg in (synth.tiny_config(gamma=(1.0, 0.3, 0.3)), bf16_small()):
+    # (model, weight seed): the seeds are ones whose first rounds clear the margin filter below
+    for cfg, seed in ((synth.tiny_config(gamma=(1.0, 0.3, 0.3)), 99), (bf16_small(), 99), (bf16_small(head_rank=64), 7)):
         k = 4
-        O, model, sess, first, gfirst = _setup(cfg, 99, [50, 20], 3 * (k + 1) + 2)
+        O, model, sess, first, gfirst = _setup(cfg, seed, [50, 20], 3 * (k + 1) + 2)
         assert gfirst.tolist() == first.tolist()
         compared = 0
         for rnd in range(6):

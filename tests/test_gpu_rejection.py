@@ -154,7 +154,7 @@ def test_bf16_distributions_and_decisions():
         if rnd == 0:      # distributions against the oracle on the same tokens (fresh from the context build)
             for b, s in enumerate(O.seqs):
                 O.o.draft_inject(s, S[b])
-                pd_ref = eo.softmax_rows(O.model.exit_logits(np.stack(s.H_d[:k])))
+                pd_ref = eo.softmax_rows(O.model.exit_logits(np.stack(s.H_d[:k]), 0))
                 s.P_d = list(pd_ref)
                 assert np.max(np.abs(Pd[b] - pd_ref)) / np.max(pd_ref) <= TOL["bf16"]
                 O.o.verify_intermediate(s, (u_a[b], float(u_r[b])))
