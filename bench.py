@@ -54,6 +54,7 @@ WORKLOADS = {
     "8b_b1_ctx32768_k16_r4": (synth.llama8b_config, [32768], 16, 0.9, 4),
     "8b_b1_ctx32768_k16_li8_r4": (lambda: synth.llama8b_config(exit_inter=8), [32768], 16, 0.9, 4),
     "8b_b1_ctx32768_k16_li24_r4": (lambda: synth.llama8b_config(exit_inter=24), [32768], 16, 0.9, 4),
+    "8b_b1_ctx2048_k8_heads1024": (lambda: synth.llama8b_config(head_rank=1024), [2048], 8, 0.8),   # low-rank heads at L_d, L_i
     "70b_b4_ctx1024_k8": (synth.llama70b_config, [1024] * 4, 8, 0.75),
     "tiny_b1_ctx32_k4": (lambda: synth.tiny_config(gamma=(1.0, 0.3, 0.3)), [32], 4, 0.8),
     "8b_reduced_b1_ctx2048_k8": (lambda: synth.llama8b_config(n_layers=8, exit_draft=1, exit_inter=4), [2048], 8, 0.8),
@@ -147,7 +148,8 @@ def step_bytes(cfg, ctxs, k, rows_full, rounds=1):
     kv_layer = sum(ctxs) * 2 * Hkv * D * es
     # rounds x (G1 + G2), G3, + catch-up row through G1+G2
     layers = rounds * cfg.exit_inter + (cfg.n_layers - cfg.exit_inter) + (cfg.exit_inter if rows_full else 0)
-    return layers * (per_layer + kv_layer) + (rounds + 1) * head
+    aux = 2 * cfg.head_rank * d * es           # the intermediate exit's low-rank adapter, once per round
+    return layers * (per_layer + kv_layer) + (rounds + 1) * head + rounds * aux
 
 
 def build_workload(name, seed=MODEL_SEED):
