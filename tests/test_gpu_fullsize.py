@@ -114,6 +114,77 @@ def test_full_width_reduced_depth_matches_oracle():
     sess.close(); model.close()
 
 
+class _SampledHead:
+    """A weight store whose LM head holds only the rows of chosen token ids, so that the oracle's own exit
+    head code yields the logits of those ids without the 128256 x 4096 matrix."""
+
+    def __init__(self, store, cfg, seed, ids):
+        self.store, self.rows = store, _head_rows(cfg, seed, ids)
+
+    def get(self, name, layer=0):
+        return self.rows if name == "head" else self.store.get(name, layer)
+
+
+def test_full_width_low_rank_heads_match_oracle():
+    """Rank-1024 exit heads at the 8B width (App. I): the L_d head while self-drafting and the L_i head of a
+    verification, on sampled logits, through the launch shapes of the full-size model."""
+    import paper_2510_01336_amd as hs
+    cfg = synth.llama8b_config(n_layers=3, exit_draft=1, exit_inter=2, gamma=(1.0, 0.3, 0.3), head_rank=1024)
+    k, ctx = 8, 200
+    tol = TOL["bf16"]
+    W = synth.WeightStore(cfg, SEED)
+    om = eo.EEModel(eo.ModelSpec.from_config(cfg), W)
+    om.embed = _RowEmb(cfg, SEED)
+    orc = eo.HiSpecOracle(om)
+    seq = eo.Sequence_(om.spec, ctx + 64)
+    prompt = synth.gen_prompt(cfg.vocab, ctx, 5)
+    om.run_layers(range(cfg.n_layers), om.embed(prompt), np.arange(ctx), seq.cache)
+    model = hs.Model(cfg, SEED)
+    sess = hs.Session(model, 1, ctx + 64, 3 * (k + 1) + 2)
+    sess.enable_logits(True)
+    first = int(sess.prefill([prompt])[0])
+    seq.C, seq.len, seq.prompt_len = [int(t) for t in prompt] + [first], [ctx, ctx, ctx], ctx
+    rng = np.random.default_rng(1)
+
+    def sampled_logits(hidden_row, which, gpu_row):
+        ids = _sample_ids(cfg.vocab, gpu_row, rng)
+        ref = eo.EEModel(om.spec, _SampledHead(W, cfg, SEED, ids)).exit_logits(hidden_row, which)[0]
+        return ids, ref
+
+    # one self-drafted token in a session of its own: the L_d head (adapter 0) on the pending token's row
+    sess_d = hs.Session(model, 1, ctx + 64, 3 * (k + 1) + 2)
+    sess_d.enable_logits(True)
+    assert int(sess_d.prefill([prompt])[0]) == first
+    gS = sess_d.draft(1)
+    glog = sess_d.last_logits()[0]                         # the bonus row that follows runs no head
+    x = om.run_layers(om.spec.group_layers(0), om.embed([first]), np.array([ctx]), seq.cache)
+    ids, ref = sampled_logits(x, 0, glog)
+    assert np.max(np.abs(glog[ids] - ref)) / np.max(np.abs(ref)) <= tol
+    assert int(gS[0][0]) == int(np.argmax(glog))
+    sess_d.close()
+
+    # a random block through L_i: hidden rows and the adapter + shared head on sampled ids
+    S = rng.integers(0, cfg.vocab, k).astype(np.int32)
+    sess.draft_inject(S[None])
+    ga, gn = sess.verify_intermediate()
+    ghid, glog = sess.last_hidden(), sess.last_logits()
+    orc.draft_inject(seq, S)
+    p0 = len(seq.T) - 1
+    Y = om.run_layers(om.spec.group_layers(1), np.stack(seq.H_d), p0 + np.arange(k + 1), seq.cache)
+    assert max_rel(ghid[:k + 1], Y) <= tol
+    plain = 0
+    for r in range(k + 1):
+        ids, ref = sampled_logits(Y[r:r + 1], 1, glog[r])
+        assert np.max(np.abs(glog[r, ids] - ref)) / np.max(np.abs(ref)) <= tol, r
+        shared = _oracle_logits_at(cfg, SEED, Y[r:r + 1], ids)[0]
+        plain += np.max(np.abs(glog[r, ids] - shared)) / np.max(np.abs(shared)) > tol
+    assert plain >= k                                      # the adapter matters: the shared head alone is off
+    v = np.argmax(glog[:k + 1], axis=1)
+    a, out = eo.leading_substring_verify(S, v)
+    assert (int(ga[0]), int(gn[0])) == (a, out[-1])
+    sess.close(); model.close()
+
+
 def _greedy_block(sess, cfg, k, ctx, rng):
     """The intermediate verifier's teacher-forced greedy continuation, found with k untimed rounds."""
     greedy = np.zeros(k, np.int64)
