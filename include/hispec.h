@@ -129,13 +129,22 @@ int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* lens, int32_
 
 /* The same for one sequence while the others keep their state (a finished request leaves, a new one takes its
  * slot): the sequence's pages return to the shared pool, then its new prompt (host, len >= 1 tokens) is built.
- * EE_ERR_CAPACITY if the pool cannot hold it; the session is unchanged then.  Calls that step the whole batch
- * (draft, verify) require every sequence to be started. */
+ * EE_ERR_CAPACITY if the pool cannot hold it; the session is unchanged then. */
 int ee_prefill_seq(ee_session* s, int seq, const int32_t* tokens, int len, int32_t* first_token);
+
+/* A finished request leaves its slot: the sequence's KV pages return to the shared pool (Sec. 3.2: only the
+ * block table changes) and its tokens, lengths and pending blocks are dropped.  The slot is idle until
+ * ee_prefill / ee_prefill_seq starts it again: the batch-wide calls (ee_draft*, ee_verify_*, ee_decode_ar)
+ * step the started sequences only and report -1 (tokens and accept counts) for an idle slot; they fail with
+ * EE_ERR_STATE when no sequence is started.  EE_ERR_ARG for a bad index. */
+int ee_seq_release(ee_session* s, int seq);
+
+/* Pages of the shared KV pool that no sequence holds (64 positions of every layer each). */
+int ee_free_pages(const ee_session* s);
 
 /* Vanilla generation of Sec. 3.1 (the baseline the method is measured against and whose output it must
  * reproduce): n greedy single-token steps through all L_f layers per sequence, each committing
- * arg max at L_f.  Requires every sequence to be started with an empty tentative buffer and no pending
+ * arg max at L_f.  Requires every started sequence to have an empty tentative buffer and no pending
  * draft block (EE_ERR_STATE otherwise); 1 <= n <= max_rows; EE_ERR_CAPACITY if positions would overflow.
  * All three group lengths advance by n.  out: host [batch, n], the committed tokens. */
 int ee_decode_ar(ee_session* s, int n, int32_t* out);

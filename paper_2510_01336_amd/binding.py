@@ -14,7 +14,7 @@ import numpy as np
 __all__ = [
     "lib", "lib_path", "EEError", "ee_config", "make_config", "Model", "Session",
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
-    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_decode_ar", "ee_draft", "ee_draft_inject",
+    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_seq_release", "ee_free_pages", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
@@ -29,7 +29,7 @@ TENSOR_IDS = {"emb": 0, "head": 1, "gfinal": 2, "g1": 3, "wq": 4, "wk": 5, "wv":
 
 EXPORTED_SYMBOLS = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
-    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_decode_ar", "ee_draft", "ee_draft_inject",
+    "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_seq_release", "ee_free_pages", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
@@ -77,6 +77,8 @@ def _load():
         "ee_prefill": (C.c_int, [vp, i32p, i32p, i32p]),
         "ee_decode_ar": (C.c_int, [vp, C.c_int, i32p]),
         "ee_prefill_seq": (C.c_int, [vp, C.c_int, i32p, C.c_int, i32p]),
+        "ee_seq_release": (C.c_int, [vp, C.c_int]),
+        "ee_free_pages": (C.c_int, [vp]),
         "ee_draft": (C.c_int, [vp, C.c_int, i32p]),
         "ee_draft_inject": (C.c_int, [vp, C.c_int, i32p]),
         "ee_verify_intermediate": (C.c_int, [vp, i32p, i32p]),
@@ -214,6 +216,14 @@ def ee_prefill(session: int, tokens: np.ndarray, lens: np.ndarray) -> np.ndarray
     first = np.empty(len(l), np.int32)
     _chk(lib.ee_prefill(session, _p_i32(t), _p_i32(l), _p_i32(first)))
     return first
+
+
+def ee_seq_release(session: int, seq: int) -> None:
+    _chk(lib.ee_seq_release(session, seq))
+
+
+def ee_free_pages(session: int) -> int:
+    return int(lib.ee_free_pages(session))
 
 
 def ee_prefill_seq(session: int, seq: int, tokens: np.ndarray) -> int:
@@ -420,6 +430,12 @@ class Session:
 
     def prefill_seq(self, seq: int, prompt: np.ndarray) -> int:
         return ee_prefill_seq(self.handle, seq, prompt)
+
+    def release(self, seq: int) -> None:
+        ee_seq_release(self.handle, seq)
+
+    def free_pages(self) -> int:
+        return ee_free_pages(self.handle)
 
     def decode_ar(self, n: int) -> np.ndarray:
         return ee_decode_ar(self.handle, self.batch, n)

@@ -88,7 +88,7 @@ void bf16_argmax_reduce(hipStream_t st, const float* pmax, const int* pidx, int 
 void k_softmax_rows(hipStream_t st, const float* in, size_t in_stride, float* out, const int* out_idx, int out_add, int M, int vocab);
 void k_rs_accept(hipStream_t st, const float* Pt, const float* Pd, int pd_rows_per_seq, int vocab, const CallMeta& meta,
                  int cand_stride, int B, const float* u_acc, int u_stride, int* n_accept);
-void k_draw_rows(hipStream_t st, const float* P, int rows_per_seq, int j, int vocab, const float* u, int u_stride, int B,
-                 int* tok_next, int* draft_out, int stride);
+void k_draw_rows(hipStream_t st, const float* P, int rows_per_seq, int j, int vocab, const float* u, int u_stride,
+                 const int* row_seq, int M, int* tok_next, int* draft_out, int stride);
 void k_rs_draw(hipStream_t st, const float* Pt, const float* Pd, int pd_rows_per_seq, int vocab, const CallMeta& meta, int B,
                const int* n_accept, const float* u_res, int* next_tok);

@@ -127,18 +127,19 @@ __device__ inline int draw_token(const float* __restrict__ A, const float* __res
 
 // drafting: token of sequence b ~ row b*rows_per_seq + j of P (the distribution just stored there)
 __global__ __launch_bounds__(EE_SAMPLE_THREADS) void draw_rows_kernel(const float* __restrict__ P, int rows_per_seq, int j, int vocab,
-                                                                      const float* __restrict__ u, int u_stride, int* tok_next,
+                                                                      const float* __restrict__ u, int u_stride,
+                                                                      const int* __restrict__ row_seq, int* tok_next,
                                                                       int* draft_out, int stride) {
   __shared__ float chunk[EE_SAMPLE_THREADS];
   __shared__ int hit[2];
-  const int b = blockIdx.x;
+  const int r = blockIdx.x, b = row_seq[r];            // one row per drafting sequence
   const int tok = draw_token(P + ((size_t)b * rows_per_seq + j) * vocab, nullptr, vocab, u[(size_t)b * u_stride + j], chunk, hit);
-  if (threadIdx.x == 0) { tok_next[b] = tok; draft_out[b * stride + j] = tok; }
+  if (threadIdx.x == 0) { tok_next[r] = tok; draft_out[b * stride + j] = tok; }
 }
-void k_draw_rows(hipStream_t st, const float* P, int rows_per_seq, int j, int vocab, const float* u, int u_stride, int B,
-                 int* tok_next, int* draft_out, int stride) {
-  hipLaunchKernelGGL(draw_rows_kernel, dim3(B), dim3(EE_SAMPLE_THREADS), 0, st, P, rows_per_seq, j, vocab, u, u_stride, tok_next,
-                     draft_out, stride);
+void k_draw_rows(hipStream_t st, const float* P, int rows_per_seq, int j, int vocab, const float* u, int u_stride,
+                 const int* row_seq, int M, int* tok_next, int* draft_out, int stride) {
+  hipLaunchKernelGGL(draw_rows_kernel, dim3(M), dim3(EE_SAMPLE_THREADS), 0, st, P, rows_per_seq, j, vocab, u, u_stride, row_seq,
+                     tok_next, draft_out, stride);
 }
 
 // after the accept tests: the replacement from the residual distribution at the first rejected position, or,

@@ -568,22 +568,37 @@ extern "C" int ee_prefill_seq(ee_session* s, int seq, const int32_t* tokens, int
 // ---------------------------------------------------------------------------------------------
 // C ABI: vanilla greedy generation at full depth (Sec. 3.1)
 // ---------------------------------------------------------------------------------------------
+extern "C" int ee_seq_release(ee_session* s, int seq) {
+  if (!s || seq < 0 || seq >= s->B) { ee_set_error("bad sequence index"); return EE_ERR_ARG; }
+  SeqState& q = s->seq[seq];
+  while (!q.pages.empty()) { s->free_pages.push_back(q.pages.back()); q.pages.pop_back(); }
+  q = SeqState();
+  return EE_OK;
+}
+
+extern "C" int ee_free_pages(const ee_session* s) { return s ? (int)s->free_pages.size() : -1; }
+
 extern "C" int ee_decode_ar(ee_session* s, int n, int32_t* out) {
   if (!s || !out) { ee_set_error("null argument"); return EE_ERR_ARG; }
   const ee_config& c = s->m->cfg;
   if (n < 1 || n > s->max_rows) { ee_set_error("%d tokens per call do not fit max_rows %d", n, s->max_rows); return EE_ERR_ARG; }
-  std::vector<int> want(s->B);
+  std::vector<int> want(s->B, 0);
+  int live = 0;
   for (int b = 0; b < s->B; ++b) {
     const SeqState& q = s->seq[b];
-    if (!q.started) { ee_set_error("sequence %d has no context (call ee_prefill)", b); return EE_ERR_STATE; }
+    if (!q.started) continue;                         // an idle slot takes no part
     if (q.n_hd || !q.V.empty()) { ee_set_error("sequence %d has unverified tokens", b); return EE_ERR_STATE; }
     want[b] = (int)q.C.size() + n;
+    live++;
   }
+  if (!live) { ee_set_error("no sequence has a context (call ee_prefill)"); return EE_ERR_STATE; }
   EE_TRY(check_capacity(s, want));
   reset_accounting(s);
   CallPlan p;
-  p.m.assign(s->B, 1); p.p0.resize(s->B);
+  p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
   for (int b = 0; b < s->B; ++b) {
+    if (!s->seq[b].started) continue;
+    p.m[b] = 1;
     p.p0[b] = (int)s->seq[b].C.size() - 1;          // the pending token's position
     EE_TRY(grow_pages(s, b, want[b]));
   }
@@ -601,6 +616,7 @@ extern "C" int ee_decode_ar(ee_session* s, int n, int32_t* out) {
   EE_TRY(finish(s));
   for (int b = 0; b < s->B; ++b) {
     SeqState& q = s->seq[b];
+    if (!p.m[b]) { for (int j = 0; j < n; ++j) out[b * n + j] = -1; continue; }
     for (int j = 0; j < n; ++j) { out[b * n + j] = dh[b * s->max_rows + j]; q.C.push_back(dh[b * s->max_rows + j]); }
     q.len[0] = q.len[1] = q.len[2] = (int)q.C.size() - 1;
   }
@@ -612,15 +628,18 @@ extern "C" int ee_decode_ar(ee_session* s, int n, int32_t* out) {
 // ---------------------------------------------------------------------------------------------
 static int draft_precheck(ee_session* s, int k, int rows) {
   if (k < 1 || rows > s->max_rows) { ee_set_error("draft length %d does not fit max_rows %d", k, s->max_rows); return EE_ERR_ARG; }
-  std::vector<int> want(s->B);
+  std::vector<int> want(s->B, 0);
+  int live = 0;
   for (int b = 0; b < s->B; ++b) {
     const SeqState& q = s->seq[b];
-    if (!q.started) { ee_set_error("sequence %d has no context (call ee_prefill)", b); return EE_ERR_STATE; }
+    if (!q.started) continue;                         // an idle slot takes no part
+    live++;
     if (q.n_hd) { ee_set_error("sequence %d already has an unverified draft block", b); return EE_ERR_STATE; }
     int nT = (int)(q.C.size() + q.V.size());
     if ((int)q.V.size() + rows + 1 > s->max_rows) { ee_set_error("tentative buffer of sequence %d would overflow max_rows", b); return EE_ERR_CAPACITY; }
     want[b] = nT - 1 + rows + 1;   // one spare position for the pending token's later catch-up
   }
+  if (!live) { ee_set_error("no sequence has a context (call ee_prefill)"); return EE_ERR_STATE; }
   return check_capacity(s, want);
 }
 
@@ -643,9 +662,11 @@ static int draft_impl(ee_session* s, int k, int32_t* draft, const float* u) {
   reset_accounting(s);
   s->need_logits = u != nullptr;
   CallPlan p;
-  p.m.assign(s->B, 1); p.p0.resize(s->B);
+  p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
   for (int b = 0; b < s->B; ++b) {
     const SeqState& q = s->seq[b];
+    if (!q.started) continue;
+    p.m[b] = 1;
     p.p0[b] = (int)(q.C.size() + q.V.size()) - 1;
     EE_TRY(grow_pages(s, b, p.p0[b] + rows + 1));
   }
@@ -662,9 +683,9 @@ static int draft_impl(ee_session* s, int k, int32_t* draft, const float* u) {
     KF(KF_COPY, k_copy_rows(s->st, s->Hd, mt.row_dst, j, s->X, nullptr, p.M, c.d_model));
     if (j < k) {
       exit_head(s, p.M, 0);
-      if (u) {      // p_{L_d} of this position into the draft-distribution store, then the draw (row r = sequence r here)
+      if (u) {      // p_{L_d} of this position into the draft-distribution store, then the draw
         KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->Pd, mt.row_dst, j, p.M, c.vocab));
-        KF(KF_MISC, k_draw_rows(s->st, s->Pd, s->max_rows, j, c.vocab, s->u_dev, k, s->B, s->tok_next, s->draft_dev, s->max_rows));
+        KF(KF_MISC, k_draw_rows(s->st, s->Pd, s->max_rows, j, c.vocab, s->u_dev, k, mt.row_seq, p.M, s->tok_next, s->draft_dev, s->max_rows));
       } else {
         KF(KF_MISC, k_take_token(s->st, s->vtok, mt.row_seq, p.M, s->tok_next, s->draft_dev, s->max_rows, j));
       }
@@ -676,6 +697,7 @@ static int draft_impl(ee_session* s, int k, int32_t* draft, const float* u) {
   EE_TRY(finish(s));
   for (int b = 0; b < s->B; ++b) {
     SeqState& q = s->seq[b];
+    if (!p.m[b]) { for (int j = 0; j < k; ++j) draft[b * k + j] = -1; continue; }
     q.S.assign(dh + b * s->max_rows, dh + b * s->max_rows + k);
     q.n_hd = rows;
     q.sampled = u != nullptr;
@@ -698,12 +720,14 @@ extern "C" int ee_draft_inject(ee_session* s, int k, const int32_t* draft) {
   const int rows = k + (c.bonus_inter ? 1 : 0);
   EE_TRY(draft_precheck(s, k, rows));
   for (int i = 0; i < s->B * k; ++i)
-    if (draft[i] < 0 || draft[i] >= c.vocab) { ee_set_error("draft token out of range"); return EE_ERR_ARG; }
+    if (s->seq[i / k].started && (draft[i] < 0 || draft[i] >= c.vocab)) { ee_set_error("draft token out of range"); return EE_ERR_ARG; }
   reset_accounting(s);
   CallPlan p;
-  p.m.assign(s->B, rows); p.p0.resize(s->B);
+  p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
   for (int b = 0; b < s->B; ++b) {
     const SeqState& q = s->seq[b];
+    if (!q.started) continue;                         // an idle slot's entries of `draft` are ignored
+    p.m[b] = rows;
     p.p0[b] = (int)(q.C.size() + q.V.size()) - 1;
     EE_TRY(grow_pages(s, b, p.p0[b] + rows + 1));
   }
@@ -720,6 +744,7 @@ extern "C" int ee_draft_inject(ee_session* s, int k, const int32_t* draft) {
   HIP_TRY(hipGetLastError());
   for (int b = 0; b < s->B; ++b) {
     SeqState& q = s->seq[b];
+    if (!p.m[b]) continue;
     q.S.assign(draft + b * k, draft + b * k + k);
     q.n_hd = rows;
     q.sampled = false;

@@ -458,3 +458,86 @@ def test_sequence_restart_keeps_the_others():
     assert sess.lengths().tolist() == lens
     assert isinstance(sess.prefill_seq(0, synth.gen_prompt(cfg.vocab, 150, 3)), int)               # 3 pages fit
     sess.close(); model.close()
+
+
+def test_released_slot_idles_while_the_batch_goes_on():
+    """ee_seq_release: the pages go back to the pool, the slot takes no part in the batch-wide calls (which
+    report -1 for it), the other sequences verify exactly as the oracle says, and the
+    slot can be started again."""
+    cfg = bf16_small()
+    k, tol = 6, TOL["bf16"]
+    O, model, sess, first, gfirst = _setup(cfg, 31, [90, 40, 130], 3 * (k + 1) + 2)
+    rng = np.random.default_rng(12)
+    _round(O, sess, k, 0.7, rng, True, tol)
+    free0, held = sess.free_pages(), -(-(int(sess.lengths()[1].max()) + 1) // 64)
+    sess.release(1)
+    assert sess.free_pages() == free0 + held
+    assert sess.lengths()[1].tolist() == [0, 0, 0] and sess.tokens(1).tolist() == []
+    live, B = (0, 2), 3
+    for rnd in range(2):
+        drafts = np.full((B, k), -7, np.int32)               # the idle slot's entries are never read
+        for b in live:
+            s = O.seqs[b]
+            greedy = O.greedy(s, k, cfg.exit_inter)
+            for _ in range(25):
+                S = synth.make_draft_block(greedy, k, 0.7, cfg.vocab, rng, first_mismatch=synth.draw_first_mismatch(k, 0.7, rng))
+                if _trial_round(O, [s], [S], True) > MARGIN:
+                    break
+            else:
+                pytest.fail("no draft block cleared the margin filter")
+            drafts[b] = S
+        sess.draft_inject(drafts)
+        ga, gn = sess.verify_intermediate()
+        for b in range(B):
+            if b in live:
+                O.o.draft_inject(O.seqs[b], drafts[b])
+                assert (int(ga[b]), int(gn[b])) == O.o.verify_intermediate(O.seqs[b])
+            else:
+                assert (int(ga[b]), int(gn[b])) == (-1, -1)
+        gf, gn, gcom = sess.verify_full()
+        for b in range(B):
+            if b in live:
+                f, nxt, F = O.o.verify_full(O.seqs[b])
+                assert (int(gf[b]), int(gn[b]), gcom[b]) == (f, nxt, F)
+            else:
+                assert (int(gf[b]), int(gn[b]), list(gcom[b])) == (-1, -1, [])
+        lens = sess.lengths()
+        for b in live:
+            assert list(lens[b]) == O.seqs[b].len and sess.tokens(b).tolist() == O.seqs[b].T
+        assert lens[1].tolist() == [0, 0, 0]
+    # self-drafting and vanilla steps skip the idle slot as well
+    gS = sess.draft(2)
+    assert gS[1].tolist() == [-1, -1] and all(0 <= t < cfg.vocab for b in live for t in gS[b])
+    sess.verify_intermediate(); sess.verify_full()
+    before = sess.lengths().copy()
+    out = sess.decode_ar(2)
+    assert out[1].tolist() == [-1, -1] and sess.lengths()[1].tolist() == [0, 0, 0]
+    for b in live:
+        assert (sess.lengths()[b] == before[b].max() + 2).all()
+    # bring the oracle's live sequences to where the GPU now stands by replaying the GPU's committed streams
+    # through the oracle's own prefill (they are inputs from here on), then start the slot again
+    import paper_2510_01336_amd as hs
+    for b in live:
+        toks = sess.tokens(b).tolist()
+        s_new = eo.Sequence_(O.model.spec, O.seqs[b].cache.capacity)
+        O.o.prefill(s_new, toks[:-1])
+        s_new.C[-1] = toks[-1]
+        O.seqs[b] = s_new
+    for attempt in range(20):
+        prompt = synth.gen_prompt(cfg.vocab, 70, 500 + attempt)
+        s_new = eo.Sequence_(O.model.spec, O.seqs[0].cache.capacity)
+        f_new = O.o.prefill(s_new, prompt)
+        if eo.top2_margin(O.o.last_logits)[0] > MARGIN:
+            break
+    assert sess.prefill_seq(1, prompt) == f_new
+    O.seqs[1] = s_new
+    _check_state(O, sess)
+    _round(O, sess, k, 0.7, rng, True, tol)
+    # nothing started: the batch-wide calls say so
+    for b in range(B):
+        sess.release(b)
+    with pytest.raises(hs.EEError):
+        sess.draft(2)
+    with pytest.raises(hs.EEError):
+        sess.decode_ar(1)
+    sess.close(); model.close()
