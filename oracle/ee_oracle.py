@@ -141,13 +141,20 @@ class ModelSpec:
     rms_eps: float
     round_mode: str = "none"
     head_rank: int = 0       # > 0: low-rank adapters in front of the shared head at L_d and L_i (App. I)
+    exit_extra: Tuple[int, ...] = ()   # further intermediate verifiers L_{i,2} < L_{i,3} < ... (the paper's Future Work)
 
     @classmethod
     def from_config(cls, cfg, round_mode: Optional[str] = None) -> "ModelSpec":
         rm = round_mode if round_mode is not None else ("bf16" if getattr(cfg, "dtype", "f32") == "bf16" else "none")
         return cls(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
                    cfg.d_ffn, cfg.vocab, cfg.exit_draft, cfg.exit_inter,
-                   float(cfg.rope_theta), float(cfg.rms_eps), rm, int(getattr(cfg, "head_rank", 0)))
+                   float(cfg.rope_theta), float(cfg.rms_eps), rm, int(getattr(cfg, "head_rank", 0)),
+                   tuple(int(e) for e in getattr(cfg, "exit_extra", ())))
+
+    @property
+    def exits(self) -> Tuple[int, ...]:
+        """L_d < L_{i,1} < L_{i,2} < ... < L_f."""
+        return (self.exit_draft, self.exit_inter) + tuple(self.exit_extra) + (self.n_layers,)
 
     def exit_index(self, exit_layer: int) -> int:
         """0 for L_d, 1 for L_i, 2 for any other depth (the shared head alone)."""
@@ -551,6 +558,160 @@ class HiSpecOracle:
             f, nxt, F = self.verify_full(seq)
             if log is not None:
                 log.append(("full", f, nxt, list(F)))
+        return seq.C[seq.prompt_len:seq.prompt_len + n_new]
+
+
+# ----------------------------------------------------------------------------
+# several intermediate verifiers
+# ----------------------------------------------------------------------------
+
+class MultiSequence:
+    """One sequence under a hierarchy of verifiers at the exits e_0 = L_d < e_1 < ... < e_n = L_f.
+
+    V[j] (j = 1..n-1) holds the tokens accepted at exit e_j that still wait for exit e_{j+1}; the
+    text so far is  T = C || V[n-1] || ... || V[1],  deepest verdict first.  H[j] holds, for buffer
+    V[j], the e_j hidden rows of the tokens [the token just before V[j], V[j][0], ..., V[j][-2]]:
+    row r is the state that predicts V[j][r] one level up.  H[0] are the draft block's L_d rows.
+    len[g] is the KV length of layer group g (layers e_{g-1}..e_g, e_{-1} = 0)."""
+
+    def __init__(self, spec: ModelSpec, capacity: int):
+        n = len(spec.exits) - 1
+        self.n = n
+        self.cache = KVCache(spec, capacity)
+        self.C: List[int] = []
+        self.V: List[List[int]] = [[] for _ in range(n)]         # V[0] unused
+        self.S: List[int] = []
+        self.H: List[List[np.ndarray]] = [[] for _ in range(n)]
+        self.len = [0] * (n + 1)
+        self.prompt_len = 0
+
+    @property
+    def T(self) -> List[int]:
+        out = list(self.C)
+        for j in range(self.n - 1, 0, -1):
+            out += self.V[j]
+        return out
+
+
+class MultiLevelOracle:
+    """Alg. 2 with the single intermediate verifier replaced by a chain of them (the extension the
+    paper's Future Work section sketches; with exits (L_d, L_i, L_f) it is Alg. 2 itself).
+
+    Level 1 checks a draft block S exactly as L_i does in Alg. 2.  Level j >= 2 treats the buffer
+    V[j-1] as its draft: the buffered e_{j-1} rows, plus one row for the buffer's last token (which
+    has no state yet: it runs through the groups below first), pass through layer group j, and
+    LeadingSubstringVerify against exit e_j's arg max keeps the matching prefix and e_j's own next
+    token.  What is kept moves to V[j] (to C at the last level); everything below is dropped and
+    the KV lengths of the groups up to j are pruned to the kept prefix (Sec. 3.2).  A level runs
+    only when every buffer below the one it checks is empty."""
+
+    def __init__(self, model: EEModel):
+        self.m, self.spec = model, model.spec
+        self.exits = model.spec.exits
+        self.n = len(self.exits) - 1
+        self.last_logits: Optional[np.ndarray] = None
+
+    def group(self, g: int) -> range:
+        return range(self.exits[g - 1] if g else 0, self.exits[g])
+
+    def _head(self, x: np.ndarray, level: int) -> np.ndarray:
+        return self.m.exit_logits(x, level if level < 2 else 2)
+
+    def prefill(self, seq: MultiSequence, prompt: Sequence[int]) -> int:
+        t = len(prompt)
+        x = self.m.run_layers(range(self.spec.n_layers), self.m.embed(prompt), np.arange(t), seq.cache)
+        self.last_logits = self.m.exit_logits(x[-1:])
+        c0 = int(argmax_rows(self.last_logits)[0])
+        seq.C = [int(p) for p in prompt] + [c0]
+        seq.len = [t] * (self.n + 1)
+        seq.prompt_len = t
+        return c0
+
+    def _draft_rows(self, seq: MultiSequence, tokens: Sequence[int]) -> None:
+        p0 = len(seq.T) - 1
+        x = self.m.run_layers(self.group(0), self.m.embed(tokens), p0 + np.arange(len(tokens)), seq.cache)
+        seq.H[0] = [r for r in x]
+        seq.len[0] = p0 + len(tokens)
+
+    def draft_inject(self, seq: MultiSequence, S: Sequence[int]) -> None:
+        """A given draft block: the pending token and S through the draft layers in one pass."""
+        assert not seq.S and not seq.H[0]
+        seq.S = [int(t) for t in S]
+        self._draft_rows(seq, [seq.T[-1]] + seq.S)
+
+    def draft(self, seq: MultiSequence, k: int) -> List[int]:
+        """Generate(L_d, T, k): k sequential shallow passes, then the last draft token's own row."""
+        assert not seq.S and not seq.H[0]
+        p0 = len(seq.T) - 1
+        tok, rows, S = seq.T[-1], [], []
+        for j in range(k + 1):
+            x = self.m.run_layers(self.group(0), self.m.embed([tok]), np.array([p0 + j]), seq.cache)
+            rows.append(x[0])
+            if j < k:
+                tok = int(argmax_rows(self._head(x, 0))[0])
+                S.append(tok)
+        seq.S, seq.H[0], seq.len[0] = S, rows, p0 + k + 1
+        return S
+
+    def verify_level(self, seq: MultiSequence, j: int) -> Tuple[int, int, List[int]]:
+        """Returns (a, next token, the tokens that moved up: accepted prefix + next token)."""
+        n = self.n
+        assert 1 <= j <= n
+        src = seq.S if j == 1 else seq.V[j - 1]
+        assert src, "nothing to verify at this level"
+        assert j == 1 or (not seq.S and all(not seq.V[i] for i in range(1, j - 1)))
+        above = len(seq.C) + sum(len(seq.V[i]) for i in range(j, n))     # tokens already past level j
+        p0 = above - 1
+        rows = list(seq.H[j - 1])
+        if j >= 2:      # the buffer's last token has no state anywhere yet
+            p = p0 + len(src)
+            x = self.m.embed([src[-1]])
+            for g in range(j):
+                x = self.m.run_layers(self.group(g), x, np.array([p]), seq.cache)
+            rows.append(x[0])
+        assert len(rows) == len(src) + 1
+        Y = self.m.run_layers(self.group(j), np.stack(rows), p0 + np.arange(len(rows)), seq.cache)
+        self.last_logits = self._head(Y, j)
+        a, out = leading_substring_verify(src, argmax_rows(self.last_logits))
+        moved = [int(t) for t in out]                 # accepted prefix and the verifier's own next token
+        keep = len(moved)
+        if j == n:
+            seq.C += moved
+        else:
+            seq.V[j] += moved
+            seq.H[j] += [r for r in Y[:keep]]
+        seq.S = []
+        for i in range(j):
+            seq.H[i] = []
+            if i >= 1:
+                seq.V[i] = []
+        for g in range(j + 1):
+            seq.len[g] = p0 + keep
+        if j == n:
+            seq.len = [len(seq.C) - 1] * (n + 1)
+        return a, moved[-1], moved
+
+    def generate(self, prompt: Sequence[int], n_new: int, k: int, windows: Sequence[int],
+                 log: Optional[list] = None) -> List[int]:
+        """Decoding loop: draft + level 1 until |V[1]| >= windows[0]; then level 2, and so on up as long
+        as the buffer a level has just filled reaches its window (windows[j-1] for V[j]); a
+        generation that has enough tokens flushes every level in order."""
+        n = self.n
+        assert len(windows) == n - 1
+        seq = MultiSequence(self.spec, len(prompt) + n_new + (k + 2) * (sum(windows) + 4) + 8)
+        self.prefill(seq, prompt)
+        while len(seq.C) - seq.prompt_len < n_new:
+            flush = len(seq.T) - seq.prompt_len >= n_new + k + 2
+            self.draft(seq, k)
+            a, _, _ = self.verify_level(seq, 1)
+            if log is not None:
+                log.append((1, a))
+            for j in range(2, n + 1):
+                if not seq.V[j - 1] or not (flush or len(seq.V[j - 1]) >= windows[j - 2]):
+                    break
+                a, _, _ = self.verify_level(seq, j)
+                if log is not None:
+                    log.append((j, a))
         return seq.C[seq.prompt_len:seq.prompt_len + n_new]
 
 

@@ -67,6 +67,7 @@ class EEConfig:
     sigma: float = 0.02
     gamma: Tuple[float, float, float] = (1.0, 1.0, 1.0)
     head_rank: int = 0       # > 0: the exits L_d and L_i carry a low-rank adapter of this rank in front of the shared head
+    exit_extra: Tuple[int, ...] = ()   # further intermediate verifier exits between L_i and L_f (strictly increasing)
 
     def __post_init__(self):
         assert 0 < self.exit_draft < self.exit_inter < self.n_layers
@@ -74,6 +75,8 @@ class EEConfig:
         assert self.head_dim % 2 == 0
         assert self.dtype in ("f32", "bf16")
         assert self.head_rank >= 0 and (self.dtype == "f32" or self.head_rank % 32 == 0)
+        ex = (self.exit_inter,) + tuple(self.exit_extra) + (self.n_layers,)
+        assert len(self.exit_extra) <= 4 and all(a < b for a, b in zip(ex, ex[1:]))
 
     @property
     def exit_full(self) -> int:
