@@ -75,6 +75,9 @@ typedef struct ee_config {
                            z = h + B (A RMSNorm(h; g)), and feed z to the shared norm and head -- the
                            low-rank prediction heads of the post-training conversion (App. I).  The final
                            exit is unchanged.  EE_BF16 models need a multiple of 32.                       */
+  int32_t n_extra_exits;   /* 0..4 further intermediate verifiers L_{i,2} < L_{i,3} < ... between L_i and L_f
+                              (the hierarchy of the paper's Future Work section); 0 = Alg. 2 as printed       */
+  int32_t extra_exits[4];  /* their layers, strictly increasing, L_i < . < n_layers                          */
 } ee_config;
 
 typedef struct ee_model ee_model;
@@ -178,6 +181,21 @@ int ee_verify_intermediate(ee_session* s, int32_t* n_accept, int32_t* next_token
 int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
                    int32_t* committed, int32_t* n_committed);
 
+/* Several intermediate verifiers (the extension the paper's Future Work section sketches; models with
+ * n_extra_exits > 0).  The verifier exits after L_d are levels 1..n = ee_n_levels(): level 1 is L_i
+ * (ee_verify_intermediate), level n is L_f.  Level j in 2..n treats the tokens that exit j-1 accepted and that
+ * still wait for exit j as its draft block, exactly as L_i treats S in Alg. 2: their buffered hidden rows of
+ * exit j-1 (plus, in bonus_full mode, one row for the buffer's last token, run through the groups below first)
+ * pass through the layers between the two exits, LeadingSubstringVerify against exit j's arg max keeps the
+ * matching prefix and exit j's own next token, everything below is dropped and the KV lengths of the groups up
+ * to j are pruned to what was kept (Sec. 3.2).  The kept tokens wait for exit j+1; at level n they are committed
+ * and the call is ee_verify_full.  Every buffer below the one being checked must be empty (EE_ERR_STATE), so the
+ * levels run bottom-up: 1, then 2 when enough tokens wait there, and so on.  Arguments as ee_verify_full
+ * (`moved`: host [batch, max_rows+1], the kept tokens).  EE_ERR_ARG for a level outside 2..n; EE_ERR_CAPACITY when
+ * a level's buffer would exceed max_rows tokens. */
+int ee_verify_level(ee_session* s, int level, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
+                    int32_t* moved, int32_t* n_moved);
+
 /* In-place KV length rollback of one sequence (Sec. 3.2 "pruning"): keep `new_len` positions.
  * group_mask bit0 = G1, bit1 = G2, bit2 = G3.  G1 and G2 move together: T is cut to new_len+1
  * tokens (the last becomes pending), V / H_i follow; if the cut reaches committed tokens V is
@@ -214,7 +232,8 @@ int ee_verify_full_rs(ee_session* s, const uint8_t* active, const float* u_acc, 
 int ee_debug_read_dist(ee_session* s, int which, int seq, int row0, int n, float* host_out);
 
 /* ---- introspection (parity tests; not part of the timed path) ---------------------------- */
-int ee_get_lengths(const ee_session* s, int32_t* len_3_by_batch);           /* host [batch,3]      */
+int ee_get_lengths(const ee_session* s, int32_t* len_by_batch);   /* host [batch, ee_n_levels()+1]: KV length of every layer group (3 for Alg. 2) */
+int ee_n_levels(const ee_session* s);   /* verifier exits after L_d: 2 (L_i, L_f) plus the model's extra exits */
 int ee_get_counts(const ee_session* s, int32_t* n_committed, int32_t* n_tentative); /* [batch] each */
 int ee_get_tokens(const ee_session* s, int seq, int32_t* out, int cap, int32_t* n_out); /* T = C||V */
 /* When enabled, every exit-head call also stores full fp32 logits for its rows. */

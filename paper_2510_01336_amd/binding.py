@@ -15,7 +15,7 @@ __all__ = [
     "lib", "lib_path", "EEError", "ee_config", "make_config", "Model", "Session",
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_seq_release", "ee_free_pages", "ee_decode_ar", "ee_draft", "ee_draft_inject",
-    "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
+    "ee_verify_intermediate", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
@@ -30,7 +30,7 @@ TENSOR_IDS = {"emb": 0, "head": 1, "gfinal": 2, "g1": 3, "wq": 4, "wk": 5, "wv":
 EXPORTED_SYMBOLS = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_seq_release", "ee_free_pages", "ee_decode_ar", "ee_draft", "ee_draft_inject",
-    "ee_verify_intermediate", "ee_verify_full", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
+    "ee_verify_intermediate", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_stream_copy", "ee_last_error",
@@ -42,7 +42,7 @@ class ee_config(C.Structure):
                                          "exit_draft", "exit_inter")] + \
                [("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
                 ("bonus_inter", C.c_int32), ("bonus_full", C.c_int32), ("sigma", C.c_float), ("gamma", C.c_float * 3),
-                ("head_rank", C.c_int32)]
+                ("head_rank", C.c_int32), ("n_extra_exits", C.c_int32), ("extra_exits", C.c_int32 * 4)]
 
 
 class EEError(RuntimeError):
@@ -83,6 +83,8 @@ def _load():
         "ee_draft_inject": (C.c_int, [vp, C.c_int, i32p]),
         "ee_verify_intermediate": (C.c_int, [vp, i32p, i32p]),
         "ee_verify_full": (C.c_int, [vp, C.POINTER(C.c_uint8), i32p, i32p, i32p, i32p]),
+        "ee_verify_level": (C.c_int, [vp, C.c_int, C.POINTER(C.c_uint8), i32p, i32p, i32p, i32p]),
+        "ee_n_levels": (C.c_int, [vp]),
         "kv_rollback": (C.c_int, [vp, C.c_int, C.c_int, C.c_int]),
         "ee_sampling_bytes": (C.c_size_t, [vp]),
         "ee_sampling_attach": (C.c_int, [vp, vp, C.c_size_t]),
@@ -146,6 +148,10 @@ def make_config(cfg, bonus_inter: int = 1, bonus_full: int = 1) -> ee_config:
     for i, g in enumerate(getattr(cfg, "gamma", (1.0, 1.0, 1.0))):
         c.gamma[i] = float(g)
     c.head_rank = int(getattr(cfg, "head_rank", 0))
+    extra = tuple(getattr(cfg, "exit_extra", ()))
+    c.n_extra_exits = len(extra)
+    for i, e in enumerate(extra):
+        c.extra_exits[i] = int(e)
     return c
 
 
@@ -268,6 +274,21 @@ def ee_verify_full(session: int, batch: int, max_rows: int, active: Optional[Seq
     return a, n, [com[b, :nc[b]].tolist() for b in range(batch)]
 
 
+def ee_verify_level(session: int, level: int, batch: int, max_rows: int, active: Optional[Sequence[int]] = None):
+    a, n, nc = np.empty(batch, np.int32), np.empty(batch, np.int32), np.empty(batch, np.int32)
+    com = np.zeros((batch, max_rows + 1), np.int32)
+    act = None
+    if active is not None:
+        act_arr = np.ascontiguousarray(active, dtype=np.uint8)
+        act = act_arr.ctypes.data_as(C.POINTER(C.c_uint8))
+    _chk(lib.ee_verify_level(session, level, act, _p_i32(a), _p_i32(n), _p_i32(com), _p_i32(nc)))
+    return a, n, [com[b, :nc[b]].tolist() for b in range(batch)]
+
+
+def ee_n_levels(session: int) -> int:
+    return int(lib.ee_n_levels(session))
+
+
 def _f32c(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.float32)
 
@@ -319,7 +340,7 @@ def kv_rollback(session: int, seq: int, group_mask: int, new_len: int) -> None:
 
 
 def ee_get_lengths(session: int, batch: int) -> np.ndarray:
-    out = np.empty((batch, 3), np.int32)
+    out = np.empty((batch, ee_n_levels(session) + 1), np.int32)
     _chk(lib.ee_get_lengths(session, _p_i32(out)))
     return out
 
@@ -451,6 +472,12 @@ class Session:
 
     def verify_full(self, active=None):
         return ee_verify_full(self.handle, self.batch, self.max_rows, active)
+
+    def verify_level(self, level: int, active=None):
+        return ee_verify_level(self.handle, level, self.batch, self.max_rows, active)
+
+    def n_levels(self) -> int:
+        return ee_n_levels(self.handle)
 
     def enable_sampling(self) -> None:
         """Allocate and attach the buffers of the rejection-sampling calls."""

@@ -98,8 +98,10 @@ struct LayerLoc {
   MatLoc qkv, o, gu, down;   // gu: gate/up interleaved in 16-row tiles (gate tile j, up tile j, ...)
 };
 
+#define EE_MAX_GROUPS 7        // L_d, L_i, up to four further verifier exits, L_f: at most seven layer groups
 struct ee_model {
   ee_config cfg;
+  std::vector<int> exits;    // verifier exits in layers: L_d, L_i, the extra ones, L_f; group g = layers [exits[g-1], exits[g])
   char* base = nullptr;
   size_t bytes = 0;
   hipStream_t stream = nullptr;

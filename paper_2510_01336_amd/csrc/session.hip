@@ -5,9 +5,14 @@
 #include <algorithm>
 #include <cstring>
 
+// With further verifier exits (n levels > 2) C also holds the tokens that wait for the levels above L_i,
+// deepest verdict first: C = committed || V[n-1] || ... || V[2], where V[j] are the tokens accepted at exit j that
+// exit j+1 has not seen; cut[j] = |committed || V[n-1] || ... || V[j]|, so cut[n] tokens are committed and
+// cut[2] == |C| always.  V stays the buffer of L_i (level 1).  With the paper's three exits cut[2] = |C| is all there is.
 struct SeqState {
-  std::vector<int> C, V, S;   // committed, tentative, pending draft block
-  int len[3] = {0, 0, 0};     // KV length per layer group
+  std::vector<int> C, V, S;   // (see above), tentative at L_i, pending draft block
+  int cut[EE_MAX_GROUPS] = {0, 0, 0, 0, 0, 0, 0};
+  int len[EE_MAX_GROUPS] = {0, 0, 0, 0, 0, 0, 0};     // KV length per layer group
   int n_hd = 0;               // buffered L_d hidden rows (pending draft block incl. bonus row)
   int n_pi = 0;               // rejection sampling: tokens of V whose L_i distribution is stored
   bool sampled = false;       // the pending draft block was drawn from p_{L_d} (its distributions are stored)
@@ -33,6 +38,8 @@ struct ee_session {
   // device buffers (inside the caller's arena)
   void* kv = nullptr;
   float *X = nullptr, *QKV = nullptr, *GU = nullptr, *LOGITS = nullptr, *Hd = nullptr, *Hi = nullptr;
+  float* Hup[4] = {nullptr, nullptr, nullptr, nullptr};   // hidden rows buffered at the further verifier exits (levels 2..n-1)
+  int n_levels = 2;             // verifier levels: exits after L_d (2 = Alg. 2: L_i and L_f)
   void *XN = nullptr, *Qb = nullptr, *AO = nullptr, *H = nullptr;
   float2* cs = nullptr;
   int *vtok = nullptr, *tok_next = nullptr, *draft_dev = nullptr, *out_dev = nullptr, *page_scratch = nullptr;
@@ -123,6 +130,7 @@ static size_t carve(ee_session* s, char* base) {
   }
   s->Hd = cv.take<float>((size_t)s->B * s->max_rows * d);
   s->Hi = cv.take<float>((size_t)s->B * s->max_rows * d);
+  for (int j = 2; j < s->n_levels; ++j) s->Hup[j - 2] = cv.take<float>((size_t)s->B * s->max_rows * d);
   s->cs = cv.take<float2>((size_t)s->maxM * (D / 2));
   s->vtok = cv.take<int>(s->maxM);
   s->tok_next = cv.take<int>(s->maxM);
@@ -155,6 +163,7 @@ static int shape_session(ee_session* s, const ee_model* m, int batch, int max_ct
   if (!m->bf16 && max_ctx > 8192) { ee_set_error("EE_F32 sessions support max_ctx <= 8192"); return EE_ERR_ARG; }
   const int rep = m->cfg.n_q_heads / m->cfg.n_kv_heads;
   s->m = const_cast<ee_model*>(m);
+  s->n_levels = (int)m->exits.size() - 1;
   s->B = batch; s->max_ctx = max_ctx; s->max_rows = max_rows;
   s->pps = ceil_div(max_ctx, EE_PAGE);
   s->n_pages = total_pages > 0 ? total_pages : batch * s->pps;
@@ -236,10 +245,19 @@ static int grow_pages(ee_session* s, int b, int n) {
   }
   return EE_OK;
 }
+static int max_len(const ee_session* s, const SeqState& q) {
+  int m = 0;
+  for (int g = 0; g <= s->n_levels; ++g) m = std::max(m, q.len[g]);
+  return m;
+}
+// every group at the same length, nothing waiting above L_i: the state after a prompt, a vanilla step or the last level
+static void settle(const ee_session* s, SeqState& q) {
+  for (int g = 0; g <= s->n_levels; ++g) { q.len[g] = (int)q.C.size() - 1; q.cut[g] = (int)q.C.size(); }
+}
 // give back pages no group needs any more (Sec. 3.2 pruning: only the table tail changes)
 static void trim_pages(ee_session* s, int b) {
   SeqState& q = s->seq[b];
-  int keep = ceil_div(std::max(q.len[0], std::max(q.len[1], q.len[2])) + 1, EE_PAGE);
+  int keep = ceil_div(max_len(s, q) + 1, EE_PAGE);
   while ((int)q.pages.size() > keep) { s->free_pages.push_back(q.pages.back()); q.pages.pop_back(); }
 }
 static int check_capacity(ee_session* s, const std::vector<int>& want_positions) {
@@ -487,7 +505,7 @@ static int prefill_impl(ee_session* s, const int32_t* tokens, const int32_t* len
   size_t total = 0;
   for (int b = 0; b < s->B; ++b) {
     const SeqState& q = s->seq[b];
-    want[b] = lens[b] > 0 ? lens[b] + 1 : (q.started ? std::max(q.len[0], std::max(q.len[1], q.len[2])) : 0);
+    want[b] = lens[b] > 0 ? lens[b] + 1 : (q.started ? max_len(s, q) : 0);
     total += lens[b];
   }
   for (size_t i = 0; i < total; ++i)
@@ -540,7 +558,7 @@ static int prefill_impl(ee_session* s, const int32_t* tokens, const int32_t* len
     SeqState& q = s->seq[b];
     q.C.assign(tokens + off, tokens + off + lens[b]);
     q.C.push_back(s->out_host[b]);
-    q.len[0] = q.len[1] = q.len[2] = lens[b];
+    settle(s, q);
     q.started = true;
     first_token[b] = s->out_host[b];
     off += lens[b];
@@ -587,7 +605,7 @@ extern "C" int ee_decode_ar(ee_session* s, int n, int32_t* out) {
   for (int b = 0; b < s->B; ++b) {
     const SeqState& q = s->seq[b];
     if (!q.started) continue;                         // an idle slot takes no part
-    if (q.n_hd || !q.V.empty()) { ee_set_error("sequence %d has unverified tokens", b); return EE_ERR_STATE; }
+    if (q.n_hd || !q.V.empty() || q.cut[s->n_levels] != (int)q.C.size()) { ee_set_error("sequence %d has unverified tokens", b); return EE_ERR_STATE; }
     want[b] = (int)q.C.size() + n;
     live++;
   }
@@ -618,7 +636,7 @@ extern "C" int ee_decode_ar(ee_session* s, int n, int32_t* out) {
     SeqState& q = s->seq[b];
     if (!p.m[b]) { for (int j = 0; j < n; ++j) out[b * n + j] = -1; continue; }
     for (int j = 0; j < n; ++j) { out[b * n + j] = dh[b * s->max_rows + j]; q.C.push_back(dh[b * s->max_rows + j]); }
-    q.len[0] = q.len[1] = q.len[2] = (int)q.C.size() - 1;
+    settle(s, q);
   }
   return EE_OK;
 }
@@ -841,24 +859,45 @@ extern "C" int ee_verify_intermediate_rs(ee_session* s, const float* u_acc, int 
 }
 
 // ---------------------------------------------------------------------------------------------
-// C ABI: full verification at L_f
+// C ABI: verification at the levels above L_i -- full verification at L_f (Alg. 2) and, with further
+// verifier exits, the levels in between (the hierarchy of the paper's Future Work section)
 // ---------------------------------------------------------------------------------------------
-static int verify_full_impl(ee_session* s, const uint8_t* active, int32_t* n_accept, int32_t* next_token, int32_t* committed,
-                            int32_t* n_committed, const float* u_acc, int u_stride, const float* u_res) {
+static float* level_rows(const ee_session* s, int j) { return j == 0 ? s->Hd : (j == 1 ? s->Hi : s->Hup[j - 2]); }
+
+// Level j (2 <= j <= n) takes the buffer of level j-1 as its draft: V for j = 2, else the tail C[cut[j]..) (every
+// buffer below it must be empty).  The buffered rows of exit j-1 plus, in bonus mode, one row for the buffer's
+// last token (through the groups below first) run through layer group j; LeadingSubstringVerify keeps the
+// matching prefix and exit j's own next token.  What is kept joins level j's buffer (the committed tokens at
+// the last level); the KV lengths of the groups up to j are pruned to it.
+static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
+                             int32_t* committed, int32_t* n_committed, const float* u_acc, int u_stride, const float* u_res) {
   if (!s || !n_accept || !next_token || !committed || !n_committed) { ee_set_error("null argument"); return EE_ERR_ARG; }
   const ee_config& c = s->m->cfg;
+  const int n = s->n_levels, j = level;
+  if (j < 2 || j > n) { ee_set_error("level must be 2..%d", n); return EE_ERR_ARG; }
+  const std::vector<int>& ex = s->m->exits;
   const int bonus = c.bonus_full ? 1 : 0;
   const bool rs = u_acc != nullptr;
-  std::vector<int> act(s->B, 0);
+  if (rs && n != 2) { ee_set_error("the sampling calls support one intermediate verifier"); return EE_ERR_STATE; }
+  std::vector<int> act(s->B, 0), m_src(s->B, 0), base(s->B, 0);
   int any = 0;
   for (int b = 0; b < s->B; ++b) {
     const SeqState& q = s->seq[b];
     if (active && !active[b]) continue;
-    if (q.V.empty()) continue;
+    // base: tokens already past level j; m_src: tokens of the buffer below it
+    base[b] = j == 2 ? (int)q.C.size() : q.cut[j];
+    m_src[b] = j == 2 ? (int)q.V.size() : (int)q.C.size() - q.cut[j];
+    if (!q.started || m_src[b] == 0) continue;
     if (q.n_hd) { ee_set_error("sequence %d still has an unverified draft block", b); return EE_ERR_STATE; }
+    if (j > 2 && (!q.V.empty() || q.cut[j - 1] != (int)q.C.size())) {
+      ee_set_error("sequence %d: the buffers below level %d must be verified first", b, j - 1); return EE_ERR_STATE;
+    }
     if (rs && q.n_pi != (int)q.V.size()) {
       ee_set_error("sequence %d: the tentative tokens were not produced by the sampling calls", b);
       return EE_ERR_STATE;
+    }
+    if (j < n && (q.cut[j] - q.cut[j + 1]) + m_src[b] + bonus > s->max_rows) {
+      ee_set_error("level %d buffer of sequence %d would overflow max_rows", j, b); return EE_ERR_CAPACITY;
     }
     act[b] = 1; any++;
   }
@@ -869,49 +908,52 @@ static int verify_full_impl(ee_session* s, const uint8_t* active, int32_t* n_acc
     for (int b = 0; b < s->B; ++b) EE_TRY(upload_uniforms(s, u_acc + (size_t)b * u_stride, u_stride, (size_t)b * s->max_rows));
     EE_TRY(upload_uniforms(s, u_res, s->B, (size_t)s->B * s->max_rows));
   }
+  auto src_tok = [&](int b, int i) { const SeqState& q = s->seq[b]; return j == 2 ? q.V[i] : q.C[q.cut[j] + i]; };
+  float* rows_below = level_rows(s, j - 1);
   reset_accounting(s);
   if (bonus) {
-    // the pending token V[-1] owns no hidden state yet: one row per sequence through G1 and G2
+    // the buffer's last token owns no hidden state yet: one row per sequence through the groups below level j
     CallPlan p;
     p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
     for (int b = 0; b < s->B; ++b) {
       if (!act[b]) continue;
-      const SeqState& q = s->seq[b];
-      p.m[b] = 1; p.p0[b] = (int)(q.C.size() + q.V.size()) - 1;
+      p.m[b] = 1; p.p0[b] = base[b] + m_src[b] - 1;
       EE_TRY(grow_pages(s, b, p.p0[b] + 1));
     }
     EE_TRY(build_meta(s, 1, p, [&](int b, int, int& tok, int&, int& dst) {
-      tok = s->seq[b].V.back();
-      dst = b * s->max_rows + (int)s->seq[b].V.size();
+      tok = src_tok(b, m_src[b] - 1);
+      dst = b * s->max_rows + m_src[b];
     }));
     EE_TRY(upload_meta(s, 1));
     CallMeta mt = meta_ptrs(s, s->slot[1].d);
     KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
-    run_layers(s, 0, c.exit_inter, p, mt, 0);
-    KF(KF_COPY, k_copy_rows(s->st, s->Hi, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));
+    run_layers(s, 0, ex[j - 1], p, mt, 0);
+    KF(KF_COPY, k_copy_rows(s->st, rows_below, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));
   }
   CallPlan p;
   p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
   for (int b = 0; b < s->B; ++b) {
     if (!act[b]) continue;
-    const SeqState& q = s->seq[b];
-    p.m[b] = (int)q.V.size() + bonus; p.p0[b] = (int)q.C.size() - 1;
+    p.m[b] = m_src[b] + bonus; p.p0[b] = base[b] - 1;
   }
-  EE_TRY(build_meta(s, 0, p, [&](int b, int r, int&, int& src, int&) { src = b * s->max_rows + r; }));
+  EE_TRY(build_meta(s, 0, p, [&](int b, int r, int&, int& src, int& dst) {
+    src = b * s->max_rows + r;
+    dst = b * s->max_rows + (j < n ? s->seq[b].cut[j] - s->seq[b].cut[j + 1] : 0) + r;     // row of level j's own buffer
+  }));
   int* h = s->slot[0].h;
   for (int b = 0; b < s->B; ++b) {
     if (!act[b]) continue;
-    const SeqState& q = s->seq[b];
-    h[s->o_n_cand + b] = (int)q.V.size();
-    for (size_t j = 0; j < q.V.size(); ++j) h[s->o_cand + (size_t)b * s->cand_stride + j] = q.V[j];
+    h[s->o_n_cand + b] = m_src[b];
+    for (int i = 0; i < m_src[b]; ++i) h[s->o_cand + (size_t)b * s->cand_stride + i] = src_tok(b, i);
   }
   EE_TRY(upload_meta(s, 0));
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
-  KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, s->Hi, mt.row_src, p.M, c.d_model));       // consume buffered H_i
-  run_layers(s, c.exit_inter, c.n_layers, p, mt, 0);
+  KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, rows_below, mt.row_src, p.M, c.d_model));  // consume the buffered rows
+  run_layers(s, ex[j - 1], ex[j], p, mt, 0);
   s->need_logits = rs;
   exit_head(s, p.M, 2);
   s->need_logits = false;
+  if (j < n) KF(KF_COPY, k_copy_rows(s->st, level_rows(s, j), mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));   // keep exit j's rows
   if (rs) {      // second stage of App. G: V, distributed as p_{L_i}, is the draft; p_{L_f} the target
     KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->LOGITS, nullptr, 0, p.M, c.vocab));
     KF(KF_ACCEPT, k_rs_accept(s->st, s->LOGITS, s->Pi, s->max_rows, c.vocab, mt, s->cand_stride, s->B, s->u_dev, s->max_rows, s->out_dev));
@@ -929,13 +971,15 @@ static int verify_full_impl(ee_session* s, const uint8_t* active, int32_t* n_acc
     if (!act[b]) continue;
     const int f = n_accept[b];
     int32_t* out = committed + (size_t)b * (s->max_rows + 1);
-    int n = 0;
-    for (int j = 0; j < f; ++j) out[n++] = q.V[j];
-    if (f < p.m[b]) out[n++] = next_token[b];
-    n_committed[b] = n;
-    q.C.insert(q.C.end(), out, out + n);
+    int cnt = 0;
+    for (int i = 0; i < f; ++i) out[cnt++] = src_tok(b, i);
+    if (f < p.m[b]) out[cnt++] = next_token[b];
+    n_committed[b] = cnt;
+    if (j > 2) q.C.resize(q.cut[j]);
+    q.C.insert(q.C.end(), out, out + cnt);
     q.V.clear(); q.n_pi = 0;
-    q.len[0] = q.len[1] = q.len[2] = (int)q.C.size() - 1;
+    for (int g = 2; g <= j; ++g) q.cut[g] = (int)q.C.size();
+    for (int g = 0; g <= j; ++g) q.len[g] = (int)q.C.size() - 1;
     trim_pages(s, b);
   }
   return EE_OK;
@@ -943,13 +987,21 @@ static int verify_full_impl(ee_session* s, const uint8_t* active, int32_t* n_acc
 
 extern "C" int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
                               int32_t* committed, int32_t* n_committed) {
-  return verify_full_impl(s, active, n_accept, next_token, committed, n_committed, nullptr, 0, nullptr);
+  if (!s) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  return verify_upper_impl(s, s->n_levels, active, n_accept, next_token, committed, n_committed, nullptr, 0, nullptr);
 }
+
+extern "C" int ee_verify_level(ee_session* s, int level, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
+                               int32_t* moved, int32_t* n_moved) {
+  return verify_upper_impl(s, level, active, n_accept, next_token, moved, n_moved, nullptr, 0, nullptr);
+}
+
+extern "C" int ee_n_levels(const ee_session* s) { return s ? s->n_levels : -1; }
 
 extern "C" int ee_verify_full_rs(ee_session* s, const uint8_t* active, const float* u_acc, int u_stride, const float* u_res,
                                  int32_t* n_accept, int32_t* next_token, int32_t* committed, int32_t* n_committed) {
-  if (!u_acc || !u_res) { ee_set_error("null argument"); return EE_ERR_ARG; }
-  return verify_full_impl(s, active, n_accept, next_token, committed, n_committed, u_acc, u_stride, u_res);
+  if (!s || !u_acc || !u_res) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  return verify_upper_impl(s, s->n_levels, active, n_accept, next_token, committed, n_committed, u_acc, u_stride, u_res);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -977,11 +1029,13 @@ extern "C" int kv_rollback(ee_session* s, int seq, int group_mask, int new_len) 
   if (!s || seq < 0 || seq >= s->B) { ee_set_error("bad sequence index"); return EE_ERR_ARG; }
   SeqState& q = s->seq[seq];
   if (!q.started) { ee_set_error("sequence %d has no context", seq); return EE_ERR_STATE; }
+  const int n = s->n_levels;
   const int m12 = group_mask & 3;
   if (m12 != 0 && m12 != 3) { ee_set_error("G1 and G2 roll back together"); return EE_ERR_ARG; }
-  if (group_mask & ~7) { ee_set_error("bad group mask"); return EE_ERR_ARG; }
+  if (group_mask & ~((1 << (n + 1)) - 1)) { ee_set_error("bad group mask"); return EE_ERR_ARG; }
   if (m12 == 0) {
-    if ((group_mask & 4) && new_len != q.len[2]) { ee_set_error("G3 cannot roll back alone"); return EE_ERR_ARG; }
+    for (int g = 2; g <= n; ++g)
+      if ((group_mask & (1 << g)) && new_len != q.len[g]) { ee_set_error("the groups above G2 cannot roll back alone"); return EE_ERR_ARG; }
     q.n_hd = 0; q.S.clear(); q.sampled = false; q.len[0] = q.len[1];
     trim_pages(s, seq);
     return EE_OK;
@@ -989,9 +1043,12 @@ extern "C" int kv_rollback(ee_session* s, int seq, int group_mask, int new_len) 
   if (new_len < 0 || new_len > q.len[1]) { ee_set_error("rollback can only shrink (len %d -> %d)", q.len[1], new_len); return EE_ERR_ARG; }
   const int nT = new_len + 1;
   if (nT <= (int)q.C.size()) {
-    if (new_len < q.len[2] && !(group_mask & 4)) { ee_set_error("cut reaches committed tokens: G3 must roll back too"); return EE_ERR_ARG; }
+    for (int g = 2; g <= n; ++g)
+      if (new_len < q.len[g] && !(group_mask & (1 << g))) {
+        ee_set_error("cut reaches tokens that group %d has seen: it must roll back too", g + 1); return EE_ERR_ARG;
+      }
     q.C.resize(nT); q.V.clear();
-    q.len[2] = new_len;
+    for (int g = 2; g <= n; ++g) { q.len[g] = std::min(q.len[g], new_len); q.cut[g] = std::min(q.cut[g], nT); }
   } else {
     q.V.resize(nT - q.C.size());
   }
@@ -1007,12 +1064,16 @@ extern "C" int kv_rollback(ee_session* s, int seq, int group_mask, int new_len) 
 // ---------------------------------------------------------------------------------------------
 extern "C" int ee_get_lengths(const ee_session* s, int32_t* out) {
   if (!s || !out) { ee_set_error("null argument"); return EE_ERR_ARG; }
-  for (int b = 0; b < s->B; ++b) for (int g = 0; g < 3; ++g) out[b * 3 + g] = s->seq[b].len[g];
+  const int G = s->n_levels + 1;
+  for (int b = 0; b < s->B; ++b) for (int g = 0; g < G; ++g) out[b * G + g] = s->seq[b].len[g];
   return EE_OK;
 }
 extern "C" int ee_get_counts(const ee_session* s, int32_t* nc, int32_t* nv) {
   if (!s || !nc || !nv) { ee_set_error("null argument"); return EE_ERR_ARG; }
-  for (int b = 0; b < s->B; ++b) { nc[b] = (int)s->seq[b].C.size(); nv[b] = (int)s->seq[b].V.size(); }
+  for (int b = 0; b < s->B; ++b) {
+    const SeqState& q = s->seq[b];
+    nc[b] = q.cut[s->n_levels]; nv[b] = (int)(q.C.size() + q.V.size()) - nc[b];
+  }
   return EE_OK;
 }
 extern "C" int ee_get_tokens(const ee_session* s, int seq, int32_t* out, int cap, int32_t* n_out) {
@@ -1110,8 +1171,9 @@ extern "C" int ee_debug_poison_dead_kv(ee_session* s, int seq) {
   const ee_config& c = s->m->cfg;
   const SeqState& q = s->seq[seq];
   EE_TRY(upload_pages(s, seq));
-  const int bounds[4] = {0, c.exit_draft, c.exit_inter, c.n_layers};
-  for (int g = 0; g < 3; ++g)
+  std::vector<int> bounds = {0};
+  bounds.insert(bounds.end(), s->m->exits.begin(), s->m->exits.end());
+  for (int g = 0; g <= s->n_levels; ++g)
     k_fill_nan_dead_kv(s->st, s->m->bf16, s->kv, s->page_scratch, (int)q.pages.size(), q.len[g], bounds[g], bounds[g + 1],
                        s->n_pages, c.n_kv_heads, c.head_dim);
   HIP_TRY(hipGetLastError());

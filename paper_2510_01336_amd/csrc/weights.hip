@@ -38,6 +38,11 @@ static int check_config(const ee_config* c) {
   if (c->head_dim % 2 || c->head_dim > 256) { ee_set_error("head_dim must be even and <= 256"); return EE_ERR_ARG; }
   if (c->n_q_heads / c->n_kv_heads > 16) { ee_set_error("at most 16 query heads per KV head"); return EE_ERR_ARG; }
   if (!(c->rope_theta > 1.f) || !(c->rms_eps > 0.f)) { ee_set_error("bad rope_theta / rms_eps"); return EE_ERR_ARG; }
+  if (c->n_extra_exits < 0 || c->n_extra_exits > 4) { ee_set_error("0..4 extra verifier exits"); return EE_ERR_ARG; }
+  for (int i = 0, prev = c->exit_inter; i < c->n_extra_exits; prev = c->extra_exits[i++])
+    if (!(prev < c->extra_exits[i] && c->extra_exits[i] < c->n_layers)) {
+      ee_set_error("extra verifier exits must increase strictly between L_i and L_f"); return EE_ERR_ARG;
+    }
   if (c->head_rank < 0 || c->head_rank > 16384 || (c->dtype == EE_BF16 && c->head_rank % 32)) {
     ee_set_error("head_rank must be 0 or a rank up to 16384 (a multiple of 32 for EE_BF16 models)"); return EE_ERR_ARG;
   }
@@ -58,6 +63,9 @@ static MatLoc place(size_t& cur, int N, int K, bool bf16) {
 int ee_layout_model(ee_model* m) {
   const ee_config& c = m->cfg;
   m->bf16 = c.dtype == EE_BF16;
+  m->exits = {c.exit_draft, c.exit_inter};
+  for (int i = 0; i < c.n_extra_exits; ++i) m->exits.push_back(c.extra_exits[i]);
+  m->exits.push_back(c.n_layers);
   const size_t es = m->bf16 ? 2 : 4;
   const int d = c.d_model, D = c.head_dim;
   m->Fp = ceil_div(c.d_ffn, 16) * 16;

@@ -8,7 +8,7 @@ tokens (Sec. 3.4) or after a fixed number of intermediate rounds -- and collects
 from __future__ import annotations
 
 from dataclasses import dataclass, field
-from typing import List, Optional
+from typing import List, Optional, Sequence
 
 import numpy as np
 
@@ -93,6 +93,47 @@ def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, ever
             out[b].extend(int(t) for t in com[b])
             st.committed += len(com[b])
     return np.array([o[:n_new] for o in out], np.int32), st
+
+
+def hispec_generate_levels(sess, n_new: int, k: int, windows: Sequence[int]):
+    """The decoding loop over a chain of verifier exits (models with extra exits; ee_verify_level).
+
+    Every iteration drafts k tokens and checks them at level 1 (L_i).  A sequence then climbs: level j runs
+    for it when level j-1 has just run for it and the tokens waiting below level j number at least
+    windows[j-2] (the per-stage windows N_{i,1}, N_{i,2}, ... of the paper's Future Work section), or when the
+    sequence already holds enough tokens and is being flushed.  The last level commits.  Returns (tokens
+    [batch, n_new], {"calls", "checked", "accepted"}: per level, index 0 unused).
+    """
+    n = sess.n_levels()
+    assert len(windows) == n - 1 and all(w >= 1 for w in windows)
+    B = sess.batch
+    out: List[List[int]] = [[] for _ in range(B)]
+    stats = {"calls": [0] * (n + 1), "checked": [0] * (n + 1), "accepted": [0] * (n + 1)}
+    while min(len(o) for o in out) < n_new:
+        sess.draft(k)
+        a, _ = sess.verify_intermediate()
+        stats["calls"][1] += 1
+        stats["checked"][1] += B * k
+        stats["accepted"][1] += int(a.sum())
+        lens = sess.lengths()
+        flush = np.array([len(out[b]) + int(lens[b, 1] - lens[b, n]) >= n_new + k + 2 for b in range(B)])
+        ran = np.ones(B, bool)
+        for j in range(2, n + 1):
+            waiting = lens[:, j - 1] - lens[:, j]             # tokens accepted at level j-1 that level j has not seen
+            act = ran & (waiting > 0) & ((waiting >= windows[j - 2]) | flush)
+            if not act.any():
+                break
+            mask = act.astype(np.uint8)
+            f, _, moved = sess.verify_level(j, mask) if j < n else sess.verify_full(mask)
+            stats["calls"][j] += 1
+            stats["checked"][j] += int(waiting[act].sum())
+            stats["accepted"][j] += int(np.minimum(f, waiting)[act].sum())
+            if j == n:
+                for b in np.flatnonzero(act):
+                    out[b].extend(int(t) for t in moved[b])
+            ran = act
+            lens = sess.lengths()
+    return np.array([o[:n_new] for o in out], np.int32), stats
 
 
 def hispec_generate_sampling(sess, n_new: int, k: int, n_i: int, rng: np.random.Generator):
