@@ -55,6 +55,7 @@ WORKLOADS = {
     "8b_b1_ctx32768_k16_li8_r4": (lambda: synth.llama8b_config(exit_inter=8), [32768], 16, 0.9, 4),
     "8b_b1_ctx32768_k16_li24_r4": (lambda: synth.llama8b_config(exit_inter=24), [32768], 16, 0.9, 4),
     "8b_b1_ctx2048_k8_heads1024": (lambda: synth.llama8b_config(head_rank=1024), [2048], 8, 0.8),   # low-rank heads at L_d, L_i
+    "8b_b1_ctx2048_k8_chain24": (lambda: synth.llama8b_config(exit_extra=(24,)), [2048], 8, 0.8),   # second intermediate verifier at layer 24
     "70b_b4_ctx1024_k8": (synth.llama70b_config, [1024] * 4, 8, 0.75),
     "tiny_b1_ctx32_k4": (lambda: synth.tiny_config(gamma=(1.0, 0.3, 0.3)), [32], 4, 0.8),
     "8b_reduced_b1_ctx2048_k8": (lambda: synth.llama8b_config(n_layers=8, exit_draft=1, exit_inter=4), [2048], 8, 0.8),
@@ -146,10 +147,13 @@ def step_bytes(cfg, ctxs, k, rows_full, rounds=1):
     per_layer = ((Hq + 2 * Hkv) * D * d + d * Hq * D + 3 * F * d) * es
     head = cfg.vocab * d * es
     kv_layer = sum(ctxs) * 2 * Hkv * D * es
-    # rounds x (G1 + G2), G3, + catch-up row through G1+G2
-    layers = rounds * cfg.exit_inter + (cfg.n_layers - cfg.exit_inter) + (cfg.exit_inter if rows_full else 0)
+    # rounds x (G1 + G2); then every higher level: its own layer group + the catch-up row through the groups below
+    exits = (cfg.exit_inter,) + tuple(cfg.exit_extra) + (cfg.n_layers,)
+    layers = rounds * cfg.exit_inter
+    for lo, hi in zip(exits, exits[1:]):
+        layers += (hi - lo) + (lo if rows_full else 0)
     aux = 2 * cfg.head_rank * d * es           # the intermediate exit's low-rank adapter, once per round
-    return layers * (per_layer + kv_layer) + (rounds + 1) * head + rounds * aux
+    return layers * (per_layer + kv_layer) + (rounds + len(exits) - 1) * head + rounds * aux
 
 
 def build_workload(name, seed=MODEL_SEED):
@@ -179,14 +183,15 @@ def build_workload(name, seed=MODEL_SEED):
             a, nxt = sess.verify_intermediate()
             greedy[:, j] = np.where(a > j, S[:, j], nxt)      # (a random token may match by chance)
             for b in range(batch):
-                sess.rollback(b, 0b011 if r else 0b111, int(base[b]))
+                sess.rollback(b, 0b011 if r else (1 << (sess.n_levels() + 1)) - 1, int(base[b]))
         drafts = np.stack([synth.make_draft_block(greedy[b], k, p, cfg.vocab, rng) for b in range(batch)])
         blocks.append(drafts)
         if r + 1 < R:
             sess.draft_inject(drafts)
             sess.verify_intermediate()
+    all_groups = (1 << (sess.n_levels() + 1)) - 1
     for b in range(batch):
-        sess.rollback(b, 0b111, ctxs[b])
+        sess.rollback(b, all_groups, ctxs[b])
     return dict(cfg=cfg, model=model, sess=sess, batch=batch, ctxs=ctxs, k=k, p=p, drafts=blocks[0], blocks=blocks, rounds=R,
                 name=name)
 
@@ -207,12 +212,17 @@ def one_step(w, collect=None, wall=None):
             collect(sess.kernel_times(), "inter")
     a = a_sum
     t1 = time.perf_counter()
+    n = sess.n_levels()
+    for level in range(2, n):                 # models with further verifier exits: bottom-up, then L_f
+        sess.verify_level(level)
+        if collect is not None:
+            collect(sess.kernel_times(), "full")
     f, fn, com = sess.verify_full()
     t2 = time.perf_counter()
     if collect is not None:
         collect(sess.kernel_times(), "full")
     for b in range(w["batch"]):
-        sess.rollback(b, 0b111, w["ctxs"][b])
+        sess.rollback(b, (1 << (n + 1)) - 1, w["ctxs"][b])
     if wall is not None:
         wall.append((t1 - t0, t2 - t1))
     return a, f
@@ -350,7 +360,7 @@ def main():
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": w["batch"],
                    "kv_context": w["ctxs"][0] if w["batch"] == 1 else w["ctxs"], "k": w["k"],
-                   "draft_agreement_p": w["p"], "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers],
+                   "draft_agreement_p": w["p"], "exits": [cfg.exit_draft, cfg.exit_inter, *cfg.exit_extra, cfg.n_layers],
                    "intermediate_rounds_per_full_verification": w["rounds"],
                    "step": "rounds x [draft_inject(G1) + verify_intermediate(G2)] + verify_full(G1+G2 catch-up row, G3) + rollback",
                    "accepted_inter": [int(x) for x in a], "accepted_full": [int(x) for x in f]},
