@@ -80,7 +80,7 @@ def run_e2e(args):
     factory, ctx, k, n_i, n_new = E2E_WORKLOADS[args.workload]
     gamma = tuple(float(x) for x in args.gamma.split(","))
     cfg = factory(gamma)
-    model = hs.Model(cfg, MODEL_SEED)
+    model = hs.Model(cfg, MODEL_SEED, 1, args.bonus_full)
     rows = max(4 * (k + 1) + 2, 32)
     sess = hs.Session(model, 1, ctx + n_new + 2 * rows + 64, rows)
     prompt = [synth.gen_prompt(cfg.vocab, ctx, 7)]
@@ -121,7 +121,7 @@ def run_e2e(args):
         "n_gpus": 1, "steps": 1, "warmup": 1, "ms_per_step": 1e3 * t_hs, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": 1, "kv_context": ctx, "k": k, "n_i": n_i, "generated": n_new,
-                   "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers], "gamma": list(gamma),
+                   "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers], "gamma": list(gamma), "bonus_full": args.bonus_full,
                    "vanilla_tokens_per_s": n_new / t_ar, "speedup_vs_vanilla": t_ar / t_hs,
                    "rounds": st.rounds, "full_verifies": st.full_verifies,
                    "draft_accept_rate_at_L_i": st.accepted_inter / max(1, st.drafted),
@@ -296,6 +296,8 @@ def main():
     ap.add_argument("--workload", default="8b_b1_ctx2048_k8", choices=sorted(WORKLOADS) + sorted(E2E_WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gamma", default="1.0,0.02,0.01", help="e2e workloads: residual-branch damping of G1,G2,G3")
+    ap.add_argument("--bonus-full", type=int, default=0, choices=[0, 1],
+                    help="e2e workloads: 1 = the full verification also yields L_f's next token (one catch-up row through G1+G2), 0 = not")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
