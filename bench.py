@@ -80,7 +80,8 @@ def run_e2e(args):
     factory, ctx, k, n_i, n_new = E2E_WORKLOADS[args.workload]
     gamma = tuple(float(x) for x in args.gamma.split(","))
     cfg = factory(gamma)
-    model = hs.Model(cfg, MODEL_SEED, 1, args.bonus_full)
+    bonus_full = 0 if args.bonus_full is None else args.bonus_full
+    model = hs.Model(cfg, MODEL_SEED, 1, bonus_full)
     rows = max(4 * (k + 1) + 2, 32)
     sess = hs.Session(model, 1, ctx + n_new + 2 * rows + 64, rows)
     prompt = [synth.gen_prompt(cfg.vocab, ctx, 7)]
@@ -121,7 +122,7 @@ def run_e2e(args):
         "n_gpus": 1, "steps": 1, "warmup": 1, "ms_per_step": 1e3 * t_hs, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": 1, "kv_context": ctx, "k": k, "n_i": n_i, "generated": n_new,
-                   "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers], "gamma": list(gamma), "bonus_full": args.bonus_full,
+                   "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers], "gamma": list(gamma), "bonus_full": bonus_full,
                    "vanilla_tokens_per_s": n_new / t_ar, "speedup_vs_vanilla": t_ar / t_hs,
                    "rounds": st.rounds, "full_verifies": st.full_verifies,
                    "draft_accept_rate_at_L_i": st.accepted_inter / max(1, st.drafted),
@@ -156,14 +157,14 @@ def step_bytes(cfg, ctxs, k, rows_full, rounds=1):
     return layers * (per_layer + kv_layer) + (rounds + len(exits) - 1) * head + rounds * aux
 
 
-def build_workload(name, seed=MODEL_SEED):
+def build_workload(name, seed=MODEL_SEED, bonus_full=1):
     import paper_2510_01336_amd as hs
     factory, ctxs, k, p = WORKLOADS[name][:4]
     R = WORKLOADS[name][4] if len(WORKLOADS[name]) > 4 else 1
     ctxs = list(ctxs() if callable(ctxs) else ctxs)
     batch = len(ctxs)
     cfg = factory()
-    model = hs.Model(cfg, seed)
+    model = hs.Model(cfg, seed, 1, bonus_full)
     sess = hs.Session(model, batch, max(ctxs) + R * (k + 1) + 64, (R + 1) * (k + 1) + 2)
     prompts = [synth.gen_prompt(cfg.vocab, c, 7 + b) for b, c in enumerate(ctxs)]
     sess.prefill(prompts)
@@ -193,7 +194,7 @@ def build_workload(name, seed=MODEL_SEED):
     for b in range(batch):
         sess.rollback(b, all_groups, ctxs[b])
     return dict(cfg=cfg, model=model, sess=sess, batch=batch, ctxs=ctxs, k=k, p=p, drafts=blocks[0], blocks=blocks, rounds=R,
-                name=name)
+                name=name, bonus_full=bonus_full)
 
 
 def one_step(w, collect=None, wall=None):
@@ -296,8 +297,9 @@ def main():
     ap.add_argument("--workload", default="8b_b1_ctx2048_k8", choices=sorted(WORKLOADS) + sorted(E2E_WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gamma", default="1.0,0.02,0.01", help="e2e workloads: residual-branch damping of G1,G2,G3")
-    ap.add_argument("--bonus-full", type=int, default=0, choices=[0, 1],
-                    help="e2e workloads: 1 = the full verification also yields L_f's next token (one catch-up row through G1+G2), 0 = not")
+    ap.add_argument("--bonus-full", type=int, default=None, choices=[0, 1],
+                    help="1 = the full verification also yields L_f's next token (one catch-up row through G1+G2), 0 = not; "
+                         "default: 1 for the verify-step workloads (Alg. 2 as printed), 0 for the e2e loop (faster)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -309,7 +311,7 @@ def main():
     if args.workload in E2E_WORKLOADS:
         run_e2e(args)
         return
-    w = build_workload(args.workload)
+    w = build_workload(args.workload, bonus_full=1 if args.bonus_full is None else args.bonus_full)
     cfg, sess = w["cfg"], w["sess"]
     calibration_copy(w["model"].stream)
 
@@ -352,7 +354,7 @@ def main():
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": gu_bytes, "avg_launch_us": gu_avg_s * 1e6,
                 "launches": gu_n}
-    sb = step_bytes(cfg, w["ctxs"], w["k"], True, w["rounds"])
+    sb = step_bytes(cfg, w["ctxs"], w["k"], bool(w["bonus_full"]), w["rounds"])
     kernel_ms = {k2: round(v[0] / args.steps, 4) for k2, v in acc.items()}
 
     out = {
@@ -364,7 +366,9 @@ def main():
                    "kv_context": w["ctxs"][0] if w["batch"] == 1 else w["ctxs"], "k": w["k"],
                    "draft_agreement_p": w["p"], "exits": [cfg.exit_draft, cfg.exit_inter, *cfg.exit_extra, cfg.n_layers],
                    "intermediate_rounds_per_full_verification": w["rounds"],
-                   "step": "rounds x [draft_inject(G1) + verify_intermediate(G2)] + verify_full(G1+G2 catch-up row, G3) + rollback",
+                   "bonus_full": w["bonus_full"],
+                   "step": "rounds x [draft_inject(G1) + verify_intermediate(G2)] + verify_full("
+                           + ("G1+G2 catch-up row, " if w["bonus_full"] else "") + "G3) + rollback",
                    "accepted_inter": [int(x) for x in a], "accepted_full": [int(x) for x in f]},
         "roofline": roofline,
         "phase_ms_median": {"inject_plus_verify_intermediate": 1e3 * t_i, "verify_full": 1e3 * t_f},
