@@ -69,6 +69,7 @@ WORKLOADS = {
 E2E_WORKLOADS = {
     # name: (config factory, KV context, k, N_i, tokens generated)
     "e2e_8b_ctx2048_k8": (lambda g: synth.llama8b_config(gamma=g), 2048, 8, 12, 256),
+    "e2e_8b_ctx2048_k4": (lambda g: synth.llama8b_config(gamma=g), 2048, 4, 6, 256),     # the best point of the k / N_i sweep
     "e2e_8b_reduced_ctx512_k4": (lambda g: synth.llama8b_config(n_layers=8, exit_draft=1, exit_inter=4, gamma=g), 512, 4, 6, 64),
 }
 
@@ -78,6 +79,7 @@ def run_e2e(args):
     import paper_2510_01336_amd as hs
     from paper_2510_01336_amd.loop import hispec_generate
     factory, ctx, k, n_i, n_new = E2E_WORKLOADS[args.workload]
+    k, n_i = args.k or k, args.n_i or n_i
     gamma = tuple(float(x) for x in args.gamma.split(","))
     cfg = factory(gamma)
     bonus_full = 0 if args.bonus_full is None else args.bonus_full
@@ -297,6 +299,8 @@ def main():
     ap.add_argument("--workload", default="8b_b1_ctx2048_k8", choices=sorted(WORKLOADS) + sorted(E2E_WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gamma", default="1.0,0.02,0.01", help="e2e workloads: residual-branch damping of G1,G2,G3")
+    ap.add_argument("--k", type=int, default=0, help="e2e workloads: draft tokens per round (default: the workload's)")
+    ap.add_argument("--n-i", type=int, default=0, help="e2e workloads: tentative tokens that trigger the full verification")
     ap.add_argument("--bonus-full", type=int, default=None, choices=[0, 1],
                     help="1 = the full verification also yields L_f's next token (one catch-up row through G1+G2), 0 = not; "
                          "default: 1 for the verify-step workloads (Alg. 2 as printed), 0 for the e2e loop (faster)")
