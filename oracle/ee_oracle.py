@@ -691,6 +691,27 @@ class MultiLevelOracle:
             seq.len = [len(seq.C) - 1] * (n + 1)
         return a, moved[-1], moved
 
+    def rollback(self, seq: MultiSequence, new_len: int) -> None:
+        """Explicit prune to new_len positions in every group that is longer (Sec. 3.2: only lengths
+        change).  new_len + 1 tokens of T remain, the last of them pending again; a pending draft block is
+        dropped; every buffer keeps the tokens (and the hidden rows) that lie before the cut."""
+        n = self.n
+        assert 0 <= new_len <= seq.len[1]
+        keep = new_len + 1
+        room = keep
+        take = min(room, len(seq.C)); seq.C = seq.C[:take]; room -= take
+        for j in range(n - 1, 0, -1):
+            take = min(room, len(seq.V[j]))
+            seq.V[j] = seq.V[j][:take]
+            seq.H[j] = seq.H[j][:take]
+            room -= take
+        seq.S, seq.H[0] = [], []
+        seq.len[0] = seq.len[1] = new_len
+        for g in range(2, n + 1):
+            seq.len[g] = min(seq.len[g], new_len)
+        seq.cache.K[:, new_len:] = np.nan       # dead entries must never be read again
+        seq.cache.V[:, new_len:] = np.nan
+
     def generate(self, prompt: Sequence[int], n_new: int, k: int, windows: Sequence[int],
                  log: Optional[list] = None) -> List[int]:
         """Decoding loop: draft + level 1 until |V[1]| >= windows[0]; then level 2, and so on up as long

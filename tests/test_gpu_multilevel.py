@@ -35,6 +35,8 @@ PLANS = [
     ("bf16_4_levels", bf16_chain(), 8, [90, 33], 6, [[1, 2], [1], [1, 2, 3], [1, 2, 3, 4], [1, 2, 3, 4]]),
     # low-rank heads at L_d and L_i, the shared head at the exits above
     ("f32_3_levels_low_rank_heads", f32_chain(head_rank=24), 1, [40, 9], 4, [[1], [1, 2], [1, 2, 3], [1, 2, 3]]),
+    # an explicit prune through the buffers in the middle, then on
+    ("f32_3_levels_rollback", f32_chain(), 1, [40, 9], 4, [[1, 2], [1, 2], [1], "cut", [1, 2], [1, 2, 3], "cut", [1, 2, 3]]),
 ]
 
 
@@ -72,6 +74,21 @@ def run_plan(cfg, seed, ctx, k, plan, sess=None, p=0.7):
         return w
 
     for levels in plan:
+        if levels == "cut":
+            # prune one token short of the end of the level-2 buffer (of the committed tokens if it is empty):
+            # the level-1 buffer goes, deeper state stays; all groups roll back together
+            for b, s in enumerate(seqs):
+                keep = len(s.C) + (max(1, len(s.V[2]) - 1) if s.V[2] else -1)
+                M.rollback(s, keep - 1)
+                if sess is not None:
+                    sess.rollback(b, (1 << (n + 1)) - 1, keep - 1)
+            if sess is not None:
+                lens = sess.lengths()
+                nc, nv = sess.counts()
+                for b, s in enumerate(seqs):
+                    assert list(lens[b]) == s.len and sess.tokens(b).tolist() == s.T
+                    assert (nc[b], nv[b]) == (len(s.C), len(s.T) - len(s.C))
+            continue
         drafts = []
         for s in seqs:
             greedy = eo.ar_generate(model, s.T, k, cfg.exit_inter)

@@ -117,3 +117,63 @@ def test_a_deeper_verifier_rejects_what_a_shallower_one_let_through():
     want = next((i for i in range(6) if e1[i] != e2[i]), 6)
     a2, nxt2, moved = M.verify_level(seq, 2)
     assert (a2, nxt2) == (want, e2[want]) and seq.V[2] == e2[:want + 1] == moved and not seq.V[1]
+
+
+def _check_against_recomputation(m, M, seq):
+    n, T = M.n, seq.T
+    assert seq.len[0] == seq.len[1] == len(T) - 1
+    for g in range(2, n + 1):
+        assert seq.len[g] == len(seq.C) + sum(len(seq.V[i]) for i in range(g, n)) - 1
+    scratch = eo.KVCache(m.spec, len(T))
+    x = m.embed(T)
+    for g in range(n + 1):
+        x = m.run_layers(M.group(g), x, np.arange(len(T)), scratch)
+        L = seq.len[g]
+        for l in M.group(g):
+            np.testing.assert_allclose(seq.cache.K[l, :L], scratch.K[l, :L], rtol=1e-9, atol=1e-11)
+        if 1 <= g < n and seq.V[g]:
+            first = len(seq.C) + sum(len(seq.V[i]) for i in range(g + 1, n)) - 1
+            np.testing.assert_allclose(np.stack(seq.H[g]), x[first:first + len(seq.V[g])], rtol=1e-9, atol=1e-11)
+
+
+@pytest.mark.parametrize("cut_in", ["V1", "V2", "C"])
+def test_rollback_through_the_buffers_then_continue(cut_in):
+    """A prune that ends inside the level-1 buffer, inside the level-2 buffer or inside the committed tokens
+    leaves a state that a recomputation from scratch confirms, and decoding from it is still lossless."""
+    cfg = _cfg(exit_draft=1, exit_inter=3, exit_extra=(5,))
+    m = _model(cfg)
+    M = eo.MultiLevelOracle(m)
+    seq = eo.MultiSequence(m.spec, 200)
+    prompt = synth.gen_prompt(cfg.vocab, 12, 5)
+    M.prefill(seq, prompt)
+    rng = np.random.default_rng(3)
+    for lv in [1, 2, 1, 2, 3, 1, 2, 1, 2, 1]:           # ends with tokens in C, V[2] and V[1]
+        if lv == 1:
+            greedy = eo.ar_generate(m, seq.T, 3, cfg.exit_inter)
+            M.draft_inject(seq, synth.make_draft_block(greedy, 3, 0.8, cfg.vocab, rng))
+        M.verify_level(seq, lv)
+    assert seq.V[1] and seq.V[2] and len(seq.C) > len(prompt) + 1
+    M.draft_inject(seq, [1, 2, 3])                        # a pending block is dropped by the prune as well
+    nC, n2, n1 = len(seq.C), len(seq.V[2]), len(seq.V[1])
+    keep = {"V1": nC + n2 + max(1, n1 - 1), "V2": nC + max(1, n2 - 1), "C": nC - 1}[cut_in]
+    before = seq.T[:keep]
+    M.rollback(seq, keep - 1)
+    assert seq.T == before and not seq.S
+    if cut_in == "C":
+        assert not seq.V[1] and not seq.V[2] and seq.len == [keep - 1] * 4
+    elif cut_in == "V2":
+        assert not seq.V[1] and len(seq.V[2]) == max(1, n2 - 1)
+    _check_against_recomputation(m, M, seq)
+    # go on: bottom-up through whatever still waits, then a few more rounds; the committed stream stays the AR stream
+    for rnd in range(6):
+        M.draft(seq, 3)
+        M.verify_level(seq, 1)
+        M.verify_level(seq, 2)
+        if rnd % 2:
+            M.verify_level(seq, 3)
+    M.draft(seq, 2); M.verify_level(seq, 1); M.verify_level(seq, 2); M.verify_level(seq, 3)
+    # the committed tokens that survived the cut stay; what follows them is the full model's greedy continuation
+    surv = before[:min(nC, keep)]
+    assert seq.C[:len(surv)] == surv
+    assert seq.C[len(surv):] == eo.ar_generate(m, surv, len(seq.C) - len(surv))
+    _check_against_recomputation(m, M, seq)
