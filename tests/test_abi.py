@@ -64,3 +64,27 @@ def test_config_checks_need_no_device(lib):
     # null / misaligned arenas are refused before any device work
     out = ctypes.c_void_p()
     assert lib.ee_model_load(ctypes.byref(good), None, 0, 0, None, ctypes.byref(out)) == -1
+
+
+def test_config_checks_of_the_optional_model_parts(lib):
+    """Low-rank exit heads (App. I) and further verifier exits: shape rules and their cost in bytes, no device."""
+    import paper_2510_01336_amd as hs
+    import synth
+    lib.ee_model_bytes.restype = ctypes.c_size_t
+    lib.ee_last_error.restype = ctypes.c_char_p
+    plain = lib.ee_model_bytes(ctypes.byref(hs.make_config(synth.llama8b_config())))
+    heads = lib.ee_model_bytes(ctypes.byref(hs.make_config(synth.llama8b_config(head_rank=1024))))
+    # two exits x (A: 1024 x 4096, B: 4096 x 1024) in bf16 = 33.6 MB plus gains and alignment: under 2 % of the model
+    assert 2 * 2 * 2 * 1024 * 4096 <= heads - plain <= 2 * 2 * 2 * 1024 * 4096 + 65536
+    bad = hs.make_config(synth.llama8b_config())
+    bad.head_rank = 40                                   # bf16 models need a multiple of 32
+    assert lib.ee_model_bytes(ctypes.byref(bad)) == 0 and b"head_rank" in lib.ee_last_error()
+    chain = hs.make_config(synth.llama8b_config(exit_extra=(20, 24)))
+    assert (chain.n_extra_exits, list(chain.extra_exits)[:2]) == (2, [20, 24])
+    assert lib.ee_model_bytes(ctypes.byref(chain)) == plain     # exits add no weights
+    for extra in ((16,), (24, 20), (32,)):               # not above L_i, not increasing, not below L_f
+        bad = hs.make_config(synth.llama8b_config())
+        bad.n_extra_exits = len(extra)
+        for i, e in enumerate(extra):
+            bad.extra_exits[i] = e
+        assert lib.ee_model_bytes(ctypes.byref(bad)) == 0 and b"verifier exits" in lib.ee_last_error()
