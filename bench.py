@@ -70,6 +70,7 @@ E2E_WORKLOADS = {
     # name: (config factory, KV context, k, N_i, tokens generated)
     "e2e_8b_ctx2048_k8": (lambda g: synth.llama8b_config(gamma=g), 2048, 8, 12, 256),
     "e2e_8b_ctx2048_k4": (lambda g: synth.llama8b_config(gamma=g), 2048, 4, 6, 256),     # the best point of the k / N_i sweep
+    "e2e_8b_b8_ctx1024_k4": (lambda g: synth.llama8b_config(gamma=g), 1024, 4, 6, 128, 8),   # eight sequences decoded together
     "e2e_8b_reduced_ctx512_k4": (lambda g: synth.llama8b_config(n_layers=8, exit_draft=1, exit_inter=4, gamma=g), 512, 4, 6, 64),
 }
 
@@ -78,15 +79,16 @@ def run_e2e(args):
     import torch
     import paper_2510_01336_amd as hs
     from paper_2510_01336_amd.loop import hispec_generate
-    factory, ctx, k, n_i, n_new = E2E_WORKLOADS[args.workload]
+    factory, ctx, k, n_i, n_new = E2E_WORKLOADS[args.workload][:5]
+    B = E2E_WORKLOADS[args.workload][5] if len(E2E_WORKLOADS[args.workload]) > 5 else 1
     k, n_i = args.k or k, args.n_i or n_i
     gamma = tuple(float(x) for x in args.gamma.split(","))
     cfg = factory(gamma)
     bonus_full = 0 if args.bonus_full is None else args.bonus_full
     model = hs.Model(cfg, MODEL_SEED, 1, bonus_full)
     rows = max(4 * (k + 1) + 2, 32)
-    sess = hs.Session(model, 1, ctx + n_new + 2 * rows + 64, rows)
-    prompt = [synth.gen_prompt(cfg.vocab, ctx, 7)]
+    sess = hs.Session(model, B, ctx + n_new + 2 * rows + 64, rows)
+    prompt = [synth.gen_prompt(cfg.vocab, ctx, 7 + b) for b in range(B)]
     first = sess.prefill(prompt)
     hispec_generate(sess, 2 * k, k, n_i=n_i)                      # warm-up
     sess.prefill(prompt)
@@ -111,21 +113,22 @@ def run_e2e(args):
     sess.prefill(prompt)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ar = []
-    while len(ar) < n_new:
-        ar.extend(int(t) for t in sess.decode_ar(min(32, n_new - len(ar)))[0])
+    ar = np.zeros((B, 0), np.int32)
+    while ar.shape[1] < n_new:
+        ar = np.concatenate([ar, sess.decode_ar(min(32, n_new - ar.shape[1]))], axis=1)
     torch.cuda.synchronize()
     t_ar = time.perf_counter() - t0
-    same = 0
-    while same < n_new and int(toks[0][same]) == ar[same]:
-        same += 1
+    same = n_new                              # leading tokens equal to the vanilla stream, the worst sequence
+    for b in range(B):
+        diff = np.flatnonzero(np.asarray(toks[b]) != ar[b])
+        same = min(same, int(diff[0]) if len(diff) else n_new)
     out = {
-        "metric": "generated tokens/sec per GPU (hierarchical speculative decoding loop)", "value": n_new / t_hs, "unit": "tokens/s",
+        "metric": "generated tokens/sec per GPU (hierarchical speculative decoding loop)", "value": B * n_new / t_hs, "unit": "tokens/s",
         "n_gpus": 1, "steps": 1, "warmup": 1, "ms_per_step": 1e3 * t_hs, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "batch": 1, "kv_context": ctx, "k": k, "n_i": n_i, "generated": n_new,
+        "config": {"workload": args.workload, "batch": B, "kv_context": ctx, "k": k, "n_i": n_i, "generated": n_new,
                    "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers], "gamma": list(gamma), "bonus_full": bonus_full,
-                   "vanilla_tokens_per_s": n_new / t_ar, "speedup_vs_vanilla": t_ar / t_hs,
+                   "vanilla_tokens_per_s": B * n_new / t_ar, "speedup_vs_vanilla": t_ar / t_hs,
                    "rounds": st.rounds, "full_verifies": st.full_verifies,
                    "draft_accept_rate_at_L_i": st.accepted_inter / max(1, st.drafted),
                    "tentative_accept_rate_at_L_f": st.accepted_full / max(1, st.tentative),
@@ -133,7 +136,7 @@ def run_e2e(args):
                    "reject_rate_at_L_i": 1.0 - st.accepted_inter / max(1, st.drafted),
                    "false_accept_rate": (st.tentative - st.accepted_full) / max(1, st.drafted),
                    "leading_tokens_equal_to_vanilla_stream": same,
-                   "rejection_sampling": {"tokens_per_s": n_new / t_rs, "speedup_vs_vanilla": t_ar / t_rs,
+                   "rejection_sampling": {"tokens_per_s": B * n_new / t_rs, "speedup_vs_vanilla": t_ar / t_rs,
                                           "draft_accept_rate_at_L_i": st_rs.accepted_inter / max(1, st_rs.drafted),
                                           "tentative_accept_rate_at_L_f": st_rs.accepted_full / max(1, st_rs.tentative),
                                           "tokens_per_round": st_rs.committed / max(1, st_rs.rounds)}},
