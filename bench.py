@@ -70,7 +70,7 @@ E2E_WORKLOADS = {
     # name: (config factory, KV context, k, N_i, tokens generated)
     "e2e_8b_ctx2048_k8": (lambda g: synth.llama8b_config(gamma=g), 2048, 8, 12, 256),
     "e2e_8b_ctx2048_k4": (lambda g: synth.llama8b_config(gamma=g), 2048, 4, 6, 256),     # the best point of the k / N_i sweep
-    "e2e_8b_b8_ctx1024_k4": (lambda g: synth.llama8b_config(gamma=g), 1024, 4, 6, 128, 8),   # eight sequences decoded together
+    "e2e_8b_b8_ctx1024_k4": (lambda g: synth.llama8b_config(gamma=g), 1024, 4, 4, 128, 8),   # eight sequences decoded together
     "e2e_8b_reduced_ctx512_k4": (lambda g: synth.llama8b_config(n_layers=8, exit_draft=1, exit_inter=4, gamma=g), 512, 4, 6, 64),
 }
 
@@ -94,7 +94,7 @@ def run_e2e(args):
     sess.prefill(prompt)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    toks, st = hispec_generate(sess, n_new, k, n_i=n_i)
+    toks, st = hispec_generate(sess, n_new, k, n_i=n_i, trigger=args.trigger)
     torch.cuda.synchronize()
     t_hs = time.perf_counter() - t0
     # the same loop under the rejection-sampling acceptance of App. G (full distributions at all three exits)
@@ -127,7 +127,7 @@ def run_e2e(args):
         "n_gpus": 1, "steps": 1, "warmup": 1, "ms_per_step": 1e3 * t_hs, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "kv_context": ctx, "k": k, "n_i": n_i, "generated": n_new,
-                   "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers], "gamma": list(gamma), "bonus_full": bonus_full,
+                   "exits": [cfg.exit_draft, cfg.exit_inter, cfg.n_layers], "gamma": list(gamma), "bonus_full": bonus_full, "trigger": args.trigger,
                    "vanilla_tokens_per_s": B * n_new / t_ar, "speedup_vs_vanilla": t_ar / t_hs,
                    "rounds": st.rounds, "full_verifies": st.full_verifies,
                    "draft_accept_rate_at_L_i": st.accepted_inter / max(1, st.drafted),
@@ -302,6 +302,8 @@ def main():
     ap.add_argument("--workload", default="8b_b1_ctx2048_k8", choices=sorted(WORKLOADS) + sorted(E2E_WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gamma", default="1.0,0.02,0.01", help="e2e workloads: residual-branch damping of G1,G2,G3")
+    ap.add_argument("--trigger", default="any", choices=["all", "any"],
+                    help="e2e workloads with a batch: full verification when all / any of the sequences hold N_i tentative tokens")
     ap.add_argument("--k", type=int, default=0, help="e2e workloads: draft tokens per round (default: the workload's)")
     ap.add_argument("--n-i", type=int, default=0, help="e2e workloads: tentative tokens that trigger the full verification")
     ap.add_argument("--bonus-full", type=int, default=None, choices=[0, 1],

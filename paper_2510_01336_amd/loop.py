@@ -49,10 +49,10 @@ class AdaptivePolicy:
 
 
 def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, every: Optional[int] = None,
-                    adaptive: Optional[AdaptivePolicy] = None):
+                    adaptive: Optional[AdaptivePolicy] = None, trigger: str = "all"):
     """Generate n_new tokens per sequence after the session's current context (ee_prefill done, nothing pending).
 
-    Exactly one of n_i (fire the full verification when every sequence's tentative buffer holds >= n_i
+    Exactly one of n_i (fire the full verification when every sequence's -- trigger="any": any sequence's -- tentative buffer holds >= n_i
     tokens) and every (fire after that many intermediate rounds) is given.  With `adaptive` (needs n_i), k
     and n_i are the starting values of N_d and N_i and move by the rule of App. J.  Returns (tokens
     [batch, n_new], LoopStats).  The committed stream may run a few tokens past n_new inside the session;
@@ -77,7 +77,8 @@ def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, ever
                 k_used = k
                 k = adapt_step(k, float(a.sum()) / (B * k_used), *adaptive.nd_tau, adaptive.nd_min, adaptive.nd_max)
             _, nv = sess.counts()
-            if (n_i is not None and int(nv.min()) >= n_i) or (every is not None and rounds >= every):
+            full = int(nv.min()) if trigger == "all" else int(nv.max())     # batch: every / any sequence holds N_i tokens
+            if (n_i is not None and full >= n_i) or (every is not None and rounds >= every):
                 break
             if min(len(o) + int(v) for o, v in zip(out, nv)) >= n_new + k + 2:
                 break

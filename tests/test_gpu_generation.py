@@ -61,7 +61,8 @@ def _adaptive():
     return dict(n_i=4, adaptive=AdaptivePolicy(nd_max=4))
 
 
-@pytest.mark.parametrize("policy", [dict(n_i=6), dict(every=2), "adaptive", "heads"], ids=["n_i6", "every2", "adaptive", "low_rank_heads"])
+@pytest.mark.parametrize("policy", [dict(n_i=6), dict(n_i=4, trigger="any"), dict(every=2), "adaptive", "heads"],
+                         ids=["n_i6", "n_i4_any", "every2", "adaptive", "low_rank_heads"])
 def test_hispec_stream_equals_vanilla_stream_on_gpu(policy):
     from paper_2510_01336_amd.loop import hispec_generate
     cfg = synth.tiny_config(gamma=(1.0, 0.3, 0.3))       # damped upper groups: the exits agree often, not always
