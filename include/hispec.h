@@ -125,7 +125,8 @@ int ee_session_create(ee_model* m, int batch, int max_ctx, int max_rows, int tot
 void ee_session_free(ee_session* s);
 
 /* Context build.  tokens: host, the prompts packed back to back; lens: host [batch], each >= 1.
- * Runs all L_f layers over every prompt (in row chunks), leaves all three group lengths at
+ * Runs all L_f layers over every prompt in passes of up to 512 rows (64 for EE_F32 models): a long prompt fills
+ * passes by itself, short prompts share one; leaves all group lengths at
  * lens[b], and commits first_token[b] = arg max at L_f of the last prompt position
  * (the "Vanilla generation" step of Sec. 3.1).  first_token: host [batch]. */
 int ee_prefill(ee_session* s, const int32_t* tokens, const int32_t* lens, int32_t* first_token);

@@ -528,29 +528,46 @@ static int prefill_impl(ee_session* s, const int32_t* tokens, const int32_t* len
     q = SeqState();
   }
   reset_accounting(s);
-  size_t off = 0;
-  for (int b = 0; b < s->B; ++b) {
-    if (lens[b] <= 0) continue;
-    EE_TRY(grow_pages(s, b, want[b]));
-    const int n = lens[b];
-    for (int r0 = 0, ci = 0; r0 < n; r0 += s->chunk, ++ci) {
-      const int si = ci & 1;      // alternate upload slots so the host runs one chunk ahead
-      CallPlan p;
-      p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
-      p.m[b] = std::min(s->chunk, n - r0); p.p0[b] = r0;
-      const int32_t* tk = tokens + off + r0;
-      EE_TRY(build_meta(s, si, p, [&](int, int r, int& tok, int&, int&) { tok = tk[r]; }));
-      EE_TRY(upload_meta(s, si));
-      CallMeta mt = meta_ptrs(s, s->slot[si].d);
-      KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
-      run_layers(s, 0, c.n_layers, p, mt, 0);
-      if (r0 + s->chunk >= n) {
-        exit_head(s, p.M, 2);
-        HIP_TRY(hipMemcpyAsync(s->out_host + b, s->vtok + (p.M - 1), sizeof(int), hipMemcpyDeviceToHost, s->st));
-      }
+  std::vector<size_t> off0(s->B, 0);
+  std::vector<int> done(s->B, 0);
+  {
+    size_t o = 0;
+    for (int b = 0; b < s->B; ++b) {
+      off0[b] = o;
+      if (lens[b] <= 0) continue;
+      o += lens[b];
+      EE_TRY(grow_pages(s, b, want[b]));
     }
-    off += n;
   }
+  // Passes of up to `chunk` rows.  A pass takes one contiguous piece of every prompt that still has rows, in
+  // sequence order, until it is full: a long prompt fills passes by itself, short prompts share one (the weights
+  // cross HBM once per pass).  A sequence's next piece comes in a later pass, after its earlier rows are cached.
+  for (int ci = 0;; ++ci) {
+    const int si = ci & 1;        // alternate upload slots so the host runs one pass ahead
+    CallPlan p;
+    p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
+    int room = s->chunk;
+    for (int b = 0; b < s->B && room > 0; ++b) {
+      if (lens[b] <= 0 || done[b] >= lens[b]) continue;
+      p.m[b] = std::min(lens[b] - done[b], room); p.p0[b] = done[b];
+      room -= p.m[b];
+    }
+    if (room == s->chunk) break;
+    EE_TRY(build_meta(s, si, p, [&](int b, int r, int& tok, int&, int&) { tok = tokens[off0[b] + done[b] + r]; }));
+    EE_TRY(upload_meta(s, si));
+    CallMeta mt = meta_ptrs(s, s->slot[si].d);
+    KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
+    run_layers(s, 0, c.n_layers, p, mt, 0);
+    bool head_done = false;
+    for (int b = 0, row = 0; b < s->B; row += p.m[b], ++b) {
+      if (!p.m[b] || done[b] + p.m[b] < lens[b]) continue;
+      // the prompt ends in this pass: its last row decides the first committed token
+      if (!head_done) { exit_head(s, p.M, 2); head_done = true; }
+      HIP_TRY(hipMemcpyAsync(s->out_host + b, s->vtok + (row + p.m[b] - 1), sizeof(int), hipMemcpyDeviceToHost, s->st));
+    }
+    for (int b = 0; b < s->B; ++b) done[b] += p.m[b];
+  }
+  size_t off = 0;
   EE_TRY(finish(s));
   off = 0;
   for (int b = 0; b < s->B; ++b) {
