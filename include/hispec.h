@@ -49,7 +49,7 @@ enum { EE_F32 = 0, EE_BF16 = 1 };
 enum {
   EE_T_EMB = 0, EE_T_HEAD = 1, EE_T_GFINAL = 2, EE_T_G1 = 3, EE_T_WQ = 4, EE_T_WK = 5,
   EE_T_WV = 6, EE_T_WO = 7, EE_T_G2 = 8, EE_T_WGATE = 9, EE_T_WUP = 10, EE_T_WDOWN = 11,
-  /* auxiliary low-rank exit heads (head_rank > 0): the `layer` argument is the exit, 0 = L_d, 1 = L_i */
+  /* auxiliary low-rank exit heads (head_rank > 0): the `layer` argument is the exit, 0 = L_d, 1 = L_i, 2.. = extra exits */
   EE_T_AUX_G = 12,   /* gain of the adapter's RMSNorm        [d_model]            */
   EE_T_AUX_A = 13,   /* down projection                      [head_rank, d_model] */
   EE_T_AUX_B = 14    /* up projection (synthetic init: damped by gamma[exit])  [d_model, head_rank] */
@@ -70,8 +70,8 @@ typedef struct ee_config {
   float sigma;          /* std of the synthetic weights (used by seeded init only)           */
   float gamma[3];       /* synthetic damping of the residual-writing matrices (Wo, Wdown) of
                            G1, G2, G3; 1 = plain random init                                 */
-  int32_t head_rank;    /* 0: every exit uses the shared final norm + LM head (Sec. 3.1).  r > 0: the early
-                           exits L_d and L_i first pass the hidden state through their own rank-r adapter,
+  int32_t head_rank;    /* 0: every exit uses the shared final norm + LM head (Sec. 3.1).  r > 0: every early
+                           exit (L_d, L_i, the extra verifier exits) first passes the hidden state through its own rank-r adapter,
                            z = h + B (A RMSNorm(h; g)), and feed z to the shared norm and head -- the
                            low-rank prediction heads of the post-training conversion (App. I).  The final
                            exit is unchanged.  EE_BF16 models need a multiple of 32.                       */

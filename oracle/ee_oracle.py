@@ -157,8 +157,9 @@ class ModelSpec:
         return (self.exit_draft, self.exit_inter) + tuple(self.exit_extra) + (self.n_layers,)
 
     def exit_index(self, exit_layer: int) -> int:
-        """0 for L_d, 1 for L_i, 2 for any other depth (the shared head alone)."""
-        return 0 if exit_layer == self.exit_draft else (1 if exit_layer == self.exit_inter else 2)
+        """Position of a layer in the exit list; any other depth counts as the final exit (the shared head alone)."""
+        ex = self.exits
+        return ex.index(exit_layer) if exit_layer in ex else len(ex) - 1
 
     def group_layers(self, g: int) -> range:
         b = (0, self.exit_draft, self.exit_inter, self.n_layers)
@@ -213,15 +214,18 @@ class EEModel:
             x = self.layer(l, x, pos, cache)
         return x
 
-    def exit_logits(self, x: np.ndarray, which: int = 2) -> np.ndarray:
-        """Prediction head of exit `which` (0 = L_d, 1 = L_i, 2 = L_f) on hidden rows x.
+    def exit_logits(self, x: np.ndarray, which: Optional[int] = None) -> np.ndarray:
+        """Prediction head of exit number `which` in spec.exits (0 = L_d, 1 = L_i, ..., last = L_f, the
+        default) on hidden rows x.
 
         The final layer, and every exit of a model without auxiliary heads, uses the shared final
         norm + shared LM head.  With head_rank = r > 0 (the post-training conversion of App. I,
-        "low-rank prediction heads") the early exits first pass the hidden state through their own
-        rank-r residual adapter,  z = x + B_e (A_e RMSNorm(x; g_e)),  and feed z to the shared norm
+        "low-rank prediction heads") every early exit first passes the hidden state through its own
+        rank-r residual adapter,  z = x + B_e (A_e RMSNorm(x; g_e)),  and feeds z to the shared norm
         and head: the reading that fits the appendix's bound on added parameters."""
-        if self.spec.head_rank > 0 and which < 2:
+        last = len(self.spec.exits) - 1
+        which = last if which is None else which
+        if self.spec.head_rank > 0 and which < last:
             n = self.rnd(rmsnorm(x, self._w("aux_g", which), self.spec.rms_eps))
             t = self.rnd(n @ self._w("aux_a", which).T)
             x = x + t @ self._w("aux_b", which).T
@@ -615,7 +619,7 @@ class MultiLevelOracle:
         return range(self.exits[g - 1] if g else 0, self.exits[g])
 
     def _head(self, x: np.ndarray, level: int) -> np.ndarray:
-        return self.m.exit_logits(x, level if level < 2 else 2)
+        return self.m.exit_logits(x, level)
 
     def prefill(self, seq: MultiSequence, prompt: Sequence[int]) -> int:
         t = len(prompt)

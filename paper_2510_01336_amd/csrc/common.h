@@ -111,8 +111,8 @@ struct ee_model {
   size_t emb = 0;            // [vocab][d] row-major, bf16 or fp32
   size_t gfinal = 0;         // fp32 [d]
   MatLoc head;
-  size_t auxg[2] = {0, 0};   // auxiliary exit heads (cfg.head_rank > 0), per early exit: fp32 gain [d],
-  MatLoc auxA[2], auxB[2];   // down projection [r, d] and up projection [d, r]
+  size_t auxg[EE_MAX_GROUPS - 1] = {0, 0, 0, 0, 0, 0};   // auxiliary exit heads (cfg.head_rank > 0), per early exit: fp32 gain [d],
+  MatLoc auxA[EE_MAX_GROUPS - 1], auxB[EE_MAX_GROUPS - 1];   // down projection [r, d] and up projection [d, r]
   std::vector<LayerLoc> L;
   double* inv_freq = nullptr;  // device [head_dim/2] rotary frequencies (inside the arena)
 };

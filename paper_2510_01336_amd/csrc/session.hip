@@ -365,8 +365,9 @@ static void gemm(ee_session* s, int epi, const MatLoc& ml, const bf16_t* A, int 
 // offset of the gain that normalises the hidden state behind layer l1: the adapter's own gain at an early exit
 // with an auxiliary head, else the shared final gain
 static size_t closing_gain(const ee_model* m, int l1) {
-  if (m->cfg.head_rank > 0 && l1 == m->cfg.exit_draft) return m->auxg[0];
-  if (m->cfg.head_rank > 0 && l1 == m->cfg.exit_inter) return m->auxg[1];
+  if (m->cfg.head_rank > 0)
+    for (size_t e = 0; e + 1 < m->exits.size(); ++e)
+      if (l1 == m->exits[e]) return m->auxg[e];
   return m->gfinal;
 }
 
@@ -433,7 +434,7 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
   }
 }
 
-// Prediction head of exit `which` (0 = L_d, 1 = L_i, 2 = L_f) + arg max for rows 0..M-1 of X -> vtok.
+// Prediction head of exit `which` (0 = L_d, 1 = L_i, ..., n_levels = L_f) + arg max for rows 0..M-1 of X -> vtok.
 // The shared final RMSNorm and LM head (Sec. 3.1); at an early exit of a model with auxiliary heads
 // (App. I) behind that exit's rank-r adapter  z = x + B (A RMSNorm(x; g)),  which leaves X itself alone.
 static void exit_head(ee_session* s, int M, int which) {
@@ -442,7 +443,7 @@ static void exit_head(ee_session* s, int M, int which) {
   hipStream_t st = s->st;
   const int d = c.d_model, r = c.head_rank;
   const float* gf = (const float*)(m->base + m->gfinal);
-  const bool aux = r > 0 && which < 2;
+  const bool aux = r > 0 && which < s->n_levels;
   if (m->bf16) {
     // the last down projection of the pass left XN = bf16(x * gain) and the partial sums of squares
     const int Mp = s->Mp;
@@ -562,7 +563,7 @@ static int prefill_impl(ee_session* s, const int32_t* tokens, const int32_t* len
     for (int b = 0, row = 0; b < s->B; row += p.m[b], ++b) {
       if (!p.m[b] || done[b] + p.m[b] < lens[b]) continue;
       // the prompt ends in this pass: its last row decides the first committed token
-      if (!head_done) { exit_head(s, p.M, 2); head_done = true; }
+      if (!head_done) { exit_head(s, p.M, s->n_levels); head_done = true; }
       HIP_TRY(hipMemcpyAsync(s->out_host + b, s->vtok + (row + p.m[b] - 1), sizeof(int), hipMemcpyDeviceToHost, s->st));
     }
     for (int b = 0; b < s->B; ++b) done[b] += p.m[b];
@@ -643,7 +644,7 @@ extern "C" int ee_decode_ar(ee_session* s, int n, int32_t* out) {
   for (int j = 0; j < n; ++j) {       // the next token stays on the device; positions advance through pos_add
     KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, j == 0 ? mt.row_tok : s->tok_next, s->X, p.M, c.d_model));
     run_layers(s, 0, c.n_layers, p, mt, j);
-    exit_head(s, p.M, 2);
+    exit_head(s, p.M, s->n_levels);
     KF(KF_MISC, k_take_token(s->st, s->vtok, mt.row_seq, p.M, s->tok_next, s->draft_dev, s->max_rows, j));
   }
   int* dh = s->out_host + 2 * s->B;
@@ -968,7 +969,7 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
   KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, rows_below, mt.row_src, p.M, c.d_model));  // consume the buffered rows
   run_layers(s, ex[j - 1], ex[j], p, mt, 0);
   s->need_logits = rs;
-  exit_head(s, p.M, 2);
+  exit_head(s, p.M, j);
   s->need_logits = false;
   if (j < n) KF(KF_COPY, k_copy_rows(s->st, level_rows(s, j), mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));   // keep exit j's rows
   if (rs) {      // second stage of App. G: V, distributed as p_{L_i}, is the draft; p_{L_f} the target

@@ -73,7 +73,7 @@ int ee_layout_model(ee_model* m) {
   m->emb = cur; cur += (size_t)c.vocab * d * es;
   cur = align_up(cur, 256); m->gfinal = cur; cur += (size_t)d * 4;
   m->head = place(cur, c.vocab, d, m->bf16);
-  for (int e = 0; e < 2 && c.head_rank > 0; ++e) {
+  for (int e = 0; e + 1 < (int)m->exits.size() && c.head_rank > 0; ++e) {      // every exit but the last
     cur = align_up(cur, 256); m->auxg[e] = cur; cur += (size_t)d * 4;
     m->auxA[e] = place(cur, c.head_rank, d, m->bf16);
     m->auxB[e] = place(cur, d, c.head_rank, m->bf16);
@@ -100,7 +100,7 @@ int ee_tensor_map(const ee_model* m, int tid, int layer, TensorMap* t) {
   const int d = c.d_model, D = c.head_dim;
   if (tid >= EE_T_AUX_G && tid <= EE_T_AUX_B) {
     if (c.head_rank <= 0) { ee_set_error("the model has no auxiliary exit heads"); return EE_ERR_ARG; }
-    if (layer < 0 || layer > 1) { ee_set_error("exit index must be 0 (L_d) or 1 (L_i)"); return EE_ERR_ARG; }
+    if (layer < 0 || layer + 1 >= (int)m->exits.size()) { ee_set_error("exit index must name an early exit (0 = L_d, 1 = L_i, ...)"); return EE_ERR_ARG; }
     if (tid == EE_T_AUX_G) *t = {1, d, 1, m->auxg[layer], 0, 0, 0, D};
     else if (tid == EE_T_AUX_A) *t = {0, c.head_rank, d, m->auxA[layer].off, 0, 0, m->auxA[layer].Kp, D};
     else *t = {0, d, c.head_rank, m->auxB[layer].off, 0, 0, m->auxB[layer].Kp, D};
@@ -208,7 +208,7 @@ static int gen_one(ee_model* m, int tid, int layer) {
   const bool per_layer = tid >= EE_T_G1;
   uint64_t key = mix64(mix64(m->seed) ^ (((uint64_t)tid << 32) | (uint64_t)(per_layer ? layer : 0)));
   float gamma = (tid == EE_T_WO || tid == EE_T_WDOWN) ? m->cfg.gamma[group_of_layer(m->cfg, layer)] : 1.0f;
-  if (tid == EE_T_AUX_B) gamma = m->cfg.gamma[layer];     // `layer` is the exit index here
+  if (tid == EE_T_AUX_B) gamma = m->cfg.gamma[layer < 2 ? layer : 2];     // `layer` is the exit index here
   volatile float s1 = m->cfg.sigma * gamma;        // one fp32 product, then an exact power-of-two scale
   float scale = s1 * 1.52587890625e-05f;           // 2^-16
   int gain = (tid == EE_T_GFINAL || tid == EE_T_G1 || tid == EE_T_G2 || tid == EE_T_AUX_G);
@@ -249,7 +249,7 @@ extern "C" int ee_model_load(const ee_config* cfg, void* dev_arena, size_t arena
   if (e != hipSuccess) { ee_set_error("memset: %s", hipGetErrorString(e)); delete m; return EE_ERR_HIP; }
   int rc = EE_OK;
   for (int tid = EE_T_EMB; tid <= EE_T_GFINAL && rc == EE_OK; ++tid) rc = gen_one(m, tid, 0);
-  for (int e = 0; e < 2 && cfg->head_rank > 0; ++e)
+  for (int e = 0; e + 1 < (int)m->exits.size() && cfg->head_rank > 0; ++e)
     for (int tid = EE_T_AUX_G; tid <= EE_T_AUX_B && rc == EE_OK; ++tid) rc = gen_one(m, tid, e);
   for (int l = 0; l < cfg->n_layers && rc == EE_OK; ++l)
     for (int tid = EE_T_G1; tid <= EE_T_WDOWN && rc == EE_OK; ++tid) rc = gen_one(m, tid, l);

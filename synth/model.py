@@ -44,7 +44,7 @@ TENSOR_IDS: Dict[str, int] = {
 GLOBAL_TENSORS = ("emb", "head", "gfinal")
 LAYER_TENSORS = ("g1", "wq", "wk", "wv", "wo", "g2", "wgate", "wup", "wdown")
 # auxiliary low-rank exit heads (cfg.head_rank > 0): one set per early exit, looked up with the exit
-# index in the layer slot (0 = L_d, 1 = L_i)
+# index in the layer slot (0 = L_d, 1 = L_i, 2.. = the further verifier exits)
 EXIT_TENSORS = ("aux_g", "aux_a", "aux_b")
 GAIN_TENSORS = ("gfinal", "g1", "g2", "aux_g")
 DAMPED_TENSORS = ("wo", "wdown")  # scaled by gamma[group of the layer]; aux_b by gamma[exit index]
@@ -66,7 +66,7 @@ class EEConfig:
     dtype: str = "f32"       # "f32" | "bf16"
     sigma: float = 0.02
     gamma: Tuple[float, float, float] = (1.0, 1.0, 1.0)
-    head_rank: int = 0       # > 0: the exits L_d and L_i carry a low-rank adapter of this rank in front of the shared head
+    head_rank: int = 0       # > 0: every early exit carries a low-rank adapter of this rank in front of the shared head
     exit_extra: Tuple[int, ...] = ()   # further intermediate verifier exits between L_i and L_f (strictly increasing)
 
     def __post_init__(self):
@@ -184,7 +184,7 @@ def _lane_sum(key: int, e: np.ndarray) -> np.ndarray:
 def tensor_scale(cfg: EEConfig, name: str, layer: int) -> np.float32:
     gamma = cfg.gamma[cfg.group_of_layer(layer)] if name in DAMPED_TENSORS else 1.0
     if name == "aux_b":
-        gamma = cfg.gamma[layer]
+        gamma = cfg.gamma[min(layer, 2)]
     s1 = np.float32(cfg.sigma) * np.float32(gamma)
     return np.float32(s1) * np.float32(2.0 ** -16)
 

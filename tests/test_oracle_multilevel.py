@@ -177,3 +177,19 @@ def test_rollback_through_the_buffers_then_continue(cut_in):
     assert seq.C[:len(surv)] == surv
     assert seq.C[len(surv):] == eo.ar_generate(m, surv, len(seq.C) - len(surv))
     _check_against_recomputation(m, M, seq)
+
+
+def test_chain_with_low_rank_heads_at_every_early_exit():
+    """head_rank gives every exit but the last its own adapter (the final exit decides the output, so the
+    stream stays the greedy stream of the plain model)."""
+    cfg = _cfg(exit_draft=1, exit_inter=3, exit_extra=(5,), head_rank=16)
+    m = _model(cfg)
+    plain = _model(_cfg(exit_draft=1, exit_inter=3, exit_extra=(5,)))
+    x = np.random.default_rng(0).standard_normal((3, cfg.d_model))
+    for e in range(3):
+        assert np.max(np.abs(m.exit_logits(x, e) - plain.exit_logits(x, e))) > 1e-3       # exits 0, 1, 2 have adapters
+    np.testing.assert_array_equal(m.exit_logits(x, 3), plain.exit_logits(x, 3))
+    np.testing.assert_array_equal(m.exit_logits(x), plain.exit_logits(x))                # default: the final exit
+    assert m.spec.exit_index(5) == 2 and m.spec.exit_index(8) == 3 and m.spec.exit_index(2) == 3
+    prompt = synth.gen_prompt(cfg.vocab, 9, 1)
+    assert eo.MultiLevelOracle(m).generate(prompt, 30, 3, [3, 4]) == eo.ar_generate(plain, prompt, 30)
