@@ -33,7 +33,7 @@ def bf16_chain(**kw):
 PLANS = [
     ("f32_3_levels", f32_chain(), 3, [40, 9, 70], 4, [[1], [1, 2], [1, 2, 3], [1, 2], [1, 2, 3]]),
     ("bf16_4_levels", bf16_chain(), 8, [90, 33], 6, [[1, 2], [1], [1, 2, 3], [1, 2, 3, 4], [1, 2, 3, 4]]),
-    # low-rank heads at L_d and L_i, the shared head at the exits above
+    # low-rank heads at every early exit (L_d, L_i and the extra one), the shared head alone at L_f
     ("f32_3_levels_low_rank_heads", f32_chain(head_rank=24), 1, [40, 9], 4, [[1], [1, 2], [1, 2, 3], [1, 2, 3]]),
     # an explicit prune through the buffers in the middle, then on
     ("f32_3_levels_rollback", f32_chain(), 1, [40, 9], 4, [[1, 2], [1, 2], [1], "cut", [1, 2], [1, 2, 3], "cut", [1, 2, 3]]),
