@@ -9,6 +9,9 @@ the paper's decoding algorithms, written from the paper:
 * LeadingSubstringVerify                       -- last function of Algorithms 1/2
 * KV-cache / hidden-state reuse with pruning   -- Sec. 3.2
 * per-sequence acceptance in a batch           -- Sec. "HiSpec Supports Batched Inference"
+* rejection-sampling acceptance                -- App. G (rejection_verify and the rs arguments)
+* low-rank exit heads                          -- App. I (EEModel.exit_logits, ModelSpec.head_rank)
+* a chain of intermediate verifiers            -- Future Work section (MultiLevelOracle)
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import
 this module; the product path never does.  It shares no code with the HIP
