@@ -205,6 +205,56 @@ def test_verify_rounds_match_oracle(name, cfg, ctx, k, bonus):
     sess.close(); model.close()
 
 
+def test_more_than_512_rows_in_one_call():
+    """60 sequences x 9 block rows = 540 rows: beyond the row-tiled GEMM's 512, so the projections run as 64-row
+    passes of the skinny kernel.  With so many sequences some deciding row is always a near-tie, so every sequence
+    is compared as far as its own rows clear the margin (and dropped once the two sides may have parted)."""
+    cfg, k, tol = bf16_small(), 8, TOL["bf16"]
+    ctx = [5 + (7 * i) % 60 for i in range(60)]
+    B, max_rows = len(ctx), 3 * (k + 1) + 2
+    max_ctx = max(ctx) + 4 * max_rows
+    O = OracleSide(cfg, 777)
+    model, sess = gpu_side(cfg, 777, B, max_ctx, max_rows)
+    sess.enable_logits(True)
+    prompts = [synth.gen_prompt(cfg.vocab, n, 100 + b) for b, n in enumerate(ctx)]
+    first, margins = O.prefill(prompts, max_ctx)
+    gfirst = sess.prefill(prompts)
+    good = np.ones(B, bool)
+    for b in range(B):
+        if margins[b] > MARGIN:
+            assert gfirst[b] == first[b], b
+        elif gfirst[b] != first[b]:
+            good[b] = False
+    rng = np.random.default_rng(3)
+    drafts = np.stack([synth.make_draft_block(O.greedy(s, k, cfg.exit_inter), k, 0.7, cfg.vocab, rng) for s in O.seqs])
+    sess.draft_inject(drafts)
+    ga, gn = sess.verify_intermediate()
+    assert sess.last_logits().shape[0] >= B * (k + 1) > 512
+    glog, r0, compared_i = sess.last_logits(), 0, 0
+    for b, s in enumerate(O.seqs):
+        O.o.draft_inject(s, drafts[b])
+        a, nxt = O.o.verify_intermediate(s)
+        rows = len(O.o.last_logits)
+        clear = eo.top2_margin(O.o.last_logits)[:a + 1].min() > MARGIN
+        if good[b] and clear:
+            assert (int(ga[b]), int(gn[b])) == (a, nxt), b
+            assert max_rel(glog[r0:r0 + rows], O.o.last_logits) <= tol
+            compared_i += 1
+        elif (int(ga[b]), int(gn[b])) != (a, nxt):
+            good[b] = False
+        r0 += rows
+    gf, gn, gcom = sess.verify_full()
+    compared_f = 0
+    for b, s in enumerate(O.seqs):
+        f, nxt, F = O.o.verify_full(s)
+        clear = eo.top2_margin(O.o.last_logits)[:f + 1].min() > MARGIN
+        if good[b] and clear:
+            assert (int(gf[b]), int(gn[b]), gcom[b]) == (f, nxt, F), b
+            compared_f += 1
+    assert compared_i >= 40 and compared_f >= 30, (compared_i, compared_f)
+    sess.close(); model.close()
+
+
 def test_all_correct_and_wrong_first_blocks():
     cfg = bf16_small()
     k = 8
