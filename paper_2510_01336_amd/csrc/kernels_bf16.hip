@@ -373,7 +373,7 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row-tiled GEMM for 16 < M <= 512 rows: weights still cross HBM once, but every weight fragment now
+// Row-tiled GEMM for a block of 16 < M <= 512 rows: weights cross HBM once per block, but every weight fragment now
 // meets up to 32 row tiles, so the kernel sits near the machine's ridge (M flop per weight byte).
 // Workgroup = 8 waves (two per SIMD: one wave alone does not keep a matrix pipe busy) on a group of
 // 8 weight tiles (128 output features) and a share of K (grid.y); wave (rq, nh) owns 4 of the tiles and a
@@ -397,8 +397,10 @@ __host__ __device__ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((
 
 template <int TMT, int EPI>
 __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict__ W, int ktiles, int ntiles,
-                                                        const uint4* __restrict__ A, int M, int N, GemmOut out,
+                                                        const uint4* __restrict__ A, int row0, int M, int N, GemmOut out,
                                                         int per, float* __restrict__ partial) {
+  // rows row0 .. row0+M-1 of the operand (row0 a multiple of 16); the deferred-norm factors and the K-share
+  // partials are indexed from the block's first row, everything the epilogue touches by the row itself
   constexpr int TN = EE_ROWS_TN, NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
   constexpr int TMW = TMT / 4;                      // row tiles per wave
   static_assert(TMT % 4 == 0 && TMT >= 4 && TMT <= 32, "row tiles split four ways");
@@ -433,7 +435,7 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)&ring[0][0]) + 1024u * wave_s;
 #define ROWS_LDS(slot_, tile_) ((lptr_t)(size_t)(lds0 + 16u * ((slot_) * STAGE + (tile_) * 64)))
   const u32x4* wsrc = (const u32x4*)W + (size_t)min(blockIdx.x * (2 * TN) + wave, ntiles - 1) * ktiles * 64 + lane;
-  const u32x4* xsrc = (const u32x4*)A + (size_t)wave * ktiles * 64 + lane;
+  const u32x4* xsrc = (const u32x4*)A + (size_t)((row0 >> 4) + wave) * ktiles * 64 + lane;
 #define ROWS_REQUEST(slot_, kt_)                                                                              \
   do {                                                                                                        \
     const size_t k_ = (size_t)min(kt_, last) * 64;                                                            \
@@ -530,8 +532,8 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
       if ((mt0 + mt) * 16 >= M) continue;
       const float sc = out.nin.inv_rms ? out.nin.inv_rms[min(m, M - 1)] : 1.0f;
       EpiPre pre;
-      epi_prefetch<EPI>(pre, out, task, m, m < M, lane);
-      epi_apply<EPI>(acc[t * NB][mt], acc[t * NB + NB - 1][mt], sc, pre, out, task, m, m < M, N, lane);
+      epi_prefetch<EPI>(pre, out, task, row0 + m, m < M, lane);
+      epi_apply<EPI>(acc[t * NB][mt], acc[t * NB + NB - 1][mt], sc, pre, out, task, row0 + m, m < M, N, lane);
     }
   }
 }
@@ -539,7 +541,7 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
 // sums the K shares of one (task, row tile) in a fixed order and runs the epilogue; one wave per unit
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_rows_reduce_kernel(const float* __restrict__ partial, int ksplit, int ntiles, int TMT,
-                                                               int M, int N, GemmOut out) {
+                                                               int row0, int M, int N, GemmOut out) {
   constexpr int NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
   const int lane = threadIdx.x & 63, mc = lane & 15;
   const int mtiles = (M + 15) >> 4;
@@ -548,7 +550,7 @@ __global__ __launch_bounds__(256) void gemm_rows_reduce_kernel(const float* __re
   if (task * NB >= ntiles) return;
   const int m = mt * 16 + mc;
   EpiPre pre;
-  epi_prefetch<EPI>(pre, out, task, m, m < M, lane);
+  epi_prefetch<EPI>(pre, out, task, row0 + m, m < M, lane);
   const float sc = out.nin.inv_rms ? out.nin.inv_rms[min(m, M - 1)] : 1.0f;
   f32x4 acc[NB];
 #pragma unroll
@@ -564,7 +566,7 @@ __global__ __launch_bounds__(256) void gemm_rows_reduce_kernel(const float* __re
         if (s0 + i < ksplit) acc[nb] += t[i];
     }
   }
-  epi_apply<EPI>(acc[0], acc[NB - 1], sc, pre, out, task, m, m < M, N, lane);
+  epi_apply<EPI>(acc[0], acc[NB - 1], sc, pre, out, task, row0 + m, m < M, N, lane);
 }
 
 // per-row factor rsqrt(mean(x^2) + eps) from the producer's per-tile partial sums of squares, in a fixed order:
@@ -599,47 +601,51 @@ size_t bf16_gemm_rows_scratch_floats(int ntiles, int ktiles) {
 }
 
 template <int TMT>
-static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int M, int N,
+static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int row0, int M, int N,
                              const GemmOut& out, float* scratch) {
   const int ks = rows_ksplit(ntiles, ktiles), per = ceil_div(ktiles, ks);
   dim3 grid(ceil_div(ntiles, 2 * EE_ROWS_TN), ceil_div(ktiles, per)), blk(512), rblk(256);
   const int ksr = grid.y;
   switch (epi) {
-    case EPI_ADD: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ADD>), grid, blk, 0, st, W, ktiles, ntiles, A, M, N, out, per, scratch); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_SWIGLU>), grid, blk, 0, st, W, ktiles, ntiles, A, M, N, out, per, scratch); break;
-    case EPI_ROPE: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ROPE>), grid, blk, 0, st, W, ktiles, ntiles, A, M, N, out, per, scratch); break;
-    default: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ARGMAX>), grid, blk, 0, st, W, ktiles, ntiles, A, M, N, out, per, scratch); break;
+    case EPI_ADD: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ADD>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_SWIGLU>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); break;
+    case EPI_ROPE: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ROPE>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); break;
+    default: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ARGMAX>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); break;
   }
   if (ksr > 1) {
     const int nb = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? 2 : 1;
     const int units = (ntiles / nb) * ceil_div(M, 16);
     dim3 rgrid(ceil_div(units, 4));
     switch (epi) {
-      case EPI_ADD: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ADD>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
-      case EPI_SWIGLU: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_SWIGLU>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
-      case EPI_ROPE: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ROPE>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
-      default: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ARGMAX>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, M, N, out); break;
+      case EPI_ADD: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ADD>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, row0, M, N, out); break;
+      case EPI_SWIGLU: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_SWIGLU>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, row0, M, N, out); break;
+      case EPI_ROPE: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ROPE>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, row0, M, N, out); break;
+      default: hipLaunchKernelGGL((gemm_rows_reduce_kernel<EPI_ARGMAX>), rgrid, rblk, 0, st, scratch, ksr, ntiles, TMT, row0, M, N, out); break;
     }
   }
 }
 
-// 16 < M <= 512 rows from row 0 of the operand; out.nin.ssq, if set, is first reduced to per-row factors
+// more than 16 rows from row 0 of the operand; out.nin.ssq, if set, is first reduced to per-row factors (per block)
 void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                     const GemmOut& out0, float* scratch, float* inv_rms) {
-  GemmOut out = out0;
-  if (out.nin.ssq) {
-    hipLaunchKernelGGL(norm_factor_kernel, dim3(ceil_div(M, 4)), dim3(256), 0, st, out.nin.ssq, out.nin.n_part, out.nin.stride,
-                       out.nin.inv_d, out.nin.eps, inv_rms, M);
-    out.nin.inv_rms = inv_rms;
-  }
   const uint4* Wc = (const uint4*)W;
   const uint4* Ac = (const uint4*)A;
-  if (M <= 64) launch_gemm_rows<4>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
-  else if (M <= 128) launch_gemm_rows<8>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
-  else if (M <= 192) launch_gemm_rows<12>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
-  else if (M <= 256) launch_gemm_rows<16>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
-  else if (M <= 384) launch_gemm_rows<24>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
-  else launch_gemm_rows<32>(st, epi, Wc, ntiles, ktiles, Ac, M, N, out, scratch);
+  // blocks of up to 512 rows: calls beyond that stream the weights once per block
+  for (int m0 = 0; m0 < M; m0 += 512) {
+    const int mc = min(512, M - m0);
+    GemmOut out = out0;
+    if (out.nin.ssq) {
+      hipLaunchKernelGGL(norm_factor_kernel, dim3(ceil_div(mc, 4)), dim3(256), 0, st, out.nin.ssq + m0, out.nin.n_part, out.nin.stride,
+                         out.nin.inv_d, out.nin.eps, inv_rms, mc);
+      out.nin.inv_rms = inv_rms;
+    }
+    if (mc <= 64) launch_gemm_rows<4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
+    else if (mc <= 128) launch_gemm_rows<8>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
+    else if (mc <= 192) launch_gemm_rows<12>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
+    else if (mc <= 256) launch_gemm_rows<16>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
+    else if (mc <= 384) launch_gemm_rows<24>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
+    else launch_gemm_rows<32>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
+  }
 }
 
 template <int MT, int U>

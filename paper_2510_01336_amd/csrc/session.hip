@@ -169,8 +169,8 @@ static int shape_session(ee_session* s, const ee_model* m, int batch, int max_ct
   s->n_pages = total_pages > 0 ? total_pages : batch * s->pps;
   s->chunk = m->bf16 ? 512 : 64;                        // context-build rows per pass
   s->maxM = std::max(batch * max_rows, s->chunk);
-  // activation rows padded to whole GEMM passes: 64 rows (skinny kernel), 512 (the row-tiled kernel requests up to 32 row tiles)
-  s->Mp = s->maxM <= 64 ? 64 : std::max(512, ceil_div(s->maxM, 64) * 64);
+  // activation rows padded to whole GEMM passes: 64 rows (skinny kernel), blocks of 512 (the row-tiled kernel requests up to 32 row tiles)
+  s->Mp = s->maxM <= 64 ? 64 : ceil_div(s->maxM, 512) * 512;
   s->maxQT = ceil_div(s->maxM * rep, 16) + batch;
   layout_meta(s);
   return EE_OK;
@@ -354,11 +354,11 @@ static void reset_accounting(ee_session* s) {
 // ---------------------------------------------------------------------------------------------
 // weights cross HBM once per call: up to 16 rows the skinny kernel, from 33 to 512 the row-tiled one, in
 // between the row-tiled one for matrices of 128 MB and more (measured: the small projections are quicker
-// without its K-share reduction pass); beyond 512 rows the skinny kernel goes over the rows in passes of 64
+// without its K-share reduction pass); beyond 512 rows the row-tiled kernel goes over the rows in blocks of 512
 static void gemm(ee_session* s, int epi, const MatLoc& ml, const bf16_t* A, int M, const GemmOut& o) {
   const bf16_t* W = (const bf16_t*)(s->m->base + ml.off);
   const bool big = (size_t)ml.ntiles() * ml.ktiles() * 1024 >= ((size_t)128 << 20);
-  if (M > (big ? 16 : 32) && M <= 512) bf16_gemm_rows(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o, s->gemm_part, s->inv_rms);
+  if (M > (big ? 16 : 32)) bf16_gemm_rows(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o, s->gemm_part, s->inv_rms);
   else bf16_gemm(s->st, epi, W, ml.ntiles(), ml.ktiles(), A, M, ml.N, o);
 }
 
