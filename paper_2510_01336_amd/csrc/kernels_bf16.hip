@@ -630,9 +630,10 @@ void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kt
                     const GemmOut& out0, float* scratch, float* inv_rms) {
   const uint4* Wc = (const uint4*)W;
   const uint4* Ac = (const uint4*)A;
-  // blocks of up to 512 rows: calls beyond that stream the weights once per block
-  for (int m0 = 0; m0 < M; m0 += 512) {
-    const int mc = min(512, M - m0);
+  // blocks of up to 512 rows, of equal size up to a row tile: calls beyond 512 rows stream the weights once per block
+  const int blk = ceil_div(ceil_div(M, ceil_div(M, 512)), 16) * 16;
+  for (int m0 = 0; m0 < M; m0 += blk) {
+    const int mc = min(blk, M - m0);
     GemmOut out = out0;
     if (out.nin.ssq) {
       hipLaunchKernelGGL(norm_factor_kernel, dim3(ceil_div(mc, 4)), dim3(256), 0, st, out.nin.ssq + m0, out.nin.n_part, out.nin.stride,
