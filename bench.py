@@ -297,8 +297,8 @@ def calibration_copy(stream_ptr):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="8b_b1_ctx2048_k8", choices=sorted(WORKLOADS) + sorted(E2E_WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gamma", default="1.0,0.02,0.01", help="e2e workloads: residual-branch damping of G1,G2,G3")

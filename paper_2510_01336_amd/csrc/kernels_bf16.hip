@@ -377,7 +377,8 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 // meets up to 32 row tiles, so the kernel sits near the machine's ridge (M flop per weight byte).
 // Workgroup = 8 waves (two per SIMD: one wave alone does not keep a matrix pipe busy) on a group of
 // 8 weight tiles (128 output features) and a share of K (grid.y); wave (rq, nh) owns 4 of the tiles and a
-// quarter of the TMT row tiles: TMT accumulators.
+// quarter of the TMT row tiles (every fourth one): TMT accumulators.  Row tiles past the last row are neither
+// requested nor multiplied.
 // Both operands reach LDS by direct global->LDS loads (no staging registers, no LDS store
 // instructions): a ring of S stages, one k-tile each (8 KiB of weights + TMT KiB of activations), as many
 // as LDS holds, of which up to S-2 are in flight: that is what covers the HBM latency with one workgroup
@@ -395,7 +396,7 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 // s_waitcnt immediate: at most n vector-memory loads outstanding, all LDS reads done, export counter untouched
 __host__ __device__ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
-template <int TMT, int EPI>
+template <int TMT, int EPI, bool FULL>
 __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict__ W, int ktiles, int ntiles,
                                                         const uint4* __restrict__ A, int row0, int M, int N, GemmOut out,
                                                         int per, float* __restrict__ partial) {
@@ -406,13 +407,23 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   static_assert(TMT % 4 == 0 && TMT >= 4 && TMT <= 32, "row tiles split four ways");
   constexpr int STAGE = (2 * TN + TMT) * 64;        // 16-byte units: weight tiles first, then row tiles
   constexpr int S = (160 / (2 * TN + TMT)) & ~1;    // stages in the ring: what 160 KiB of LDS holds (even: fragments alternate between two register sets)
-  constexpr int XHI = (TMT + 7) / 8, XLO = TMT / 8; // row tiles a wave requests per stage: wave, wave+8, ... below TMT
-  constexpr int LHI = 1 + XHI, LLO = 1 + XLO;       // requests per stage of the waves below TMT % 8 / of the others
+  constexpr int XHI = (TMT + 7) / 8;                // row tiles a wave requests per stage at most: wave, wave+8, ...
+  constexpr int LHI = 1 + XHI, LLO = XHI;           // requests per stage of a wave whose last row tile is in use / is not
   static_assert((S - 1) * LHI < 64, "the load counter has six bits");
   __shared__ u32x4 ring[S][STAGE];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, rq = wave >> 1, nh = wave & 1;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);      // the same number, known to be uniform
+  const int rq = wave_s >> 1, nh = wave_s & 1;
+  const int rqv = wave >> 1, nhv = wave & 1;                    // the same again from the vector register: one address register
+                                                                // serves all LDS reads, the slots being constant offsets from it
   const int nt0 = blockIdx.x * (2 * TN) + nh * TN;              // first weight tile of this wave
-  const int mt0 = rq * TMW;                                     // first row tile of this wave
+  // Row tiles of this wave: TMW in a row when all of them hold rows (FULL: the guards below fold away), else
+  // rq, rq+4, ..., so that the tiles past the last row, which are neither requested nor multiplied, are spread
+  // over the four wave pairs.  The launcher picks the smallest TMT that holds the rows, so the unused tiles are
+  // among the last eight.
+  constexpr int MT_STEP = FULL ? 1 : 4;                         // tile of accumulator mt: mt_first + mt * MT_STEP
+  const int mt_first = FULL ? rq * TMW : rq;
+  const int mt_used = FULL ? TMT : (M + 15) >> 4;
   const int kt0 = blockIdx.y * per, kt1 = min(ktiles, kt0 + per);
   if (kt0 >= kt1) return;                                       // whole workgroup (never with the launcher's shapes)
   const int last = kt1 - 1;
@@ -428,8 +439,8 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   // for a recent request without draining all its older ones)
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
-  const int wave_s = __builtin_amdgcn_readfirstlane(wave);      // the same number, known to be uniform
-  const bool two = wave_s + 8 * XLO < TMT;          // this wave has XHI row tiles, not XLO
+  // this wave's last row tile holds rows: XHI requests per stage, else one less
+  const bool hi = (FULL && TMT % 8 == 0) || wave_s + 8 * (XHI - 1) < mt_used;
   // LDS byte address of this wave's weight tile in stage 0 as a scalar: every request's LDS address is this plus a
   // constant, so none of them occupies a vector register (measured: 3-4 % at 24 and 32 row tiles)
   const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)&ring[0][0]) + 1024u * wave_s;
@@ -440,24 +451,24 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   do {                                                                                                        \
     const size_t k_ = (size_t)min(kt_, last) * 64;                                                            \
     __builtin_amdgcn_global_load_lds((gptr_t)(wsrc + k_), ROWS_LDS(slot_, 0), 16, 0, 2);                          \
-    _Pragma("unroll") for (int j = 0; j < XLO; ++j)                                                           \
+    _Pragma("unroll") for (int j = 0; j < XHI - 1; ++j)                                                       \
       __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + (size_t)(8 * j) * ktiles * 64 + k_),                   \
                                        ROWS_LDS(slot_, 2 * TN + 8 * j), 16, 0, 0);                            \
-    if (XHI > XLO && two)                                                                                     \
-      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + (size_t)(8 * XLO) * ktiles * 64 + k_),                 \
-                                       ROWS_LDS(slot_, 2 * TN + 8 * XLO), 16, 0, 0);                          \
+    if (hi)                                                                                                   \
+      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + (size_t)(8 * (XHI - 1)) * ktiles * 64 + k_),           \
+                                       ROWS_LDS(slot_, 2 * TN + 8 * (XHI - 1)), 16, 0, 0);                    \
   } while (0)
 #define ROWS_WAIT(stages_)                                                                                    \
   do {                                                                                                        \
-    if (LHI == LLO || two) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * LHI));                     \
+    if (hi) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * LHI));                                    \
     else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * LLO));                                       \
   } while (0)
 #define ROWS_READ(buf_, slot_)                                                                               \
   do {                                                                                                        \
-    const u32x4* wl_ = &ring[slot_][(nh * TN) * 64 + lane];                                                   \
-    const u32x4* xl_ = &ring[slot_][(2 * TN + mt0) * 64 + lane];                                              \
+    const u32x4* wl_ = &ring[slot_][(nhv * TN) * 64 + lane];                                                  \
+    const u32x4* xl_ = &ring[slot_][(2 * TN + (FULL ? rqv * TMW : rqv)) * 64 + lane];                         \
     _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) wf[buf_][tn] = wl_[tn * 64];                            \
-    _Pragma("unroll") for (int mt = 0; mt < TMW; ++mt) xf[buf_][mt] = xl_[mt * 64];                           \
+    _Pragma("unroll") for (int mt = 0; mt < TMW; ++mt) xf[buf_][mt] = xl_[mt * MT_STEP * 64];                 \
   } while (0)
   u32x4 wf[2][TN], xf[2][TMW];      // fragments of the k-tile being multiplied and of the next one
 #pragma unroll
@@ -476,14 +487,14 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
     __builtin_amdgcn_s_barrier();                                                                             \
     const int cb_ = (u_) & 1, nb_ = cb_ ^ 1, ns_ = ((u_) + 1) % S;                                            \
     ROWS_REQUEST(((u_) + S - 1) % S, kt + (u_) + S - 1);                                                      \
-    const u32x4* wl_ = &ring[ns_][(nh * TN) * 64 + lane];                                                     \
-    const u32x4* xl_ = &ring[ns_][(2 * TN + mt0) * 64 + lane];                                                \
+    const u32x4* wl_ = &ring[ns_][(nhv * TN) * 64 + lane];                                                    \
+    const u32x4* xl_ = &ring[ns_][(2 * TN + (FULL ? rqv * TMW : rqv)) * 64 + lane];                           \
     const bool on_ = !(guard_) || kt + (u_) < kt1;                                                            \
     __builtin_amdgcn_sched_barrier(0);                                                                        \
     _Pragma("unroll") for (int mt = 0; mt < TMW; ++mt) {                                                      \
       _Pragma("unroll") for (int tn = mt * TN / TMW; tn < (mt + 1) * TN / TMW; ++tn) wf[nb_][tn] = wl_[tn * 64]; \
-      xf[nb_][mt] = xl_[mt * 64];                                                                             \
-      if (on_) {                                                                                              \
+      xf[nb_][mt] = xl_[mt * MT_STEP * 64];                                                                   \
+      if (on_ && (FULL || 4 * mt + 11 < TMT || rq + 4 * mt < mt_used)) {                                      \
         _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = mfma16(wf[cb_][tn], xf[cb_][mt], acc[tn][mt]); \
       }                                                                                                       \
       __builtin_amdgcn_sched_barrier(0);                                                                      \
@@ -517,7 +528,8 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
       if (nt0 + tn >= ntiles) continue;
 #pragma unroll
       for (int mt = 0; mt < TMW; ++mt)
-        if ((mt0 + mt) * 16 < M) __builtin_nontemporal_store(acc[tn][mt], pp + ((size_t)(nt0 + tn) * TMT + mt0 + mt) * 64);
+        if (mt_first + mt * MT_STEP < mt_used)
+          __builtin_nontemporal_store(acc[tn][mt], pp + ((size_t)(nt0 + tn) * TMT + mt_first + mt * MT_STEP) * 64);
     }
     return;
   }
@@ -528,8 +540,8 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
     const int task = nt / NB;
 #pragma unroll
     for (int mt = 0; mt < TMW; ++mt) {
-      const int m = (mt0 + mt) * 16 + mc;
-      if ((mt0 + mt) * 16 >= M) continue;
+      const int m = (mt_first + mt * MT_STEP) * 16 + mc;
+      if (mt_first + mt * MT_STEP >= mt_used) continue;
       const float sc = out.nin.inv_rms ? out.nin.inv_rms[min(m, M - 1)] : 1.0f;
       EpiPre pre;
       epi_prefetch<EPI>(pre, out, task, row0 + m, m < M, lane);
@@ -606,12 +618,20 @@ static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles
   const int ks = rows_ksplit(ntiles, ktiles), per = ceil_div(ktiles, ks);
   dim3 grid(ceil_div(ntiles, 2 * EE_ROWS_TN), ceil_div(ktiles, per)), blk(512), rblk(256);
   const int ksr = grid.y;
+  // every row tile holds rows; with 32 row tiles the kernel has no register to spare for the other variant
+  const bool full = M > TMT * 16 - 16 || TMT == 32;
+#define ROWS_LAUNCH(E_)                                                                                                          \
+  do {                                                                                                                           \
+    if (full) hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, true>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
+    else hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, TMT == 32>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
+  } while (0)
   switch (epi) {
-    case EPI_ADD: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ADD>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_SWIGLU>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); break;
-    case EPI_ROPE: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ROPE>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); break;
-    default: hipLaunchKernelGGL((gemm_rows_kernel<TMT, EPI_ARGMAX>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); break;
+    case EPI_ADD: ROWS_LAUNCH(EPI_ADD); break;
+    case EPI_SWIGLU: ROWS_LAUNCH(EPI_SWIGLU); break;
+    case EPI_ROPE: ROWS_LAUNCH(EPI_ROPE); break;
+    default: ROWS_LAUNCH(EPI_ARGMAX); break;
   }
+#undef ROWS_LAUNCH
   if (ksr > 1) {
     const int nb = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? 2 : 1;
     const int units = (ntiles / nb) * ceil_div(M, 16);
@@ -1133,7 +1153,7 @@ int bf16_attention_pages_per_split(const int* kv_end, const int* seq_m, int B, i
   const int rep = Hq / Hkv;
   int max_pages = 1;
   for (int b = 0; b < B; ++b) max_pages = max(max_pages, ceil_div(kv_end[b], EE_PAGE));
-  int per = max(4, ceil_div(max_pages, max(1, min(max_splits, EE_MAX_SPLITS))));
+  int per = max(2, ceil_div(max_pages, max(1, min(max_splits, EE_MAX_SPLITS))));
   for (; per < max_pages; ++per) {
     long wgs = 0;
     for (int b = 0; b < B; ++b)
