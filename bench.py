@@ -29,6 +29,7 @@ if ROOT not in sys.path:
 import synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0        # dense bf16
 MODEL_SEED = 20251001
 
 # HBM traffic of one gate/up GEMM launch (8b_b1_ctx2048_k8) measured with two rocprofv3 --pmc runs
@@ -199,7 +200,36 @@ def build_workload(name, seed=MODEL_SEED, bonus_full=1):
     for b in range(batch):
         sess.rollback(b, all_groups, ctxs[b])
     return dict(cfg=cfg, model=model, sess=sess, batch=batch, ctxs=ctxs, k=k, p=p, drafts=blocks[0], blocks=blocks, rounds=R,
-                name=name, bonus_full=bonus_full)
+                name=name, bonus_full=bonus_full, prompts=prompts)
+
+
+def context_build(w):
+    """The context build (ee_prefill) of the same prompts again, after the timed steps: the path's MFMA-bound shapes
+    (passes of 512 packed rows through all layers).  Wall time of the whole call, and the gate/up GEMM launches by HIP
+    events against the dense bf16 MFMA peak (flop = 2 x rows x 2 d_ffn x d_model per layer; every row of every prompt;
+    the events of a launch also span the small kernel that reduces the deferred RMSNorm factors before it)."""
+    import torch
+    sess, cfg = w["sess"], w["cfg"]
+    tokens = int(sum(w["ctxs"]))
+    for b in range(w["batch"]):
+        sess.release(b)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sess.prefill(w["prompts"])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for b in range(w["batch"]):
+        sess.release(b)
+    sess.time_kernels(True)
+    sess.prefill(w["prompts"])
+    times = sess.kernel_times()
+    sess.time_kernels(False)
+    gu_ms, gu_n = times["gemm_gate_up"]
+    flop = 2.0 * tokens * 2 * cfg.d_ffn * cfg.d_model * cfg.n_layers
+    tflops = flop / (gu_ms * 1e-3) / 1e12
+    return {"tokens": tokens, "ms": 1e3 * wall, "tokens_per_s": tokens / wall,
+            "gate_up_gemm": {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": tflops / MFMA_PEAK_TFLOPS, "launches": gu_n, "avg_launch_us": 1e3 * gu_ms / gu_n}}
 
 
 def one_step(w, collect=None, wall=None):
@@ -386,6 +416,7 @@ def main():
         "step_bytes": sb, "step_hbm_frac": sb / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms_per_step": kernel_ms,
     }
+    out["context_build"] = context_build(w)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
