@@ -255,6 +255,12 @@ int ee_debug_time_kernels(ee_session* s, int on);
 int ee_debug_kernel_times(ee_session* s, int32_t* n_families, const char** names /*[16]*/,
                           float* ms /*[16]*/, int32_t* launches /*[16]*/);
 
+/* Test and tuning support, process-wide: the row-tiled GEMM (calls of more than 16 rows) serves the narrow
+ * projections (O, down, QKV, adapters) either with K shares and a reduction pass or with blocks of row_tiles*16
+ * rows and no K shares; row_tiles = 4, 8 or 16 forces the second form for every such call, 0 the first, -1 restores
+ * the built-in choice.  Results agree to rounding order.  EE_ERR_ARG for any other value. */
+int ee_debug_gemm_row_blocks(int row_tiles);
+
 /* Plain device-to-device streaming copy on `stream` (pointers and size multiples of 16 bytes; not
  * synchronised).  A kernel of exactly known traffic -- `bytes` read, `bytes` written -- used to
  * calibrate hardware byte counters when the HBM traffic of the other kernels is measured. */

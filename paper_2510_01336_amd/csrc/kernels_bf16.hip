@@ -396,19 +396,22 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
 // s_waitcnt immediate: at most n vector-memory loads outstanding, all LDS reads done, export counter untouched
 __host__ __device__ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
-template <int TMT, int EPI, bool FULL>
+template <int TMT, int EPI, bool FULL, int TN>
 __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict__ W, int ktiles, int ntiles,
-                                                        const uint4* __restrict__ A, int row0, int M, int N, GemmOut out,
+                                                        const uint4* __restrict__ A, int row0, int M_all, int N, GemmOut out,
                                                         int per, float* __restrict__ partial) {
-  // rows row0 .. row0+M-1 of the operand (row0 a multiple of 16); the deferred-norm factors and the K-share
-  // partials are indexed from the block's first row, everything the epilogue touches by the row itself
-  constexpr int TN = EE_ROWS_TN, NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
+  // rows row0 .. row0+M_all-1 of the operand (row0 a multiple of 16), of which this workgroup takes the block of
+  // TMT*16 rows that blockIdx.z names; the deferred-norm factors and the K-share partials are indexed from row0,
+  // everything the epilogue touches by the row itself
+  constexpr int NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
+  static_assert(TN == 2 || TN == 4, "weight tiles per wave");
+  const int rbase = blockIdx.z * (TMT * 16), M = min(M_all - rbase, TMT * 16);
   constexpr int TMW = TMT / 4;                      // row tiles per wave
   static_assert(TMT % 4 == 0 && TMT >= 4 && TMT <= 32, "row tiles split four ways");
   constexpr int STAGE = (2 * TN + TMT) * 64;        // 16-byte units: weight tiles first, then row tiles
   constexpr int S = (160 / (2 * TN + TMT)) & ~1;    // stages in the ring: what 160 KiB of LDS holds (even: fragments alternate between two register sets)
   constexpr int XHI = (TMT + 7) / 8;                // row tiles a wave requests per stage at most: wave, wave+8, ...
-  constexpr int LHI = 1 + XHI, LLO = XHI;           // requests per stage of a wave whose last row tile is in use / is not
+  constexpr int LHI = 1 + XHI;                      // requests per stage at most: a weight tile and XHI row tiles
   static_assert((S - 1) * LHI < 64, "the load counter has six bits");
   __shared__ u32x4 ring[S][STAGE];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -439,18 +442,20 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   // for a recent request without draining all its older ones)
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
-  // this wave's last row tile holds rows: XHI requests per stage, else one less
+  // this wave's last row tile holds rows: XHI requests per stage, else one less; with four weight tiles per
+  // workgroup (TN = 2) only the first four waves request one
   const bool hi = (FULL && TMT % 8 == 0) || wave_s + 8 * (XHI - 1) < mt_used;
+  const bool wreq = TN == 4 || wave_s < 2 * TN;
   // LDS byte address of this wave's weight tile in stage 0 as a scalar: every request's LDS address is this plus a
   // constant, so none of them occupies a vector register (measured: 3-4 % at 24 and 32 row tiles)
   const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)&ring[0][0]) + 1024u * wave_s;
 #define ROWS_LDS(slot_, tile_) ((lptr_t)(size_t)(lds0 + 16u * ((slot_) * STAGE + (tile_) * 64)))
   const u32x4* wsrc = (const u32x4*)W + (size_t)min(blockIdx.x * (2 * TN) + wave, ntiles - 1) * ktiles * 64 + lane;
-  const u32x4* xsrc = (const u32x4*)A + (size_t)((row0 >> 4) + wave) * ktiles * 64 + lane;
+  const u32x4* xsrc = (const u32x4*)A + (size_t)(((row0 + rbase) >> 4) + wave) * ktiles * 64 + lane;
 #define ROWS_REQUEST(slot_, kt_)                                                                              \
   do {                                                                                                        \
     const size_t k_ = (size_t)min(kt_, last) * 64;                                                            \
-    __builtin_amdgcn_global_load_lds((gptr_t)(wsrc + k_), ROWS_LDS(slot_, 0), 16, 0, 2);                          \
+    if (wreq) __builtin_amdgcn_global_load_lds((gptr_t)(wsrc + k_), ROWS_LDS(slot_, 0), 16, 0, 2);                \
     _Pragma("unroll") for (int j = 0; j < XHI - 1; ++j)                                                       \
       __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + (size_t)(8 * j) * ktiles * 64 + k_),                   \
                                        ROWS_LDS(slot_, 2 * TN + 8 * j), 16, 0, 0);                            \
@@ -460,8 +465,9 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   } while (0)
 #define ROWS_WAIT(stages_)                                                                                    \
   do {                                                                                                        \
-    if (hi) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * LHI));                                    \
-    else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * LLO));                                       \
+    if (wreq && hi) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * LHI));                            \
+    else if (wreq || hi) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * (LHI - 1)));                 \
+    else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * (LHI - 2)));                                 \
   } while (0)
 #define ROWS_READ(buf_, slot_)                                                                               \
   do {                                                                                                        \
@@ -542,10 +548,10 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
     for (int mt = 0; mt < TMW; ++mt) {
       const int m = (mt_first + mt * MT_STEP) * 16 + mc;
       if (mt_first + mt * MT_STEP >= mt_used) continue;
-      const float sc = out.nin.inv_rms ? out.nin.inv_rms[min(m, M - 1)] : 1.0f;
+      const float sc = out.nin.inv_rms ? out.nin.inv_rms[rbase + min(m, M - 1)] : 1.0f;
       EpiPre pre;
-      epi_prefetch<EPI>(pre, out, task, row0 + m, m < M, lane);
-      epi_apply<EPI>(acc[t * NB][mt], acc[t * NB + NB - 1][mt], sc, pre, out, task, row0 + m, m < M, N, lane);
+      epi_prefetch<EPI>(pre, out, task, row0 + rbase + m, m < M, lane);
+      epi_apply<EPI>(acc[t * NB][mt], acc[t * NB + NB - 1][mt], sc, pre, out, task, row0 + rbase + m, m < M, N, lane);
     }
   }
 }
@@ -622,8 +628,8 @@ static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles
   const bool full = M > TMT * 16 - 16 || TMT == 32;
 #define ROWS_LAUNCH(E_)                                                                                                          \
   do {                                                                                                                           \
-    if (full) hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, true>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
-    else hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, TMT == 32>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
+    if (full) hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, true, EE_ROWS_TN>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
+    else hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, TMT == 32, EE_ROWS_TN>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
   } while (0)
   switch (epi) {
     case EPI_ADD: ROWS_LAUNCH(EPI_ADD); break;
@@ -645,6 +651,40 @@ static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles
   }
 }
 
+// Narrow matrices (few workgroup columns) without K shares: four weight tiles per workgroup and the rows cut into
+// blocks of TMT*16 (grid.z), so that columns x blocks fill the chip and no partial tiles go through memory.
+// Only the epilogues of the narrow projections are instantiated (O, down, adapters: residual add; QKV: RoPE).
+template <int TMT>
+static bool launch_gemm_rows_blocks(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int row0, int M,
+                                    int N, const GemmOut& out) {
+  if (epi != EPI_ADD && epi != EPI_ROPE) return false;
+  dim3 grid(ceil_div(ntiles, 4), 1, ceil_div(M, TMT * 16)), blk(512);
+  const bool full = M % (TMT * 16) == 0;
+#define ROWS_LAUNCH(E_)                                                                                                          \
+  do {                                                                                                                           \
+    if (full) hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, true, 2>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, nullptr); \
+    else hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, false, 2>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, nullptr);    \
+  } while (0)
+  if (epi == EPI_ADD) ROWS_LAUNCH(EPI_ADD);
+  else ROWS_LAUNCH(EPI_ROPE);
+#undef ROWS_LAUNCH
+  return true;
+}
+
+// row tiles per block of the launch above for a call of M rows, 0: use the K-share kernel (wide matrices, and shapes
+// where it measured faster)
+int g_rows_blocks_override = -1;   // test and tuning hook: >= 0 replaces the choice below
+static int rows_blocks_tmt(int ntiles, int ktiles, int M) {
+  if (g_rows_blocks_override >= 0) return g_rows_blocks_override;
+  // measured on the 8B shapes (N 4096 and 6144): the blocks win for K <= 4096 from about 200 rows when columns x
+  // blocks fit one round of workgroups; with K 14336 the K shares win at every row count
+  if (rows_ksplit(ntiles, ktiles) == 1 || ktiles > 128 || M <= 192) return 0;
+  const int cols = ceil_div(ntiles, 4);
+  for (int t = 4; t <= 16; t *= 2)
+    if (cols * ceil_div(M, 16 * t) <= 256) return (t == 16 && M <= 400) ? 0 : t;
+  return 0;
+}
+
 // more than 16 rows from row 0 of the operand; out.nin.ssq, if set, is first reduced to per-row factors (per block)
 void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                     const GemmOut& out0, float* scratch, float* inv_rms) {
@@ -660,6 +700,10 @@ void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kt
                          out.nin.inv_d, out.nin.eps, inv_rms, mc);
       out.nin.inv_rms = inv_rms;
     }
+    const int bt = rows_blocks_tmt(ntiles, ktiles, mc);
+    if (bt == 4 && launch_gemm_rows_blocks<4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
+    if (bt == 8 && launch_gemm_rows_blocks<8>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
+    if (bt == 16 && launch_gemm_rows_blocks<16>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
     if (mc <= 64) launch_gemm_rows<4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
     else if (mc <= 128) launch_gemm_rows<8>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
     else if (mc <= 192) launch_gemm_rows<12>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);

@@ -1198,6 +1198,15 @@ extern "C" int ee_debug_poison_dead_kv(ee_session* s, int seq) {
   HIP_TRY(hipStreamSynchronize(s->st));
   return EE_OK;
 }
+extern "C" int ee_debug_gemm_row_blocks(int row_tiles) {
+  if (row_tiles != -1 && row_tiles != 0 && row_tiles != 4 && row_tiles != 8 && row_tiles != 16) {
+    ee_set_error("row_tiles must be -1, 0, 4, 8 or 16");
+    return EE_ERR_ARG;
+  }
+  g_rows_blocks_override = row_tiles;
+  return EE_OK;
+}
+
 extern "C" int ee_debug_time_kernels(ee_session* s, int on) {
   if (!s) { ee_set_error("null session"); return EE_ERR_ARG; }
   s->time_kernels = on != 0;
