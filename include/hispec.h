@@ -257,8 +257,9 @@ int ee_debug_kernel_times(ee_session* s, int32_t* n_families, const char** names
 
 /* Test and tuning support, process-wide: the row-tiled GEMM (calls of more than 16 rows) serves the narrow
  * projections (O, down, QKV, adapters) either with K shares and a reduction pass or with blocks of row_tiles*16
- * rows and no K shares; row_tiles = 4, 8 or 16 forces the second form for every such call, 0 the first, -1 restores
- * the built-in choice.  Results agree to rounding order.  EE_ERR_ARG for any other value. */
+ * rows and no K shares; row_tiles = 4, 8 or 16 forces the second form for every such call (104 and 108: blocks of 4
+ * and 8 row tiles with eight instead of four weight tiles per workgroup), 0 the first, -1 restores the built-in
+ * choice.  Results agree to rounding order.  EE_ERR_ARG for any other value. */
 int ee_debug_gemm_row_blocks(int row_tiles);
 
 /* Plain device-to-device streaming copy on `stream` (pointers and size multiples of 16 bytes; not

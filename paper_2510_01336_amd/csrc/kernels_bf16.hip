@@ -654,16 +654,16 @@ static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles
 // Narrow matrices (few workgroup columns) without K shares: four weight tiles per workgroup and the rows cut into
 // blocks of TMT*16 (grid.z), so that columns x blocks fill the chip and no partial tiles go through memory.
 // Only the epilogues of the narrow projections are instantiated (O, down, adapters: residual add; QKV: RoPE).
-template <int TMT>
+template <int TMT, int TN>
 static bool launch_gemm_rows_blocks(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int row0, int M,
                                     int N, const GemmOut& out) {
   if (epi != EPI_ADD && epi != EPI_ROPE) return false;
-  dim3 grid(ceil_div(ntiles, 4), 1, ceil_div(M, TMT * 16)), blk(512);
+  dim3 grid(ceil_div(ntiles, 2 * TN), 1, ceil_div(M, TMT * 16)), blk(512);
   const bool full = M % (TMT * 16) == 0;
 #define ROWS_LAUNCH(E_)                                                                                                          \
   do {                                                                                                                           \
-    if (full) hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, true, 2>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, nullptr); \
-    else hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, false, 2>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, nullptr);    \
+    if (full) hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, true, TN>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, nullptr); \
+    else hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, false, TN>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, nullptr);    \
   } while (0)
   if (epi == EPI_ADD) ROWS_LAUNCH(EPI_ADD);
   else ROWS_LAUNCH(EPI_ROPE);
@@ -671,17 +671,18 @@ static bool launch_gemm_rows_blocks(hipStream_t st, int epi, const uint4* W, int
   return true;
 }
 
-// row tiles per block of the launch above for a call of M rows, 0: use the K-share kernel (wide matrices, and shapes
-// where it measured faster)
+// Form of the launch above for a call of M rows: row tiles per block, plus 100 with eight weight tiles per workgroup
+// (TN = 4) instead of four; 0: use the K-share kernel (wide matrices, and shapes where it measured faster).
 int g_rows_blocks_override = -1;   // test and tuning hook: >= 0 replaces the choice below
-static int rows_blocks_tmt(int ntiles, int ktiles, int M) {
+static int rows_blocks_form(int ntiles, int ktiles, int M) {
   if (g_rows_blocks_override >= 0) return g_rows_blocks_override;
   // measured on the 8B shapes (N 4096 and 6144): the blocks win for K <= 4096 from about 200 rows when columns x
-  // blocks fit one round of workgroups; with K 14336 the K shares win at every row count
+  // blocks fit one round of workgroups; with K 14336 the K shares win at every row count.  Among the forms that
+  // fit, the one with the cheapest k-tile step per workgroup (request time + MFMA time, in clocks) is taken.
   if (rows_ksplit(ntiles, ktiles) == 1 || ktiles > 128 || M <= 192) return 0;
-  const int cols = ceil_div(ntiles, 4);
-  for (int t = 4; t <= 16; t *= 2)
-    if (cols * ceil_div(M, 16 * t) <= 256) return (t == 16 && M <= 400) ? 0 : t;
+  static const int forms[5][3] = {{2, 4, 192}, {2, 8, 320}, {4, 4, 320}, {4, 8, 512}, {2, 16, 576}};   // TN, TMT, clocks
+  for (const auto& f : forms)
+    if (ceil_div(ntiles, 2 * f[0]) * ceil_div(M, 16 * f[1]) <= 256) return (f[0] == 4 ? 100 : 0) + f[1];
   return 0;
 }
 
@@ -700,10 +701,12 @@ void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kt
                          out.nin.inv_d, out.nin.eps, inv_rms, mc);
       out.nin.inv_rms = inv_rms;
     }
-    const int bt = rows_blocks_tmt(ntiles, ktiles, mc);
-    if (bt == 4 && launch_gemm_rows_blocks<4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
-    if (bt == 8 && launch_gemm_rows_blocks<8>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
-    if (bt == 16 && launch_gemm_rows_blocks<16>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
+    const int bt = rows_blocks_form(ntiles, ktiles, mc);
+    if (bt == 4 && launch_gemm_rows_blocks<4, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
+    if (bt == 8 && launch_gemm_rows_blocks<8, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
+    if (bt == 16 && launch_gemm_rows_blocks<16, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
+    if (bt == 104 && launch_gemm_rows_blocks<4, 4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
+    if (bt == 108 && launch_gemm_rows_blocks<8, 4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;
     if (mc <= 64) launch_gemm_rows<4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
     else if (mc <= 128) launch_gemm_rows<8>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);
     else if (mc <= 192) launch_gemm_rows<12>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, scratch);

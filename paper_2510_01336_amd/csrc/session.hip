@@ -1199,8 +1199,8 @@ extern "C" int ee_debug_poison_dead_kv(ee_session* s, int seq) {
   return EE_OK;
 }
 extern "C" int ee_debug_gemm_row_blocks(int row_tiles) {
-  if (row_tiles != -1 && row_tiles != 0 && row_tiles != 4 && row_tiles != 8 && row_tiles != 16) {
-    ee_set_error("row_tiles must be -1, 0, 4, 8 or 16");
+  if (row_tiles != -1 && row_tiles != 0 && row_tiles != 4 && row_tiles != 8 && row_tiles != 16 && row_tiles != 104 && row_tiles != 108) {
+    ee_set_error("row_tiles must be -1, 0, 4, 8, 16, 104 or 108");
     return EE_ERR_ARG;
   }
   g_rows_blocks_override = row_tiles;
