@@ -9,7 +9,8 @@ Metric: verified draft tokens per second = batch * k * steps / elapsed.
 
 Prints ONE JSON line.  `roofline` describes the dominant kernel (the gate/up weight-streaming
 GEMM): algorithmic bytes per launch / its mean launch duration, measured with HIP events on the
-library's stream in a second, instrumented pass over the same steps.  `cpu_baseline` is the
+library's stream in a second, instrumented pass over the same steps (for a weight-streaming GEMM launch the
+events are attached to the dispatch itself and hold the kernel's own start and end).  `cpu_baseline` is the
 numpy oracle timed on this machine's host cores on a bounded sample of the same workload.
 """
 from __future__ import annotations

@@ -70,6 +70,11 @@ void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kti
 // Row-tiled variant for 16 < M <= 512 rows (rows start at row 0 of the operand; the kernel reads whole row
 // tiles up to the next of 64, 128, 192, 256, 384, 512 rows, which the operand buffer must hold).  scratch: bf16_gemm_rows_scratch_floats() floats for
 // this shape (may be null when that is 0); inv_rms: M floats of scratch for the deferred RMSNorm factors.
+// Launch timing: while this points to a pair of events, the next skinny-GEMM launch attaches them to the dispatch
+// itself (hipExtLaunchKernelGGL), so that they hold the kernel's own start and end rather than the times at which
+// two marker packets around it were processed; the launcher sets `used`.
+struct LaunchEvents { hipEvent_t start, stop; bool used; };
+extern LaunchEvents* g_launch_events;
 extern int g_rows_blocks_override;   // -1: built-in choice between K shares and row blocks; else 0, or row tiles per block (+100: eight weight tiles per workgroup)
 size_t bf16_gemm_rows_scratch_floats(int ntiles, int ktiles);
 void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,

@@ -9,6 +9,7 @@
 // wavefront fetches an operand tile as one fully coalesced 1 KiB load straight into registers; no
 // LDS staging or transposition is needed anywhere on the streaming path.
 #include "kernels.h"
+#include <hip/hip_ext.h>
 #include <cmath>
 #include <type_traits>
 
@@ -673,6 +674,7 @@ static bool launch_gemm_rows_blocks(hipStream_t st, int epi, const uint4* W, int
 
 // Form of the launch above for a call of M rows: row tiles per block, plus 100 with eight weight tiles per workgroup
 // (TN = 4) instead of four; 0: use the K-share kernel (wide matrices, and shapes where it measured faster).
+LaunchEvents* g_launch_events = nullptr;
 int g_rows_blocks_override = -1;   // test and tuning hook: >= 0 replaces the choice below
 static int rows_blocks_form(int ntiles, int ktiles, int M) {
   if (g_rows_blocks_override >= 0) return g_rows_blocks_override;
@@ -723,12 +725,25 @@ static void launch_gemm_mt(hipStream_t st, int epi, const uint4* W, int ntiles, 
   const int tpw = nw / ksplit;
   const int ntasks = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? ntiles / 2 : ntiles;
   dim3 grid(ceil_div(ntasks, tpw));
+  LaunchEvents* ev = g_launch_events;
+  g_launch_events = nullptr;                       // one launch per offer
+#define SKINNY_LAUNCH(E_)                                                                                                        \
+  do {                                                                                                                           \
+    if (ev) {                                                                                                                    \
+      hipExtLaunchKernelGGL((gemm_skinny_kernel<MT, E_, U>), grid, blk, 0, st, ev->start, ev->stop, 0, W, ktiles, ntasks, A, row0, M, N, \
+                            out, ksplit);                                                                                        \
+      ev->used = true;                                                                                                           \
+    } else {                                                                                                                     \
+      hipLaunchKernelGGL((gemm_skinny_kernel<MT, E_, U>), grid, blk, 0, st, W, ktiles, ntasks, A, row0, M, N, out, ksplit);      \
+    }                                                                                                                            \
+  } while (0)
   switch (epi) {
-    case EPI_ADD: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ADD, U>), grid, blk, 0, st, W, ktiles, ntasks, A, row0, M, N, out, ksplit); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_SWIGLU, U>), grid, blk, 0, st, W, ktiles, ntasks, A, row0, M, N, out, ksplit); break;
-    case EPI_ROPE: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ROPE, U>), grid, blk, 0, st, W, ktiles, ntasks, A, row0, M, N, out, ksplit); break;
-    default: hipLaunchKernelGGL((gemm_skinny_kernel<MT, EPI_ARGMAX, U>), grid, blk, 0, st, W, ktiles, ntasks, A, row0, M, N, out, ksplit); break;
+    case EPI_ADD: SKINNY_LAUNCH(EPI_ADD); break;
+    case EPI_SWIGLU: SKINNY_LAUNCH(EPI_SWIGLU); break;
+    case EPI_ROPE: SKINNY_LAUNCH(EPI_ROPE); break;
+    default: SKINNY_LAUNCH(EPI_ARGMAX); break;
   }
+#undef SKINNY_LAUNCH
 }
 
 // launch shape: nw waves per workgroup, ksplit of them per task, register pipeline depth U (2, 4 or 8)

@@ -329,16 +329,31 @@ static int upload_meta(ee_session* s, int si) {
 // ---------------------------------------------------------------------------------------------
 // launch accounting
 // ---------------------------------------------------------------------------------------------
+// With timing on, a family call is bracketed by two recorded events; a call that is one skinny-GEMM launch takes
+// the second pair instead, attached to its dispatch (the kernel's own start and end: what a kernel trace reports,
+// 2-5 us less than the bracket, which also spans the launch gap).
 struct Scope {
   ee_session* s; int fam; hipEvent_t a = nullptr, b = nullptr;
+  LaunchEvents own{nullptr, nullptr, false};
   Scope(ee_session* s_, int f) : s(s_), fam(f) {
     s->launches[fam]++;
     if (s->time_kernels) {
       (void)hipEventCreate(&a); (void)hipEventCreate(&b); (void)hipEventRecord(a, s->st);
+      (void)hipEventCreate(&own.start); (void)hipEventCreate(&own.stop);
+      g_launch_events = &own;
     }
   }
   ~Scope() {
-    if (a) { (void)hipEventRecord(b, s->st); s->timers.push_back({fam, a, b}); }
+    if (!a) return;
+    g_launch_events = nullptr;
+    if (own.used) {
+      s->timers.push_back({fam, own.start, own.stop});
+      (void)hipEventDestroy(a); (void)hipEventDestroy(b);
+    } else {
+      (void)hipEventRecord(b, s->st);
+      s->timers.push_back({fam, a, b});
+      (void)hipEventDestroy(own.start); (void)hipEventDestroy(own.stop);
+    }
   }
 };
 #define KF(fam, call) do { Scope sc_(s, fam); call; } while (0)
