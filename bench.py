@@ -234,8 +234,8 @@ def build_workload(name, seed=MODEL_SEED, bonus_full=1):
 def context_build(w):
     """The context build (ee_prefill) of the same prompts again, after the timed steps: the path's MFMA-bound shapes
     (passes of 512 packed rows through all layers).  Wall time of the whole call, and the gate/up GEMM launches by HIP
-    events against the dense bf16 MFMA peak (flop = 2 x rows x 2 d_ffn x d_model per layer; every row of every prompt;
-    the events of a launch also span the small kernel that reduces the deferred RMSNorm factors before it)."""
+    events attached to each dispatch against the dense bf16 MFMA peak (flop = 2 x rows x 2 d_ffn x d_model per layer;
+    every row of every prompt)."""
     import torch
     sess, cfg = w["sess"], w["cfg"]
     tokens = int(sum(w["ctxs"]))

@@ -619,6 +619,17 @@ size_t bf16_gemm_rows_scratch_floats(int ntiles, int ktiles) {
   return ks > 1 ? (size_t)ks * ntiles * 32 * 256 : 0;       // [k share][weight tile][up to 32 row tiles][64 lanes x 4]
 }
 
+// plain launch, or with the offered timing events attached to the dispatch
+template <typename K, typename... Args>
+static void launch_timed(LaunchEvents* ev, K kernel, dim3 grid, dim3 blk, hipStream_t st, Args... args) {
+  if (ev) {
+    hipExtLaunchKernelGGL(kernel, grid, blk, 0, st, ev->start, ev->stop, 0, args...);
+    ev->used = true;
+  } else {
+    hipLaunchKernelGGL(kernel, grid, blk, 0, st, args...);
+  }
+}
+
 template <int TMT>
 static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles, int ktiles, const uint4* A, int row0, int M, int N,
                              const GemmOut& out, float* scratch) {
@@ -627,10 +638,13 @@ static void launch_gemm_rows(hipStream_t st, int epi, const uint4* W, int ntiles
   const int ksr = grid.y;
   // every row tile holds rows; with 32 row tiles the kernel has no register to spare for the other variant
   const bool full = M > TMT * 16 - 16 || TMT == 32;
+  // timing events are taken when this one kernel is the whole call (no K shares, hence no reduction pass)
+  LaunchEvents* ev = ksr == 1 ? g_launch_events : nullptr;
+  if (ev) g_launch_events = nullptr;
 #define ROWS_LAUNCH(E_)                                                                                                          \
   do {                                                                                                                           \
-    if (full) hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, true, EE_ROWS_TN>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
-    else hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, TMT == 32, EE_ROWS_TN>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
+    if (full) launch_timed(ev, gemm_rows_kernel<TMT, E_, true, EE_ROWS_TN>, grid, blk, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
+    else launch_timed(ev, gemm_rows_kernel<TMT, E_, TMT == 32, EE_ROWS_TN>, grid, blk, st, W, ktiles, ntiles, A, row0, M, N, out, per, scratch); \
   } while (0)
   switch (epi) {
     case EPI_ADD: ROWS_LAUNCH(EPI_ADD); break;
@@ -661,10 +675,12 @@ static bool launch_gemm_rows_blocks(hipStream_t st, int epi, const uint4* W, int
   if (epi != EPI_ADD && epi != EPI_ROPE) return false;
   dim3 grid(ceil_div(ntiles, 2 * TN), 1, ceil_div(M, TMT * 16)), blk(512);
   const bool full = M % (TMT * 16) == 0;
+  LaunchEvents* ev = g_launch_events;
+  g_launch_events = nullptr;
 #define ROWS_LAUNCH(E_)                                                                                                          \
   do {                                                                                                                           \
-    if (full) hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, true, TN>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, nullptr); \
-    else hipLaunchKernelGGL((gemm_rows_kernel<TMT, E_, false, TN>), grid, blk, 0, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, nullptr);    \
+    if (full) launch_timed(ev, gemm_rows_kernel<TMT, E_, true, TN>, grid, blk, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, (float*)nullptr); \
+    else launch_timed(ev, gemm_rows_kernel<TMT, E_, false, TN>, grid, blk, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, (float*)nullptr);    \
   } while (0)
   if (epi == EPI_ADD) ROWS_LAUNCH(EPI_ADD);
   else ROWS_LAUNCH(EPI_ROPE);
@@ -695,6 +711,7 @@ void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kt
   const uint4* Ac = (const uint4*)A;
   // blocks of up to 512 rows, of equal size up to a row tile: calls beyond 512 rows stream the weights once per block
   const int blk = ceil_div(ceil_div(M, ceil_div(M, 512)), 16) * 16;
+  if (M > blk) g_launch_events = nullptr;           // several launches: the caller's bracket times the call
   for (int m0 = 0; m0 < M; m0 += blk) {
     const int mc = min(blk, M - m0);
     GemmOut out = out0;
