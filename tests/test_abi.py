@@ -88,3 +88,14 @@ def test_config_checks_of_the_optional_model_parts(lib):
         for i, e in enumerate(extra):
             bad.extra_exits[i] = e
         assert lib.ee_model_bytes(ctypes.byref(bad)) == 0 and b"verifier exits" in lib.ee_last_error()
+
+
+def test_gemm_form_selector_checks_its_argument(lib):
+    """The tuning entry point that forces the narrow-projection GEMM form: host state only, no device."""
+    lib.ee_last_error.restype = ctypes.c_char_p
+    for ok in (0, 4, 8, 16, 104, 108, -1):
+        assert lib.ee_debug_gemm_row_blocks(ok) == 0, ok
+    for bad in (1, 12, 32, 100, -2):
+        assert lib.ee_debug_gemm_row_blocks(bad) == -1, bad
+        assert b"row_tiles" in lib.ee_last_error()
+    assert lib.ee_debug_gemm_row_blocks(-1) == 0
