@@ -203,6 +203,26 @@ def gen_flat(cfg: EEConfig, seed: int, name: str, layer: int, e0: int, count: in
 
 _CHUNK = 1 << 20
 _POOL = None
+_FAST = None     # the compiled generator (synth/gen_fast.c), False once found absent
+
+
+def _fast_lib():
+    """The C version of the recipe above, if it has been built (the build entry point compiles it); the numpy
+    version serves otherwise.  Both give the same bits."""
+    global _FAST
+    if _FAST is None:
+        import ctypes
+        import os
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsynthgen.so")
+        try:
+            lib = ctypes.CDLL(path)
+            lib.synth_fill.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_float,
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+            lib.synth_fill.restype = None
+            _FAST = lib
+        except OSError:
+            _FAST = False
+    return _FAST
 
 
 def _pool() -> ThreadPoolExecutor:
@@ -214,12 +234,18 @@ def _pool() -> ThreadPoolExecutor:
 
 
 def gen_tensor_rows(cfg: EEConfig, seed: int, name: str, layer: int,
-                    row0: int, nrows: int) -> np.ndarray:
+                    row0: int, nrows: int, use_fast: bool = True) -> np.ndarray:
     """Rows [row0, row0+nrows) of a 2-D tensor (or elements of a 1-D tensor)."""
     shape = tensor_shape(cfg, name)
     cols = shape[1] if len(shape) == 2 else 1
     e0, count = row0 * cols, nrows * cols
-    if count <= _CHUNK:
+    fast = _fast_lib() if use_fast else False
+    if fast:
+        key = stream_key(seed, TENSOR_IDS[name], layer if name in LAYER_TENSORS + EXIT_TENSORS else 0)
+        flat = np.empty(count, np.float32)
+        fast.synth_fill(key, e0, count, float(tensor_scale(cfg, name, layer)), int(name in GAIN_TENSORS),
+                        int(cfg.dtype == "bf16"), flat.ctypes.data)
+    elif count <= _CHUNK:
         flat = gen_flat(cfg, seed, name, layer, e0, count)
     else:
         starts = list(range(0, count, _CHUNK))

@@ -15,3 +15,13 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Largest errors the GPU parity tests measured against each oracle (figures quoted in the design notes)."""
+    try:
+        from hs_common import STATS
+    except Exception:
+        return
+    if STATS:
+        terminalreporter.write_line("parity maxima: " + ", ".join(f"{k}={v:.3g}" for k, v in sorted(STATS.items())))

@@ -11,7 +11,7 @@ import pytest
 
 import synth
 from oracle import ee_oracle as eo
-from hs_common import MARGIN, TOL, OracleSide, bf16_d128, bf16_small, gpu_side, max_rel
+from hs_common import MARGIN, TOL, OracleSide, bf16_d128, bf16_small, count, gpu_side, max_rel, note
 
 pytestmark = pytest.mark.gpu
 
@@ -59,29 +59,50 @@ def test_set_tensor_roundtrip():
 # ------------------------------------------------------------------------------------------------
 # helpers: one HiSpec round on both sides with margin-filtered inputs
 # ------------------------------------------------------------------------------------------------
-def _trial_round(O, seqs, drafts, do_full):
+def _trial_round(O, seqs, drafts, do_full, decisions=None):
     """Run the round on deep copies of the oracle sequences; return the smallest margin among the
-    rows whose arg max decides an output (rows 0..a of each verify)."""
+    rows whose arg max decides an output (rows 0..a of each verify).  `decisions`, if given, collects
+    what the round decided."""
     worst = np.inf
     for s0, S in zip(seqs, drafts):
         s = copy.deepcopy(s0)
         O.o.draft_inject(s, S)
-        a, _ = O.o.verify_intermediate(s)
+        a, nxt = O.o.verify_intermediate(s)
         m = eo.top2_margin(O.o.last_logits)
         worst = min(worst, m[:min(a + 1, len(m))].min())
+        out = [a, nxt]
         if do_full:
-            f, _, _ = O.o.verify_full(s)
+            f, fn, F = O.o.verify_full(s)
             m = eo.top2_margin(O.o.last_logits)
             worst = min(worst, m[:min(f + 1, len(m))].min())
+            out += [f, fn, list(F)]
+        if decisions is not None:
+            decisions.append(out)
     return worst
+
+
+def _clear(O, b, S, do_full):
+    """The block clears the margin in the oracle -- with a plain twin in both oracles, which must also decide alike."""
+    dec = []
+    if _trial_round(O, [O.seqs[b]], [S], do_full, dec) <= MARGIN:
+        return False
+    if O.P:
+        pdec = []
+        if _trial_round(O.P, [O.P.seqs[b]], [S], do_full, pdec) <= MARGIN:
+            return False
+        if dec != pdec:
+            count("oracles_disagree")
+            return False
+    return True
 
 
 def _nudge(O, sess, b):
     """Drop the last token of sequence b on both sides (it becomes pending again one position
     earlier): a different row 0, hence a fresh draw of its margin."""
-    s = O.seqs[b]
-    sess.rollback(b, 0b111, s.len[0] - 1)
-    O.o.rollback(s, 0b111, s.len[0] - 1)
+    n = O.seqs[b].len[0] - 1
+    sess.rollback(b, 0b111, n)
+    for side in O.sides():
+        side.o.rollback(side.seqs[b], 0b111, n)
 
 
 def _pick_drafts(O, sess, k, p, rng, do_full, first_mismatch=None, tries=25):
@@ -97,7 +118,7 @@ def _pick_drafts(O, sess, k, p, rng, do_full, first_mismatch=None, tries=25):
             found = None
             for a_star in range(a0, lowest, -1):
                 S = synth.make_draft_block(greedy, k, p, O.cfg.vocab, rng, first_mismatch=a_star)
-                if _trial_round(O, [s], [S], do_full) > MARGIN:
+                if _clear(O, b, S, do_full):
                     found = S
                     break
             if found is None:
@@ -109,56 +130,68 @@ def _pick_drafts(O, sess, k, p, rng, do_full, first_mismatch=None, tries=25):
     pytest.fail("no draft block cleared the margin filter")
 
 
+def _tag(side):
+    return "plain" if side.model.spec.round_mode == "none" and side.cfg.dtype == "bf16" else "own"
+
+
 def _round(O, sess, k, p, rng, do_full, tol):
-    B = len(O.seqs)
+    """One round on the GPU and in the oracle(s): decisions bit-exact, logits and hidden rows within tol of
+    every oracle (the plain twin, when there is one, is the model the bound is stated against)."""
     drafts = _pick_drafts(O, sess, k, p, rng, do_full)
     sess.draft_inject(drafts)
     ga, gn = sess.verify_intermediate()
     glog, ghid = sess.last_logits(), sess.last_hidden()
-    r0 = 0
-    for b, s in enumerate(O.seqs):
-        O.o.draft_inject(s, drafts[b])
-        a, nxt = O.o.verify_intermediate(s)
-        n = len(O.o.last_logits)
-        assert (int(ga[b]), int(gn[b])) == (a, nxt), f"seq {b}: gpu ({ga[b]},{gn[b]}) oracle ({a},{nxt})"
-        assert max_rel(glog[r0:r0 + n], O.o.last_logits) <= tol
-        assert max_rel(ghid[r0:r0 + n], O.o.last_hidden) <= tol
-        r0 += n
+    for side in O.sides():
+        r0 = 0
+        for b, s in enumerate(side.seqs):
+            side.o.draft_inject(s, drafts[b])
+            a, nxt = side.o.verify_intermediate(s)
+            n = len(side.o.last_logits)
+            assert (int(ga[b]), int(gn[b])) == (a, nxt), f"{_tag(side)} seq {b}: gpu ({ga[b]},{gn[b]}) oracle ({a},{nxt})"
+            el, eh = max_rel(glog[r0:r0 + n], side.o.last_logits), max_rel(ghid[r0:r0 + n], side.o.last_hidden)
+            note(f"{side.cfg.dtype}_logits_vs_{_tag(side)}", el); note(f"{side.cfg.dtype}_hidden_vs_{_tag(side)}", eh)
+            assert el <= tol and eh <= tol, (_tag(side), b, el, eh)
+            count(f"decisions_vs_{_tag(side)}")
+            r0 += n
     _check_state(O, sess)
     if not do_full:
         return
     gf, gn, gcom = sess.verify_full()
     glog, ghid = sess.last_logits(), sess.last_hidden()
-    r0 = 0
-    for b, s in enumerate(O.seqs):
-        f, nxt, F = O.o.verify_full(s)
-        n = len(O.o.last_logits)
-        assert (int(gf[b]), int(gn[b]), gcom[b]) == (f, nxt, F)
-        assert max_rel(glog[r0:r0 + n], O.o.last_logits) <= tol
-        assert max_rel(ghid[r0:r0 + n], O.o.last_hidden) <= tol
-        r0 += n
+    for side in O.sides():
+        r0 = 0
+        for b, s in enumerate(side.seqs):
+            f, nxt, F = side.o.verify_full(s)
+            n = len(side.o.last_logits)
+            assert (int(gf[b]), int(gn[b]), gcom[b]) == (f, nxt, F), (_tag(side), b)
+            el, eh = max_rel(glog[r0:r0 + n], side.o.last_logits), max_rel(ghid[r0:r0 + n], side.o.last_hidden)
+            note(f"{side.cfg.dtype}_logits_vs_{_tag(side)}", el); note(f"{side.cfg.dtype}_hidden_vs_{_tag(side)}", eh)
+            assert el <= tol and eh <= tol, (_tag(side), b, el, eh)
+            count(f"decisions_vs_{_tag(side)}")
+            r0 += n
     _check_state(O, sess)
 
 
 def _check_state(O, sess):
     lens = sess.lengths()
     nc, nv = sess.counts()
-    for b, s in enumerate(O.seqs):
-        assert list(lens[b]) == s.len
-        assert (nc[b], nv[b]) == (len(s.C), len(s.V))
-        assert sess.tokens(b).tolist() == s.T
+    for side in O.sides():
+        for b, s in enumerate(side.seqs):
+            assert list(lens[b]) == s.len
+            assert (nc[b], nv[b]) == (len(s.C), len(s.V))
+            assert sess.tokens(b).tolist() == s.T
 
 
-def _setup(cfg, seed, ctx_lens, max_rows, bonus=(True, True), prompt_seed=100):
+def _setup(cfg, seed, ctx_lens, max_rows, bonus=(True, True), prompt_seed=100, plain=False):
     B = len(ctx_lens)
     max_ctx = int(max(ctx_lens)) + 8 * max_rows
-    O = OracleSide(cfg, seed, *bonus)
+    O = OracleSide(cfg, seed, *bonus, plain_twin=plain)
     model, sess = gpu_side(cfg, seed, B, max_ctx, max_rows, *bonus)
     sess.enable_logits(True)
     for attempt in range(20):
         prompts = [synth.gen_prompt(cfg.vocab, int(n), prompt_seed + 1000 * attempt + b) for b, n in enumerate(ctx_lens)]
         first, margins = O.prefill(prompts, max_ctx)
-        if min(margins) > MARGIN:      # the committed first token must be decided clearly
+        if min(margins) > MARGIN:      # the committed first token must be decided clearly (by every oracle, alike)
             break
     else:
         pytest.fail("no prompt cleared the margin filter")
@@ -192,11 +225,12 @@ CASES = [
 def test_verify_rounds_match_oracle(name, cfg, ctx, k, bonus):
     tol = TOL[cfg.dtype]
     max_rows = 3 * (k + 1) + 2
-    O, model, sess, first, gfirst = _setup(cfg, 777, ctx, max_rows, bonus)
+    O, model, sess, first, gfirst = _setup(cfg, 777, ctx, max_rows, bonus, plain=True)
     assert gfirst.tolist() == first.tolist()
     # the last prefill pass covered the last sequence: its final row is the oracle's last hidden row
-    assert max_rel(sess.last_hidden()[-1:], O.o.last_hidden) <= tol
-    assert max_rel(sess.last_logits()[-1:], O.o.last_logits) <= tol
+    for side in O.sides():
+        assert max_rel(sess.last_hidden()[-1:], side.o.last_hidden) <= tol
+        assert max_rel(sess.last_logits()[-1:], side.o.last_logits) <= tol
     rng = np.random.default_rng(5)
     # round 1: intermediate only; round 2: intermediate then full; round 3: both again
     _round(O, sess, k, 0.8, rng, False, tol)
@@ -347,7 +381,7 @@ def test_self_drafting_matches_oracle():
 def test_kv_cache_matches_oracle_and_dead_entries_never_leak():
     cfg = bf16_small()
     k = 8
-    O, model, sess, _, _ = _setup(cfg, 55, [100, 30], 3 * (k + 1) + 2)
+    O, model, sess, _, _ = _setup(cfg, 55, [100, 30], 3 * (k + 1) + 2, plain=True)
     rng = np.random.default_rng(2)
     tol = TOL["bf16"]
     for rnd in range(4):
@@ -355,12 +389,15 @@ def test_kv_cache_matches_oracle_and_dead_entries_never_leak():
             sess.poison_dead_kv(b)          # NaN in every pruned / never-written slot
         _round(O, sess, k, 0.7, rng, rnd % 2 == 1, tol)
         assert np.isfinite(sess.last_logits()).all()
-    for b, s in enumerate(O.seqs):
-        for g in range(3):
-            for l in cfg.group_layers(g):
-                n = s.len[g]
-                gk, gv = sess.read_kv(b, l, 0, n)
-                assert max_rel(gk, s.cache.K[l, :n]) <= tol and max_rel(gv, s.cache.V[l, :n]) <= tol
+    for side in O.sides():          # every KV entry against the rounding oracle and against the plain model
+        for b, s in enumerate(side.seqs):
+            for g in range(3):
+                for l in cfg.group_layers(g):
+                    n = s.len[g]
+                    gk, gv = sess.read_kv(b, l, 0, n)
+                    ek, ev = max_rel(gk, s.cache.K[l, :n]), max_rel(gv, s.cache.V[l, :n])
+                    note(f"bf16_kv_vs_{_tag(side)}", max(ek, ev))
+                    assert ek <= tol and ev <= tol, (_tag(side), b, l, ek, ev)
     sess.close(); model.close()
 
 

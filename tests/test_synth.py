@@ -110,3 +110,22 @@ def test_draft_block_forced_mismatch():
         assert list(S[:a]) == [4] * a
         if a < 4:
             assert S[a] != 4 and 0 <= S[a] < 8
+
+
+def test_compiled_generator_equals_numpy_generator():
+    """synth/gen_fast.c (built by the build entry point) restates the recipe of synth/model.py: same bits for
+    fp32 and bf16 models, plain matrices, damped ones, gains and adapter tensors, at offsets inside a tensor."""
+    import pytest
+    from synth import model as sm
+    if not sm._fast_lib():
+        pytest.skip("synth/libsynthgen.so has not been built")
+    for cfg in (synth.tiny_config(gamma=(1.0, 0.5, 0.25), head_rank=24),
+                synth.llama8b_config(n_layers=3, exit_draft=1, exit_inter=2, gamma=(1.0, 0.3, 0.1), head_rank=64)):
+        for name, layer in (("emb", 0), ("head", 0), ("gfinal", 0), ("g1", 1), ("wq", 2), ("wo", 1), ("wo", 2),
+                            ("wdown", 2), ("wgate", 0), ("aux_g", 1), ("aux_a", 0), ("aux_b", 1)):
+            rows = synth.tensor_shape(cfg, name)[0]
+            r0, n = min(5, rows - 1), min(37, rows - min(5, rows - 1))
+            a = sm.gen_tensor_rows(cfg, 20251001, name, layer, r0, n)
+            b = sm.gen_tensor_rows(cfg, 20251001, name, layer, r0, n, use_fast=False)
+            assert a.dtype == b.dtype == np.float32 and a.shape == b.shape
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (cfg.dtype, name, layer)
