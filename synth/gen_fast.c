@@ -13,8 +13,9 @@ static inline uint64_t mix64(uint64_t z) {
 }
 
 /* key: stream key of (seed, tensor, layer); scale: fp32 factor; gain != 0: value = 1 + n; bf16 != 0: round
- * to bf16 (nearest even) and widen again.  out: float32[count]. */
-void synth_fill(uint64_t key, uint64_t e0, uint64_t count, float scale, int gain, int bf16, float* out) {
+ * to bf16 (nearest even) and widen again.  out: float32[count], or float64[count] holding the same values when
+ * wide != 0. */
+void synth_fill(uint64_t key, uint64_t e0, uint64_t count, float scale, int gain, int bf16, int wide, void* out) {
   const uint64_t GOLD = 0x9E3779B97F4A7C15ull;
 #pragma omp parallel for schedule(static)
   for (int64_t i = 0; i < (int64_t)count; ++i) {
@@ -33,6 +34,7 @@ void synth_fill(uint64_t key, uint64_t e0, uint64_t count, float scale, int gain
       u = ((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16) << 16;
       memcpy(&v, &u, 4);
     }
-    out[i] = v;
+    if (wide) ((double*)out)[i] = (double)v;
+    else ((float*)out)[i] = v;
   }
 }

@@ -217,7 +217,7 @@ def _fast_lib():
         try:
             lib = ctypes.CDLL(path)
             lib.synth_fill.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_float,
-                                       ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
             lib.synth_fill.restype = None
             _FAST = lib
         except OSError:
@@ -234,17 +234,18 @@ def _pool() -> ThreadPoolExecutor:
 
 
 def gen_tensor_rows(cfg: EEConfig, seed: int, name: str, layer: int,
-                    row0: int, nrows: int, use_fast: bool = True) -> np.ndarray:
-    """Rows [row0, row0+nrows) of a 2-D tensor (or elements of a 1-D tensor)."""
+                    row0: int, nrows: int, use_fast: bool = True, dtype=np.float32) -> np.ndarray:
+    """Rows [row0, row0+nrows) of a 2-D tensor (or elements of a 1-D tensor), float32 (or the same values
+    widened to float64)."""
     shape = tensor_shape(cfg, name)
     cols = shape[1] if len(shape) == 2 else 1
     e0, count = row0 * cols, nrows * cols
     fast = _fast_lib() if use_fast else False
     if fast:
         key = stream_key(seed, TENSOR_IDS[name], layer if name in LAYER_TENSORS + EXIT_TENSORS else 0)
-        flat = np.empty(count, np.float32)
+        flat = np.empty(count, dtype)
         fast.synth_fill(key, e0, count, float(tensor_scale(cfg, name, layer)), int(name in GAIN_TENSORS),
-                        int(cfg.dtype == "bf16"), flat.ctypes.data)
+                        int(cfg.dtype == "bf16"), int(np.dtype(dtype) == np.float64), flat.ctypes.data)
     elif count <= _CHUNK:
         flat = gen_flat(cfg, seed, name, layer, e0, count)
     else:
@@ -252,11 +253,11 @@ def gen_tensor_rows(cfg: EEConfig, seed: int, name: str, layer: int,
         parts = _pool().map(
             lambda s: gen_flat(cfg, seed, name, layer, e0 + s, min(_CHUNK, count - s)), starts)
         flat = np.concatenate(list(parts))
-    return flat.reshape((nrows, cols) if len(shape) == 2 else (nrows,))
+    return flat.astype(dtype, copy=False).reshape((nrows, cols) if len(shape) == 2 else (nrows,))
 
 
-def gen_tensor(cfg: EEConfig, seed: int, name: str, layer: int = 0) -> np.ndarray:
-    return gen_tensor_rows(cfg, seed, name, layer, 0, tensor_shape(cfg, name)[0])
+def gen_tensor(cfg: EEConfig, seed: int, name: str, layer: int = 0, dtype=np.float32) -> np.ndarray:
+    return gen_tensor_rows(cfg, seed, name, layer, 0, tensor_shape(cfg, name)[0], dtype=dtype)
 
 
 class WeightStore:

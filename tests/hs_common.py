@@ -1,7 +1,10 @@
 """Shared helpers of the GPU parity tests: an oracle and a library session on the same seeded inputs."""
 from __future__ import annotations
 
+import copy
+
 import numpy as np
+import pytest
 
 import synth
 from oracle import ee_oracle as eo
@@ -24,6 +27,17 @@ def max_rel(got: np.ndarray, ref: np.ndarray) -> float:
 STATS = {}    # name -> largest value seen in this test session (printed by conftest at the end of the run)
 
 
+def progress(msg):
+    """One line per finished step of a long test into gpurun_out/ (when that folder exists): the full-width
+    oracle passes take minutes of host time during which pytest itself prints nothing."""
+    import os
+    import time
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "pytest_progress.log"), "a") as f:
+            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+
+
 def note(name, value):
     STATS[name] = max(STATS.get(name, 0.0), float(value))
 
@@ -36,33 +50,84 @@ class OracleSide:
     """The oracle of a test: `o` / `seqs` follow the model's own rounding mode (the rounding oracle for a bf16
     configuration); with plain_twin a second OracleSide `P` holds the unrounded model in lockstep."""
 
-    def __init__(self, cfg, seed, bonus_inter=True, bonus_full=True, round_mode=None, plain_twin=False, weights=None):
+    def __init__(self, cfg, seed, bonus_inter=True, bonus_full=True, round_mode=None, plain_twin=False, weights=None,
+                 big=False):
         self.cfg = cfg
-        self.W = weights if weights is not None else synth.WeightStore(cfg, seed)
+        if weights is None:     # big: a full-width model -- float64 copies kept, embedding rows made on demand
+            weights = F64Store(cfg, seed) if big else synth.WeightStore(cfg, seed)
+        self.W = weights
         self.model = eo.EEModel(eo.ModelSpec.from_config(cfg, round_mode=round_mode), self.W)
+        if big:
+            self.model.embed = RowEmb(cfg, seed)
         self.o = eo.HiSpecOracle(self.model, bonus_inter, bonus_full)
         self.seqs = []
         twin = plain_twin and cfg.dtype == "bf16" and round_mode != "none"
-        self.P = OracleSide(cfg, seed, bonus_inter, bonus_full, round_mode="none", weights=self.W) if twin else None
+        self.P = OracleSide(cfg, seed, bonus_inter, bonus_full, round_mode="none", weights=self.W, big=big) if twin else None
 
     def sides(self):
         return [self] + ([self.P] if self.P else [])
 
     def prefill(self, prompts, capacity):
         self.seqs, first, margins = [], [], []
+        for side in self.sides():
+            side.seqs = []
         for p in prompts:
-            s = eo.Sequence_(self.model.spec, capacity)
-            first.append(self.o.prefill(s, p))
-            margins.append(float(eo.top2_margin(self.o.last_logits)[0]))
-            self.seqs.append(s)
-        if self.P:
-            pfirst, pmargins = self.P.prefill(prompts, capacity)
-            margins = [min(a, b) if f == g else 0.0 for a, b, f, g in zip(margins, pmargins, first, pfirst)]
+            f, m = self.prefill_one(p, capacity)
+            first.append(f); margins.append(m)
         return np.array(first), margins
+
+    def prefill_one(self, prompt, capacity, slot=None):
+        """Start one more sequence (or restart `slot`) from a prompt in every oracle; returns the first committed
+        token and its margin (0 when the oracles commit different tokens)."""
+        out = []
+        for side in self.sides():
+            s = eo.Sequence_(side.model.spec, capacity)
+            f = side.o.prefill(s, prompt)
+            out.append((f, float(eo.top2_margin(side.o.last_logits)[0])))
+            if slot is None:
+                side.seqs.append(s)
+            else:
+                side.seqs[slot] = s
+        agree = all(f == out[0][0] for f, _ in out)
+        return out[0][0], (min(m for _, m in out) if agree else 0.0)
+
+    def drop_last(self):
+        for side in self.sides():
+            side.seqs.pop()
 
     def greedy(self, seq, n, exit_layer):
         """Teacher-forced greedy continuation of T at an exit (fresh cache, state untouched)."""
         return eo.ar_generate(self.model, seq.T, n, exit_layer)
+
+
+class F64Store:
+    """The generator's tensors as float64 arrays, kept: the oracle converts whatever it is given to float64 on
+    every use, which for a full-width matrix costs more than the product it feeds."""
+
+    def __init__(self, cfg, seed):
+        self.cfg, self.seed, self.mem = cfg, seed, {}
+
+    def get(self, name, layer=0):
+        if (name, layer) not in self.mem:
+            self.mem[(name, layer)] = synth.gen_tensor(self.cfg, self.seed, name, layer, dtype=np.float64)
+        return self.mem[(name, layer)]
+
+
+class RowEmb:
+    """Embedding rows generated on demand (same values as rows of the store's "emb" tensor; a full-vocabulary
+    table of the 8B width is 2 GB)."""
+
+    def __init__(self, cfg, seed):
+        self.cfg, self.seed, self.rows = cfg, seed, {}
+
+    def __call__(self, tokens):
+        out = np.empty((len(tokens), self.cfg.d_model), np.float64)
+        for i, t in enumerate(np.asarray(tokens, np.int64)):
+            t = int(t)
+            if t not in self.rows:
+                self.rows[t] = synth.gen_tensor_rows(self.cfg, self.seed, "emb", 0, t, 1)[0].astype(np.float64)
+            out[i] = self.rows[t]
+        return out
 
 
 def gpu_side(cfg, seed, batch, max_ctx, max_rows, bonus_inter=True, bonus_full=True):
@@ -88,3 +153,156 @@ def bf16_d128(**kw):
                 gamma=(1.0, 0.2, 0.2))
     base.update(kw)
     return synth.EEConfig(**base)
+
+
+# ------------------------------------------------------------------------------------------------
+# helpers: one HiSpec round on both sides with margin-filtered inputs
+# ------------------------------------------------------------------------------------------------
+def trial_round(O, seqs, drafts, do_full, decisions=None):
+    """Run the round on deep copies of the oracle sequences; return the smallest margin among the
+    rows whose arg max decides an output (rows 0..a of each verify).  `decisions`, if given, collects
+    what the round decided."""
+    worst = np.inf
+    for s0, S in zip(seqs, drafts):
+        s = copy.deepcopy(s0)
+        O.o.draft_inject(s, S)
+        a, nxt = O.o.verify_intermediate(s)
+        m = eo.top2_margin(O.o.last_logits)
+        worst = min(worst, m[:min(a + 1, len(m))].min())
+        out = [a, nxt]
+        if do_full:
+            f, fn, F = O.o.verify_full(s)
+            m = eo.top2_margin(O.o.last_logits)
+            worst = min(worst, m[:min(f + 1, len(m))].min())
+            out += [f, fn, list(F)]
+        if decisions is not None:
+            decisions.append(out)
+    return worst
+
+
+def clear_in_oracles(O, b, S, do_full):
+    """The block clears the margin in the oracle -- with a plain twin in both oracles, which must also decide alike."""
+    dec = []
+    if trial_round(O, [O.seqs[b]], [S], do_full, dec) <= MARGIN:
+        return False
+    if O.P:
+        pdec = []
+        if trial_round(O.P, [O.P.seqs[b]], [S], do_full, pdec) <= MARGIN:
+            return False
+        if dec != pdec:
+            count("oracles_disagree")
+            return False
+    return True
+
+
+def nudge(O, sess, b):
+    """Drop the last token of sequence b on both sides (it becomes pending again one position
+    earlier): a different row 0, hence a fresh draw of its margin."""
+    n = O.seqs[b].len[0] - 1
+    sess.rollback(b, 0b111, n)
+    for side in O.sides():
+        side.o.rollback(side.seqs[b], 0b111, n)
+
+
+def pick_drafts(O, sess, k, p, rng, do_full, first_mismatch=None, tries=25):
+    """Teacher-forced draft blocks (agreement p with the L_i verifier) whose every decisive row
+    clears the margin in the oracle.  The drawn first-mismatch index is lowered until the rows up
+    to it are clear; if even row 0 is not, the context is nudged and the draw repeated."""
+    for _ in range(tries):
+        drafts = []
+        for b, s in enumerate(O.seqs):
+            greedy = O.greedy(s, k, O.cfg.exit_inter)
+            a0 = synth.draw_first_mismatch(k, p, rng) if first_mismatch is None else first_mismatch
+            lowest = -1 if first_mismatch is None else first_mismatch - 1
+            found = None
+            for a_star in range(a0, lowest, -1):
+                S = synth.make_draft_block(greedy, k, p, O.cfg.vocab, rng, first_mismatch=a_star)
+                if clear_in_oracles(O, b, S, do_full):
+                    found = S
+                    break
+            if found is None:
+                nudge(O, sess, b)
+                break
+            drafts.append(found)
+            progress(f"draft block of sequence {b} chosen")
+        else:
+            return np.stack(drafts)
+    pytest.fail("no draft block cleared the margin filter")
+
+
+def tag(side):
+    return "plain" if side.model.spec.round_mode == "none" and side.cfg.dtype == "bf16" else "own"
+
+
+def run_round(O, sess, k, p, rng, do_full, tol):
+    """One round on the GPU and in the oracle(s): decisions bit-exact, logits and hidden rows within tol of
+    every oracle (the plain twin, when there is one, is the model the bound is stated against)."""
+    drafts = pick_drafts(O, sess, k, p, rng, do_full)
+    sess.draft_inject(drafts)
+    ga, gn = sess.verify_intermediate()
+    glog, ghid = sess.last_logits(), sess.last_hidden()
+    for side in O.sides():
+        r0 = 0
+        for b, s in enumerate(side.seqs):
+            side.o.draft_inject(s, drafts[b])
+            a, nxt = side.o.verify_intermediate(s)
+            n = len(side.o.last_logits)
+            assert (int(ga[b]), int(gn[b])) == (a, nxt), f"{tag(side)} seq {b}: gpu ({ga[b]},{gn[b]}) oracle ({a},{nxt})"
+            el, eh = max_rel(glog[r0:r0 + n], side.o.last_logits), max_rel(ghid[r0:r0 + n], side.o.last_hidden)
+            note(f"{side.cfg.dtype}_logits_vs_{tag(side)}", el); note(f"{side.cfg.dtype}_hidden_vs_{tag(side)}", eh)
+            assert el <= tol and eh <= tol, (tag(side), b, el, eh)
+            count(f"decisions_vs_{tag(side)}")
+            r0 += n
+    check_state(O, sess)
+    if not do_full:
+        return
+    gf, gn, gcom = sess.verify_full()
+    glog, ghid = sess.last_logits(), sess.last_hidden()
+    for side in O.sides():
+        r0 = 0
+        for b, s in enumerate(side.seqs):
+            f, nxt, F = side.o.verify_full(s)
+            n = len(side.o.last_logits)
+            assert (int(gf[b]), int(gn[b]), gcom[b]) == (f, nxt, F), (tag(side), b)
+            el, eh = max_rel(glog[r0:r0 + n], side.o.last_logits), max_rel(ghid[r0:r0 + n], side.o.last_hidden)
+            note(f"{side.cfg.dtype}_logits_vs_{tag(side)}", el); note(f"{side.cfg.dtype}_hidden_vs_{tag(side)}", eh)
+            assert el <= tol and eh <= tol, (tag(side), b, el, eh)
+            count(f"decisions_vs_{tag(side)}")
+            r0 += n
+    check_state(O, sess)
+
+
+def check_state(O, sess):
+    lens = sess.lengths()
+    nc, nv = sess.counts()
+    for side in O.sides():
+        for b, s in enumerate(side.seqs):
+            assert list(lens[b]) == s.len
+            assert (nc[b], nv[b]) == (len(s.C), len(s.V))
+            assert sess.tokens(b).tolist() == s.T
+
+
+def setup(cfg, seed, ctx_lens, max_rows, bonus=(True, True), prompt_seed=100, plain=False, big=False):
+    """Oracle(s) and a library session on the same prompts; every prompt is one whose first committed token is
+    decided clearly (by every oracle, alike)."""
+    B = len(ctx_lens)
+    max_ctx = int(max(ctx_lens)) + 8 * max_rows
+    O = OracleSide(cfg, seed, *bonus, plain_twin=plain, big=big)
+    model, sess = gpu_side(cfg, seed, B, max_ctx, max_rows, *bonus)
+    sess.enable_logits(True)
+    prompts, first = [], []
+    for b, n in enumerate(ctx_lens):
+        for attempt in range(20):
+            prompt = synth.gen_prompt(cfg.vocab, int(n), prompt_seed + 1000 * attempt + b)
+            f, margin = O.prefill_one(prompt, max_ctx)
+            progress(f"oracle context of sequence {b}, attempt {attempt}: margin {margin:.4f}")
+            if margin > MARGIN:
+                break
+            O.drop_last()
+        else:
+            pytest.fail("no prompt cleared the margin filter")
+        prompts.append(prompt); first.append(f)
+    gfirst = sess.prefill(prompts)
+    return O, model, sess, np.array(first), gfirst
+
+

@@ -19,7 +19,7 @@ import pytest
 
 import synth
 from oracle import ee_oracle as eo
-from hs_common import MARGIN, TOL, max_rel
+from hs_common import MARGIN, STATS, TOL, max_rel, run_round, setup, tag
 
 pytestmark = pytest.mark.gpu
 
@@ -58,60 +58,55 @@ def _sample_ids(vocab, gpu_logits_row, rng, n_random=96):
     return np.unique(np.concatenate([top, rng.integers(0, vocab, n_random)]))
 
 
-def test_full_width_reduced_depth_matches_oracle():
-    import paper_2510_01336_amd as hs
-    cfg = synth.llama8b_config(n_layers=3, exit_draft=1, exit_inter=2, gamma=(1.0, 0.3, 0.3))
-    k, ctx = 8, 300
+def _full_width_case(cfg, ctx, k, rounds, seed=SEED, prompt_seed=100):
+    """A reduced-depth model of a full-size width against both oracles (the rounding one and the plain model),
+    whole vocabulary: teacher-forced blocks built from the oracle's own L_i continuation, chosen so that every
+    deciding row clears the margin in both oracles, hence every accept length, token and committed stream is
+    asserted, together with every logit, hidden row and (at the end) KV entry."""
     tol = TOL["bf16"]
-    W = synth.WeightStore(cfg, SEED)
-    om = eo.EEModel(eo.ModelSpec.from_config(cfg), W)
-    om.embed = _RowEmb(cfg, SEED)                     # same values as W.get("emb")[tokens], generated row by row
-    orc = eo.HiSpecOracle(om)
-    seq = eo.Sequence_(om.spec, ctx + 64)
-    prompt = synth.gen_prompt(cfg.vocab, ctx, 3)
-    # oracle prefill without the full-vocabulary head: the first committed token is taken from the GPU and
-    # checked on sampled logits below
-    x = om.run_layers(range(cfg.n_layers), om.embed(prompt), np.arange(ctx), seq.cache)
-
-    model = hs.Model(cfg, SEED)
-    sess = hs.Session(model, 1, ctx + 64, 3 * (k + 1) + 2)
-    sess.enable_logits(True)
-    first = int(sess.prefill([prompt])[0])
-    rng = np.random.default_rng(0)
-    glog = sess.last_logits()[-1]
-    assert max_rel(sess.last_hidden()[-1:], x[-1:]) <= tol
-    ids = _sample_ids(cfg.vocab, glog, rng)
-    ref = _oracle_logits_at(cfg, SEED, x[-1:], ids)[0]
-    assert np.max(np.abs(glog[ids] - ref)) / np.max(np.abs(ref)) <= tol
-    assert first == int(np.argmax(glog))
-    margin = np.sort(ref)[-1] - np.sort(ref)[-2]
-    if margin > MARGIN:
-        assert first == int(ids[np.argmax(ref)])
-    seq.C, seq.len, seq.prompt_len = [int(t) for t in prompt] + [first], [ctx, ctx, ctx], ctx
-
-    # one round: a random block (its tokens only matter as inputs); verify at L_i and at L_f on both sides
-    S = rng.integers(0, cfg.vocab, k).astype(np.int32)
-    sess.draft_inject(S[None])
-    ga, gn = sess.verify_intermediate()
-    ghid, glog = sess.last_hidden(), sess.last_logits()
-    orc.draft_inject(seq, S)
-    # oracle side of LeadingSubstringVerify with the head evaluated on sampled ids only
-    G2 = om.spec.group_layers(1)
-    p0 = len(seq.T) - 1
-    Y = om.run_layers(G2, np.stack(seq.H_d), p0 + np.arange(k + 1), seq.cache)
-    assert max_rel(ghid[:k + 1], Y) <= tol
-    for r in range(k + 1):
-        ids = _sample_ids(cfg.vocab, glog[r], rng)
-        ref = _oracle_logits_at(cfg, SEED, Y[r:r + 1], ids)[0]
-        assert np.max(np.abs(glog[r, ids] - ref)) / np.max(np.abs(ref)) <= tol, r
-    # the fused arg max and the accept scan against the materialised logits of the same launch
-    v = np.argmax(glog[:k + 1], axis=1)
-    a, out = eo.leading_substring_verify(S, v)
-    assert (int(ga[0]), int(gn[0])) == (a, out[-1])
-    kv_k, kv_v = sess.read_kv(0, 1, 0, p0 + a + 1)
-    n = p0 + a + 1
-    assert max_rel(kv_k, seq.cache.K[1, :n]) <= tol and max_rel(kv_v, seq.cache.V[1, :n]) <= tol
+    O, model, sess, first, gfirst = setup(cfg, seed, ctx, 3 * (k + 1) + 2, plain=True, big=True, prompt_seed=prompt_seed)
+    assert gfirst.tolist() == first.tolist()
+    for side in O.sides():
+        assert max_rel(sess.last_hidden()[-1:], side.o.last_hidden) <= tol
+        assert max_rel(sess.last_logits()[-1:], side.o.last_logits) <= tol
+    rng = np.random.default_rng(5)
+    before = dict(STATS)
+    for p, do_full in rounds:
+        run_round(O, sess, k, p, rng, do_full, tol)
+    compared = {t: STATS.get(f"decisions_vs_{t}", 0) - before.get(f"decisions_vs_{t}", 0) for t in ("own", "plain")}
+    want = len(ctx) * sum(2 if f else 1 for _, f in rounds)
+    assert compared == {"own": want, "plain": want}, compared       # nothing was skipped
+    for side in O.sides():
+        for b, s_ in enumerate(side.seqs):
+            for g in range(3):
+                for l in cfg.group_layers(g):
+                    n = s_.len[g]
+                    gk, gv = sess.read_kv(b, l, 0, n)
+                    assert max_rel(gk, s_.cache.K[l, :n]) <= tol and max_rel(gv, s_.cache.V[l, :n]) <= tol, (tag(side), b, l)
     sess.close(); model.close()
+
+
+def test_full_width_reduced_depth_matches_oracle():
+    """Every per-layer shape of the 8B configuration (d 4096, 32/8 heads x 128, FFN 14336, vocabulary 128256:
+    the tile counts, K splits and launch shapes bench.py times at 9 rows) on 3 layers, context 300, k = 8."""
+    cfg = synth.llama8b_config(n_layers=3, exit_draft=1, exit_inter=2, gamma=(1.0, 0.3, 0.3))
+    _full_width_case(cfg, [300], 8, [(0.8, True), (0.8, True)])
+
+
+def test_full_width_batch16_matches_oracle():
+    """The batch-16 workload's call shapes at the 8B width: 16 ragged short contexts x 9 block rows = 144 packed
+    rows through the row-tiled GEMM (12 row tiles, 9 in use, K-share reduction for the narrow projections),
+    16 catch-up rows and 32..160 rows in the full verification, per-sequence acceptance."""
+    cfg = synth.llama8b_config(n_layers=3, exit_draft=1, exit_inter=2, gamma=(1.0, 0.3, 0.3))
+    ctx = [20, 70, 33, 64, 65, 7, 90, 128, 40, 77, 100, 12, 55, 21, 99, 60]
+    _full_width_case(cfg, ctx, 8, [(0.8, True)], prompt_seed=300)
+
+
+def test_70b_ffn_shapes_match_oracle():
+    """The 70B per-layer shapes as the 70B workload launches them (d 8192, 64 / 8 heads x 128, FFN 28672: gate/up
+    N = 57344, down K = 28672, vocabulary 128256 at K = 8192; batch 4 x 9 block rows = 36 packed rows) on 3 layers."""
+    cfg = synth.llama70b_config(n_layers=3, exit_draft=1, exit_inter=2, gamma=(1.0, 0.3, 0.3))
+    _full_width_case(cfg, [40, 130, 64, 77], 8, [(0.75, True)], prompt_seed=500)
 
 
 class _SampledHead:

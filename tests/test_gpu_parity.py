@@ -11,7 +11,9 @@ import pytest
 
 import synth
 from oracle import ee_oracle as eo
-from hs_common import MARGIN, TOL, OracleSide, bf16_d128, bf16_small, count, gpu_side, max_rel, note
+from hs_common import (MARGIN, TOL, OracleSide, bf16_d128, bf16_small, gpu_side, max_rel, note,
+                       check_state as _check_state, pick_drafts as _pick_drafts, run_round as _round, setup as _setup,
+                       tag as _tag, trial_round as _trial_round)
 
 pytestmark = pytest.mark.gpu
 
@@ -54,149 +56,6 @@ def test_set_tensor_roundtrip():
     assert np.array_equal(model.tensor_rows("wgate", 1, 0, 688, 256), synth.gen_tensor(cfg, 1, "wgate", 1))
     assert np.array_equal(model.tensor_rows("wq", 1, 0, 512, 256), synth.gen_tensor(cfg, 1, "wq", 1))
     model.close()
-
-
-# ------------------------------------------------------------------------------------------------
-# helpers: one HiSpec round on both sides with margin-filtered inputs
-# ------------------------------------------------------------------------------------------------
-def _trial_round(O, seqs, drafts, do_full, decisions=None):
-    """Run the round on deep copies of the oracle sequences; return the smallest margin among the
-    rows whose arg max decides an output (rows 0..a of each verify).  `decisions`, if given, collects
-    what the round decided."""
-    worst = np.inf
-    for s0, S in zip(seqs, drafts):
-        s = copy.deepcopy(s0)
-        O.o.draft_inject(s, S)
-        a, nxt = O.o.verify_intermediate(s)
-        m = eo.top2_margin(O.o.last_logits)
-        worst = min(worst, m[:min(a + 1, len(m))].min())
-        out = [a, nxt]
-        if do_full:
-            f, fn, F = O.o.verify_full(s)
-            m = eo.top2_margin(O.o.last_logits)
-            worst = min(worst, m[:min(f + 1, len(m))].min())
-            out += [f, fn, list(F)]
-        if decisions is not None:
-            decisions.append(out)
-    return worst
-
-
-def _clear(O, b, S, do_full):
-    """The block clears the margin in the oracle -- with a plain twin in both oracles, which must also decide alike."""
-    dec = []
-    if _trial_round(O, [O.seqs[b]], [S], do_full, dec) <= MARGIN:
-        return False
-    if O.P:
-        pdec = []
-        if _trial_round(O.P, [O.P.seqs[b]], [S], do_full, pdec) <= MARGIN:
-            return False
-        if dec != pdec:
-            count("oracles_disagree")
-            return False
-    return True
-
-
-def _nudge(O, sess, b):
-    """Drop the last token of sequence b on both sides (it becomes pending again one position
-    earlier): a different row 0, hence a fresh draw of its margin."""
-    n = O.seqs[b].len[0] - 1
-    sess.rollback(b, 0b111, n)
-    for side in O.sides():
-        side.o.rollback(side.seqs[b], 0b111, n)
-
-
-def _pick_drafts(O, sess, k, p, rng, do_full, first_mismatch=None, tries=25):
-    """Teacher-forced draft blocks (agreement p with the L_i verifier) whose every decisive row
-    clears the margin in the oracle.  The drawn first-mismatch index is lowered until the rows up
-    to it are clear; if even row 0 is not, the context is nudged and the draw repeated."""
-    for _ in range(tries):
-        drafts = []
-        for b, s in enumerate(O.seqs):
-            greedy = O.greedy(s, k, O.cfg.exit_inter)
-            a0 = synth.draw_first_mismatch(k, p, rng) if first_mismatch is None else first_mismatch
-            lowest = -1 if first_mismatch is None else first_mismatch - 1
-            found = None
-            for a_star in range(a0, lowest, -1):
-                S = synth.make_draft_block(greedy, k, p, O.cfg.vocab, rng, first_mismatch=a_star)
-                if _clear(O, b, S, do_full):
-                    found = S
-                    break
-            if found is None:
-                _nudge(O, sess, b)
-                break
-            drafts.append(found)
-        else:
-            return np.stack(drafts)
-    pytest.fail("no draft block cleared the margin filter")
-
-
-def _tag(side):
-    return "plain" if side.model.spec.round_mode == "none" and side.cfg.dtype == "bf16" else "own"
-
-
-def _round(O, sess, k, p, rng, do_full, tol):
-    """One round on the GPU and in the oracle(s): decisions bit-exact, logits and hidden rows within tol of
-    every oracle (the plain twin, when there is one, is the model the bound is stated against)."""
-    drafts = _pick_drafts(O, sess, k, p, rng, do_full)
-    sess.draft_inject(drafts)
-    ga, gn = sess.verify_intermediate()
-    glog, ghid = sess.last_logits(), sess.last_hidden()
-    for side in O.sides():
-        r0 = 0
-        for b, s in enumerate(side.seqs):
-            side.o.draft_inject(s, drafts[b])
-            a, nxt = side.o.verify_intermediate(s)
-            n = len(side.o.last_logits)
-            assert (int(ga[b]), int(gn[b])) == (a, nxt), f"{_tag(side)} seq {b}: gpu ({ga[b]},{gn[b]}) oracle ({a},{nxt})"
-            el, eh = max_rel(glog[r0:r0 + n], side.o.last_logits), max_rel(ghid[r0:r0 + n], side.o.last_hidden)
-            note(f"{side.cfg.dtype}_logits_vs_{_tag(side)}", el); note(f"{side.cfg.dtype}_hidden_vs_{_tag(side)}", eh)
-            assert el <= tol and eh <= tol, (_tag(side), b, el, eh)
-            count(f"decisions_vs_{_tag(side)}")
-            r0 += n
-    _check_state(O, sess)
-    if not do_full:
-        return
-    gf, gn, gcom = sess.verify_full()
-    glog, ghid = sess.last_logits(), sess.last_hidden()
-    for side in O.sides():
-        r0 = 0
-        for b, s in enumerate(side.seqs):
-            f, nxt, F = side.o.verify_full(s)
-            n = len(side.o.last_logits)
-            assert (int(gf[b]), int(gn[b]), gcom[b]) == (f, nxt, F), (_tag(side), b)
-            el, eh = max_rel(glog[r0:r0 + n], side.o.last_logits), max_rel(ghid[r0:r0 + n], side.o.last_hidden)
-            note(f"{side.cfg.dtype}_logits_vs_{_tag(side)}", el); note(f"{side.cfg.dtype}_hidden_vs_{_tag(side)}", eh)
-            assert el <= tol and eh <= tol, (_tag(side), b, el, eh)
-            count(f"decisions_vs_{_tag(side)}")
-            r0 += n
-    _check_state(O, sess)
-
-
-def _check_state(O, sess):
-    lens = sess.lengths()
-    nc, nv = sess.counts()
-    for side in O.sides():
-        for b, s in enumerate(side.seqs):
-            assert list(lens[b]) == s.len
-            assert (nc[b], nv[b]) == (len(s.C), len(s.V))
-            assert sess.tokens(b).tolist() == s.T
-
-
-def _setup(cfg, seed, ctx_lens, max_rows, bonus=(True, True), prompt_seed=100, plain=False):
-    B = len(ctx_lens)
-    max_ctx = int(max(ctx_lens)) + 8 * max_rows
-    O = OracleSide(cfg, seed, *bonus, plain_twin=plain)
-    model, sess = gpu_side(cfg, seed, B, max_ctx, max_rows, *bonus)
-    sess.enable_logits(True)
-    for attempt in range(20):
-        prompts = [synth.gen_prompt(cfg.vocab, int(n), prompt_seed + 1000 * attempt + b) for b, n in enumerate(ctx_lens)]
-        first, margins = O.prefill(prompts, max_ctx)
-        if min(margins) > MARGIN:      # the committed first token must be decided clearly (by every oracle, alike)
-            break
-    else:
-        pytest.fail("no prompt cleared the margin filter")
-    gfirst = sess.prefill(prompts)
-    return O, model, sess, first, gfirst
 
 
 # ------------------------------------------------------------------------------------------------

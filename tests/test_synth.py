@@ -129,3 +129,5 @@ def test_compiled_generator_equals_numpy_generator():
             b = sm.gen_tensor_rows(cfg, 20251001, name, layer, r0, n, use_fast=False)
             assert a.dtype == b.dtype == np.float32 and a.shape == b.shape
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (cfg.dtype, name, layer)
+            wide = sm.gen_tensor_rows(cfg, 20251001, name, layer, r0, n, dtype=np.float64)
+            assert wide.dtype == np.float64 and np.array_equal(wide, b.astype(np.float64))
