@@ -193,7 +193,8 @@ int ee_verify_full(ee_session* s, const uint8_t* active, int32_t* n_accept, int3
  * and the call is ee_verify_full.  Every buffer below the one being checked must be empty (EE_ERR_STATE), so the
  * levels run bottom-up: 1, then 2 when enough tokens wait there, and so on.  Arguments as ee_verify_full
  * (`moved`: host [batch, max_rows+1], the kept tokens).  EE_ERR_ARG for a level outside 2..n; EE_ERR_CAPACITY when
- * a level's buffer would exceed max_rows tokens. */
+ * the buffer of a level below L_f would exceed max_rows - bonus_full tokens (the next level's catch-up row shares its
+ * max_rows slots); the session is unchanged then. */
 int ee_verify_level(ee_session* s, int level, const uint8_t* active, int32_t* n_accept, int32_t* next_token,
                     int32_t* moved, int32_t* n_moved);
 
@@ -220,11 +221,13 @@ size_t ee_sampling_bytes(const ee_session* s);
 int ee_sampling_attach(ee_session* s, void* dev_arena, size_t arena_bytes);
 /* u: host [batch, k], one number per drafted token.  Otherwise as ee_draft. */
 int ee_draft_sample(ee_session* s, int k, const float* u, int32_t* draft);
-/* u_acc: host [batch, u_stride], number j tests draft token j (u_stride >= k); u_res: host [batch], the
- * replacement / next-token draw.  Outputs and state transition as ee_verify_intermediate. */
+/* u_acc: host [batch, u_stride], number j tests draft token j (u_stride >= k, EE_ERR_ARG otherwise); u_res: host
+ * [batch], the replacement / next-token draw.  The entries of sequences that take no part are ignored.  Outputs
+ * and state transition as ee_verify_intermediate. */
 int ee_verify_intermediate_rs(ee_session* s, const float* u_acc, int u_stride, const float* u_res,
                               int32_t* n_accept, int32_t* next_token);
-/* u_acc: host [batch, u_stride] (u_stride >= the longest tentative buffer).  Otherwise as ee_verify_full. */
+/* u_acc: host [batch, u_stride] (u_stride >= the longest tentative buffer taking part, EE_ERR_ARG otherwise).
+ * Otherwise as ee_verify_full. */
 int ee_verify_full_rs(ee_session* s, const uint8_t* active, const float* u_acc, int u_stride, const float* u_res,
                       int32_t* n_accept, int32_t* next_token, int32_t* committed, int32_t* n_committed);
 /* Test support: n rows from row0 of one sequence's stored distributions (which = 0: the draft distributions of

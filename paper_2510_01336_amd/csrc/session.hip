@@ -709,7 +709,9 @@ static int draft_impl(ee_session* s, int k, int32_t* draft, const float* u) {
   const int rows = k + (c.bonus_inter ? 1 : 0);
   if (u && !s->Pd) { ee_set_error("sampling buffers are not attached (ee_sampling_attach)"); return EE_ERR_STATE; }
   EE_TRY(draft_precheck(s, k, rows));
-  if (u) EE_TRY(upload_uniforms(s, u, (size_t)s->B * k, 0));
+  if (u)
+    for (int b = 0; b < s->B; ++b)      // an idle slot's numbers are neither read nor checked
+      if (s->seq[b].started) EE_TRY(upload_uniforms(s, u + (size_t)b * k, k, (size_t)b * k));
   reset_accounting(s);
   s->need_logits = u != nullptr;
   CallPlan p;
@@ -831,8 +833,12 @@ static int verify_intermediate_impl(ee_session* s, int32_t* n_accept, int32_t* n
   if (rs) {
     if (!s->Pd) { ee_set_error("sampling buffers are not attached (ee_sampling_attach)"); return EE_ERR_STATE; }
     if (u_stride < 1 || u_stride > s->max_rows) { ee_set_error("bad stride of the uniform numbers"); return EE_ERR_ARG; }
-    for (int b = 0; b < s->B; ++b) EE_TRY(upload_uniforms(s, u_acc + (size_t)b * u_stride, u_stride, (size_t)b * s->max_rows));
-    EE_TRY(upload_uniforms(s, u_res, s->B, (size_t)s->B * s->max_rows));
+    for (int b = 0; b < s->B; ++b) {                         // idle sequences' numbers are neither read nor checked
+      if (!p.m[b]) continue;
+      if ((int)s->seq[b].S.size() > u_stride) { ee_set_error("sequence %d: %d draft tokens need as many uniform numbers (u_stride %d)", b, (int)s->seq[b].S.size(), u_stride); return EE_ERR_ARG; }
+      EE_TRY(upload_uniforms(s, u_acc + (size_t)b * u_stride, u_stride, (size_t)b * s->max_rows));
+      EE_TRY(upload_uniforms(s, u_res + b, 1, (size_t)s->B * s->max_rows + b));
+    }
   }
   reset_accounting(s);
   EE_TRY(build_meta(s, 0, p, [&](int b, int r, int&, int& src, int& dst) {
@@ -929,8 +935,13 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
       ee_set_error("sequence %d: the tentative tokens were not produced by the sampling calls", b);
       return EE_ERR_STATE;
     }
-    if (j < n && (q.cut[j] - q.cut[j + 1]) + m_src[b] + bonus > s->max_rows) {
-      ee_set_error("level %d buffer of sequence %d would overflow max_rows", j, b); return EE_ERR_CAPACITY;
+    // level j's buffer is level j+1's draft: its rows sit in a [max_rows] slab per sequence together with the
+    // catch-up row that level j+1 appends behind them, so it may hold max_rows - bonus tokens at most
+    if (j < n && (q.cut[j] - q.cut[j + 1]) + m_src[b] + bonus > s->max_rows - bonus) {
+      ee_set_error("level %d buffer of sequence %d would exceed %d tokens", j, b, s->max_rows - bonus); return EE_ERR_CAPACITY;
+    }
+    if (m_src[b] + bonus > s->max_rows) {      // (cannot happen given the bound above and the one on V in the draft calls)
+      ee_set_error("sequence %d: %d rows do not fit max_rows", b, m_src[b] + bonus); return EE_ERR_CAPACITY;
     }
     act[b] = 1; any++;
   }
@@ -938,8 +949,12 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
   if (rs) {
     if (!s->Pi) { ee_set_error("sampling buffers are not attached (ee_sampling_attach)"); return EE_ERR_STATE; }
     if (u_stride < 1 || u_stride > s->max_rows) { ee_set_error("bad stride of the uniform numbers"); return EE_ERR_ARG; }
-    for (int b = 0; b < s->B; ++b) EE_TRY(upload_uniforms(s, u_acc + (size_t)b * u_stride, u_stride, (size_t)b * s->max_rows));
-    EE_TRY(upload_uniforms(s, u_res, s->B, (size_t)s->B * s->max_rows));
+    for (int b = 0; b < s->B; ++b) {                         // idle sequences' numbers are neither read nor checked
+      if (!act[b]) continue;
+      if (m_src[b] > u_stride) { ee_set_error("sequence %d: %d tentative tokens need as many uniform numbers (u_stride %d)", b, m_src[b], u_stride); return EE_ERR_ARG; }
+      EE_TRY(upload_uniforms(s, u_acc + (size_t)b * u_stride, u_stride, (size_t)b * s->max_rows));
+      EE_TRY(upload_uniforms(s, u_res + b, 1, (size_t)s->B * s->max_rows + b));
+    }
   }
   auto src_tok = [&](int b, int i) { const SeqState& q = s->seq[b]; return j == 2 ? q.V[i] : q.C[q.cut[j] + i]; };
   float* rows_below = level_rows(s, j - 1);

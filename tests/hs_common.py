@@ -61,6 +61,7 @@ class OracleSide:
             self.model.embed = RowEmb(cfg, seed)
         self.o = eo.HiSpecOracle(self.model, bonus_inter, bonus_full)
         self.seqs = []
+        self.from_cache = False
         twin = plain_twin and cfg.dtype == "bf16" and round_mode != "none"
         self.P = OracleSide(cfg, seed, bonus_inter, bonus_full, round_mode="none", weights=self.W, big=big) if twin else None
 
@@ -96,8 +97,18 @@ class OracleSide:
             side.seqs.pop()
 
     def greedy(self, seq, n, exit_layer):
-        """Teacher-forced greedy continuation of T at an exit (fresh cache, state untouched)."""
-        return eo.ar_generate(self.model, seq.T, n, exit_layer)
+        """Teacher-forced greedy continuation of T at an exit (state untouched): from the tokens with a fresh
+        cache, or -- for a sequence whose context was planted rather than built (from_cache) -- from a copy of
+        its cache, one row at a time."""
+        if not self.from_cache:
+            return eo.ar_generate(self.model, seq.T, n, exit_layer)
+        s = copy.deepcopy(seq)
+        which, tok, out = self.model.spec.exit_index(exit_layer), s.T[-1], []
+        for j in range(n):
+            x = self.model.run_layers(range(exit_layer), self.model.embed([tok]), np.array([len(s.T) - 1 + j]), s.cache)
+            tok = int(eo.argmax_rows(self.model.exit_logits(x, which))[0])
+            out.append(tok)
+        return out
 
 
 class F64Store:

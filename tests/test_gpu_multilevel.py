@@ -188,3 +188,91 @@ def test_multilevel_stream_equals_vanilla_stream_on_gpu(cfg, windows):
     assert np.array_equal(np.concatenate([first[:, None], toks], axis=1), ar)
     assert all(c > 0 for c in stats["calls"][1:]) and 0 < stats["accepted"][1] < stats["checked"][1]
     sess.close(); model.close()
+
+
+def _limit_case(sess=None):
+    """Two sequences whose level-2 buffers grow by six tokens per round (every draft block is the L_i verifier's own
+    continuation and exit 6 agrees with it): with max_rows = 14 sequence 0 reaches the most a buffer below a
+    catch-up row may hold (max_rows - 1 = 13 tokens: 1, 7, 13), sequence 1 (6, 12) would pass it and is refused.
+    Level 3 then consumes sequence 0's thirteen rows plus the catch-up row (14 = max_rows rows), and afterwards
+    sequence 1's buffer, which must have stayed intact next to the full one.  With a session the GPU runs in
+    lockstep; returns the smallest margin of the deciding rows."""
+    import paper_2510_01336_amd as hs
+    cfg, seed, k, ctx, max_rows = f32_chain(gamma=(1.0, 0.1, 0.1)), 3, 4, [40, 9], 14
+    W = synth.WeightStore(cfg, seed)
+    model = eo.EEModel(eo.ModelSpec.from_config(cfg), W)
+    M = eo.MultiLevelOracle(model)
+    tol = TOL["f32"]
+    prompts = [synth.gen_prompt(cfg.vocab, c, 300 + b) for b, c in enumerate(ctx)]
+    seqs, worst = [], np.inf
+    for pr in prompts:
+        s = eo.MultiSequence(model.spec, 300)
+        M.prefill(s, pr)
+        seqs.append(s)
+    if sess is not None:
+        assert sess.prefill(prompts).tolist() == [s.C[-1] for s in seqs]
+
+    def level(lv, active):
+        """Level lv for the active sequences on both sides; compares decisions, moved tokens, logits and state."""
+        nonlocal worst
+        if sess is not None:
+            if lv == 1:
+                ga, gn = sess.verify_intermediate()
+            else:
+                act = np.array(active, np.uint8)
+                ga, gn, gmoved = sess.verify_level(lv, act) if lv < M.n else sess.verify_full(act)
+            glog, r0 = sess.last_logits(), 0
+        for b, s in enumerate(seqs):
+            if not active[b]:
+                continue
+            a, nxt, moved = M.verify_level(s, lv)
+            rows = len(M.last_logits)
+            worst = min(worst, float(eo.top2_margin(M.last_logits)[:a + 1].min()))
+            if sess is not None:
+                assert (int(ga[b]), int(gn[b])) == (a, nxt), (lv, b)
+                if lv > 1:
+                    assert gmoved[b] == moved
+                assert max_rel(glog[r0:r0 + rows], M.last_logits) <= tol
+                r0 += rows
+        if sess is not None:
+            lens = sess.lengths()
+            for b, s in enumerate(seqs):
+                assert list(lens[b]) == s.len and sess.tokens(b).tolist() == s.T, (lv, b)
+
+    def inject():
+        drafts = np.stack([np.array(eo.ar_generate(model, s.T, k, cfg.exit_inter), np.int32) for s in seqs])
+        for b, s in enumerate(seqs):
+            M.draft_inject(s, drafts[b])
+        if sess is not None:
+            sess.draft_inject(drafts)
+
+    for rnd in range(2):
+        inject(); level(1, [1, 1]); level(2, [1, 1])
+    assert [len(s.V[2]) for s in seqs] == [7, 12]
+    inject(); level(1, [1, 1]); level(2, [1, 0])
+    assert len(seqs[0].V[2]) == max_rows - 1
+    if sess is not None:
+        before = (sess.lengths().tolist(), sess.tokens(1).tolist())
+        with pytest.raises(hs.EEError) as e:                 # 12 + 5 + 1 tokens would not leave room for a catch-up row
+            sess.verify_level(2, np.array([0, 1], np.uint8))
+        assert e.value.code == -3
+        assert (sess.lengths().tolist(), sess.tokens(1).tolist()) == before
+    level(3, [1, 0])                                          # 13 buffered rows + the catch-up row = max_rows rows
+    # sequence 1: drop its level-1 buffer (and the last token of the level-2 buffer), then level 3 over the rest
+    s = seqs[1]
+    keep = len(s.C) + len(s.V[2]) - 1
+    M.rollback(s, keep - 1)
+    if sess is not None:
+        sess.rollback(1, (1 << (M.n + 1)) - 1, keep - 1)
+    level(3, [0, 1])
+    return worst
+
+
+def test_level_buffer_filled_to_its_limit_in_a_batch():
+    import paper_2510_01336_amd as hs
+    cfg = f32_chain(gamma=(1.0, 0.1, 0.1))
+    model = hs.Model(cfg, 3)
+    sess = hs.Session(model, 2, 300, 14)
+    sess.enable_logits(True)
+    assert _limit_case(sess) > margin_of(cfg)
+    sess.close(); model.close()

@@ -97,6 +97,12 @@ def test_sampling_needs_attached_buffers_and_valid_uniforms():
     assert sess.lengths().tolist() == [[16, 16, 16]]
     S = sess.draft_sample(4, np.array([[0.1, 0.2, 0.9, 0.3]], np.float32))
     assert S.shape == (1, 4) and (S >= 0).all() and (S < cfg.vocab).all()
+    # fewer uniform numbers than draft tokens: refused, the block stays pending and verifies with enough of them
+    with pytest.raises(hs.EEError) as e:
+        sess.verify_intermediate_rs(np.full((1, 3), 0.5, np.float32), np.array([0.5], np.float32))
+    assert e.value.code == -1
+    a, n = sess.verify_intermediate_rs(np.full((1, 4), 0.5, np.float32), np.array([0.5], np.float32))
+    assert 0 <= int(a[0]) <= 4
     sess.close(); model.close()
 
 
