@@ -265,6 +265,15 @@ int ee_debug_kernel_times(ee_session* s, int32_t* n_families, const char** names
  * choice.  Results agree to rounding order.  EE_ERR_ARG for any other value. */
 int ee_debug_gemm_row_blocks(int row_tiles);
 
+/* Test support, process-wide: the attention kernel cuts every sequence's cached context into KV splits of equal
+ * length, by default the shortest one that keeps the whole call within one workgroup per compute unit -- so the cut,
+ * and with it the order in which a row's softmax partials are summed, follows the shape of the batch.  pages > 0
+ * fixes the split length to that many 64-position pages for every call (raised where the split scratch would not
+ * hold the count), so that a sequence is cut alike whether it runs alone or in a batch and the batched-inference
+ * claim (a sequence's results do not depend on its neighbours) can be checked bit for bit; 0 restores the built-in
+ * choice.  EE_ERR_ARG for a negative value. */
+int ee_debug_attention_split_pages(int pages);
+
 /* Plain device-to-device streaming copy on `stream` (pointers and size multiples of 16 bytes; not
  * synchronised).  A kernel of exactly known traffic -- `bytes` read, `bytes` written -- used to
  * calibrate hardware byte counters when the HBM traffic of the other kernels is measured. */

@@ -692,6 +692,7 @@ static bool launch_gemm_rows_blocks(hipStream_t st, int epi, const uint4* W, int
 // (TN = 4) instead of four; 0: use the K-share kernel (wide matrices, and shapes where it measured faster).
 LaunchEvents* g_launch_events = nullptr;
 int g_rows_blocks_override = -1;   // test and tuning hook: >= 0 replaces the choice below
+int g_attn_pages_override = 0;
 static int rows_blocks_form(int ntiles, int ktiles, int M) {
   if (g_rows_blocks_override >= 0) return g_rows_blocks_override;
   // measured on the 8B shapes (N 4096 and 6144): the blocks win for K <= 4096 from about 200 rows when columns x
@@ -1233,6 +1234,7 @@ int bf16_attention_pages_per_split(const int* kv_end, const int* seq_m, int B, i
   int max_pages = 1;
   for (int b = 0; b < B; ++b) max_pages = max(max_pages, ceil_div(kv_end[b], EE_PAGE));
   int per = max(2, ceil_div(max_pages, max(1, min(max_splits, EE_MAX_SPLITS))));
+  if (g_attn_pages_override > 0) return min(max(per, g_attn_pages_override), max_pages);   // (never more splits than the scratch holds)
   for (; per < max_pages; ++per) {
     long wgs = 0;
     for (int b = 0; b < B; ++b)

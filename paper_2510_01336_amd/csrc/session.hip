@@ -1237,6 +1237,12 @@ extern "C" int ee_debug_gemm_row_blocks(int row_tiles) {
   return EE_OK;
 }
 
+extern "C" int ee_debug_attention_split_pages(int pages) {
+  if (pages < 0 || pages > 65536) { ee_set_error("pages per split must be 0 (built-in choice) or positive"); return EE_ERR_ARG; }
+  g_attn_pages_override = pages;
+  return EE_OK;
+}
+
 extern "C" int ee_debug_time_kernels(ee_session* s, int on) {
   if (!s) { ee_set_error("null session"); return EE_ERR_ARG; }
   s->time_kernels = on != 0;

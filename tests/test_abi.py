@@ -99,3 +99,11 @@ def test_gemm_form_selector_checks_its_argument(lib):
         assert lib.ee_debug_gemm_row_blocks(bad) == -1, bad
         assert b"row_tiles" in lib.ee_last_error()
     assert lib.ee_debug_gemm_row_blocks(-1) == 0
+
+
+def test_attention_split_selector_checks_its_argument(lib):
+    lib.ee_last_error.restype = ctypes.c_char_p
+    for ok in (2, 1, 17, 0):
+        assert lib.ee_debug_attention_split_pages(ok) == 0, ok
+    assert lib.ee_debug_attention_split_pages(-3) == -1 and b"pages per split" in lib.ee_last_error()
+    assert lib.ee_debug_attention_split_pages(0) == 0

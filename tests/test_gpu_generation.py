@@ -83,3 +83,35 @@ def test_hispec_stream_equals_vanilla_stream_on_gpu(policy):
     # the loop did speculate: some draft tokens were accepted, some rejected
     assert 0 < st.accepted_inter < st.drafted and st.full_verifies >= 1 and st.accepted_full <= st.tentative
     sess.close(); model.close()
+
+
+def test_bf16_hispec_stream_equals_vanilla_stream_and_oracle():
+    """The lossless guarantee (Sec. 3.1) on the bf16 path: a prompt whose vanilla stream clears the margin at every
+    one of 40 tokens in both oracles (the plain model and the operand-rounding one, which must also agree) is
+    decoded by ee_decode_ar and by the whole hierarchical loop (self-drafting at L_d, L_i, L_f); all three streams
+    are the oracle's."""
+    from paper_2510_01336_amd.loop import hispec_generate
+    cfg, n_new, k, ctx = bf16_small(), 40, 4, 48
+    W = synth.WeightStore(cfg, SEED)
+    models = [eo.EEModel(eo.ModelSpec.from_config(cfg, round_mode=rm), W) for rm in ("none", "bf16")]
+    for attempt in range(60):
+        prompt = synth.gen_prompt(cfg.vocab, ctx, 500 + attempt)
+        ref, margins = _oracle_ar_with_margins(models[0], prompt, n_new)
+        if min(margins) <= MARGIN:
+            continue
+        ref2, margins2 = _oracle_ar_with_margins(models[1], prompt, n_new)
+        if ref2 == ref and min(margins2) > MARGIN:
+            break
+    else:
+        pytest.fail("no prompt cleared the margin filter")
+    rows = 4 * (k + 1) + 2
+    model, sess = gpu_side(cfg, SEED, 1, ctx + n_new + 4 * rows, max(rows, n_new))
+    first = sess.prefill([prompt])
+    ar = [int(first[0])] + sess.decode_ar(n_new - 1)[0].tolist()
+    assert ar == ref
+    for policy in (dict(n_i=6), dict(every=2)):
+        assert int(sess.prefill([prompt])[0]) == ref[0]
+        toks, st = hispec_generate(sess, n_new - 1, k, **policy)
+        assert [ref[0]] + toks[0].tolist() == ref, policy
+        assert st.full_verifies >= 1 and 0 < st.accepted_inter and st.accepted_full <= st.tentative
+    sess.close(); model.close()
