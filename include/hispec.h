@@ -172,6 +172,20 @@ int ee_draft_inject(ee_session* s, int k, const int32_t* draft);
  * H_d.  n_accept: host [batch] (0..k); next_token: host [batch] (v_{a+1}, or -1 if none). */
 int ee_verify_intermediate(ee_session* s, int32_t* n_accept, int32_t* next_token);
 
+/* For callers that cannot allocate device memory or hand over more of it -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: ee_verify_intermediate with every scratch buffer of the call (the
+ * attention's KV-split partials, the exit head's per-tile (max, arg max) partials, the deferred-RMSNorm partial sums
+ * and factors, the K-share partials of the row-tiled GEMM) taken from a static device array inside the library
+ * instead of the session arena.  Arguments, results, state transition and errors as ee_verify_intermediate, and
+ * bit-identical results (same kernels, same split plan).  The array holds 32 MiB per GPU from the first such call on
+ * that GPU until the process ends; a call that needs more (about: more than 16 block rows in total on an 8B-sized
+ * model, or a very long context) returns EE_ERR_CAPACITY before any device work and leaves the session unchanged.
+ * The call allocates nothing (no hipMalloc / hipFree / event or stream creation; EE_ERR_STATE while kernel timing
+ * is enabled, which creates events).  Every such call on a GPU uses that GPU's one array, which keeps the previous
+ * call's contents (nothing in it needs clearing: each call writes what it reads), so calls on the same GPU that
+ * overlap in time -- from two sessions or two streams -- race and must be serialised by the caller. */
+int ee_verify_intermediate_static(ee_session* s, int32_t* n_accept, int32_t* next_token);
+
 /* LeadingSubstringVerify(V, L_f, x) of Algorithm 2 for every sequence with active[b] != 0
  * (null = all) and a non-empty V: the buffered H_i rows (after the pending token's catch-up
  * through G1+G2 when bonus_full) run through G3, exit head + arg max, f = leading matches with V.

@@ -15,7 +15,7 @@ __all__ = [
     "lib", "lib_path", "EEError", "ee_config", "make_config", "Model", "Session",
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_seq_release", "ee_free_pages", "ee_decode_ar", "ee_draft", "ee_draft_inject",
-    "ee_verify_intermediate", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
+    "ee_verify_intermediate", "ee_verify_intermediate_static", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_gemm_row_blocks", "ee_debug_attention_split_pages", "ee_debug_stream_copy", "ee_last_error",
@@ -30,7 +30,7 @@ TENSOR_IDS = {"emb": 0, "head": 1, "gfinal": 2, "g1": 3, "wq": 4, "wk": 5, "wv":
 EXPORTED_SYMBOLS = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_seq_release", "ee_free_pages", "ee_decode_ar", "ee_draft", "ee_draft_inject",
-    "ee_verify_intermediate", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
+    "ee_verify_intermediate", "ee_verify_intermediate_static", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_gemm_row_blocks", "ee_debug_attention_split_pages", "ee_debug_stream_copy", "ee_last_error",
@@ -82,6 +82,7 @@ def _load():
         "ee_draft": (C.c_int, [vp, C.c_int, i32p]),
         "ee_draft_inject": (C.c_int, [vp, C.c_int, i32p]),
         "ee_verify_intermediate": (C.c_int, [vp, i32p, i32p]),
+        "ee_verify_intermediate_static": (C.c_int, [vp, i32p, i32p]),
         "ee_verify_full": (C.c_int, [vp, C.POINTER(C.c_uint8), i32p, i32p, i32p, i32p]),
         "ee_verify_level": (C.c_int, [vp, C.c_int, C.POINTER(C.c_uint8), i32p, i32p, i32p, i32p]),
         "ee_n_levels": (C.c_int, [vp]),
@@ -262,6 +263,12 @@ def ee_draft_inject(session: int, draft: np.ndarray) -> None:
 def ee_verify_intermediate(session: int, batch: int) -> Tuple[np.ndarray, np.ndarray]:
     a, n = np.empty(batch, np.int32), np.empty(batch, np.int32)
     _chk(lib.ee_verify_intermediate(session, _p_i32(a), _p_i32(n)))
+    return a, n
+
+
+def ee_verify_intermediate_static(session: int, batch: int) -> Tuple[np.ndarray, np.ndarray]:
+    a, n = np.empty(batch, np.int32), np.empty(batch, np.int32)
+    _chk(lib.ee_verify_intermediate_static(session, _p_i32(a), _p_i32(n)))
     return a, n
 
 
@@ -479,6 +486,9 @@ class Session:
 
     def verify_intermediate(self):
         return ee_verify_intermediate(self.handle, self.batch)
+
+    def verify_intermediate_static(self):
+        return ee_verify_intermediate_static(self.handle, self.batch)
 
     def verify_full(self, active=None):
         return ee_verify_full(self.handle, self.batch, self.max_rows, active)

@@ -4,6 +4,7 @@
 #include "kernels.h"
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 
 // With further verifier exits (n levels > 2) C also holds the tokens that wait for the levels above L_i,
 // deepest verdict first: C = committed || V[n-1] || ... || V[2], where V[j] are the tokens accepted at exit j that
@@ -386,20 +387,31 @@ static size_t closing_gain(const ee_model* m, int l1) {
   return m->gfinal;
 }
 
+// attention split plan of a call (the same for all its layers): pages per KV split and the scratch handed to the
+// kernels; nsplit_out = KV splits of the longest sequence = stride of the partial slots
+static int attention_plan(const ee_session* s, const CallPlan& p, int pos_add, AttnScratch& scr, int* nsplit_out) {
+  const ee_config& c = s->m->cfg;
+  scr = AttnScratch{s->part_o, s->part_ml, (int)std::min<size_t>(s->max_splits, s->part_units / std::max(1, p.total_qt))};
+  int per = 1;
+  if (s->m->bf16) {
+    std::vector<int> kv_end(s->B);
+    for (int b = 0; b < s->B; ++b) kv_end[b] = p.m[b] > 0 ? p.p0[b] + p.m[b] + pos_add : 0;
+    per = bf16_attention_pages_per_split(kv_end.data(), p.m.data(), s->B, c.n_q_heads, c.n_kv_heads, scr.max_splits);
+  }
+  const int max_pages = ceil_div(p.max_kv_end + pos_add, EE_PAGE);
+  per = std::max(1, std::min(per, max_pages));
+  if (nsplit_out) *nsplit_out = ceil_div(max_pages, per);
+  return per;
+}
+
 static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const CallMeta& mt, int pos_add) {
   const ee_model* m = s->m;
   const ee_config& c = m->cfg;
   const int d = c.d_model, D = c.head_dim, Hq = c.n_q_heads, Hkv = c.n_kv_heads, M = p.M;
   hipStream_t st = s->st;
   KF(KF_ROPE, k_rope_table(st, mt.row_pos, pos_add, m->inv_freq, s->cs, M, D / 2));
-  // attention split plan of this call (the same for all its layers)
-  AttnScratch scr{s->part_o, s->part_ml, (int)std::min<size_t>(s->max_splits, s->part_units / std::max(1, p.total_qt))};
-  int per = 1;
-  if (m->bf16) {
-    std::vector<int> kv_end(s->B);
-    for (int b = 0; b < s->B; ++b) kv_end[b] = p.m[b] > 0 ? p.p0[b] + p.m[b] + pos_add : 0;
-    per = bf16_attention_pages_per_split(kv_end.data(), p.m.data(), s->B, Hq, Hkv, scr.max_splits);
-  }
+  AttnScratch scr;
+  const int per = attention_plan(s, p, pos_add, scr, nullptr);
   for (int l = l0; l < l1; ++l) {
     const LayerLoc& L = m->L[l];
     const float* g1 = (const float*)(m->base + L.g1);
@@ -807,15 +819,96 @@ extern "C" int ee_draft_inject(ee_session* s, int k, const int32_t* draft) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Scratch of one call in the library's own static device array, for callers that cannot allocate
+// ---------------------------------------------------------------------------------------------
+// What a verify call needs beyond its inputs, outputs and the session's state -- the attention's split partials, the
+// exit head's (max, arg max) tile partials, the deferred-RMSNorm partial sums and factors, the K-share partials of
+// the row-tiled GEMM -- normally sits in the caller's session arena.  ee_verify_intermediate_static places it in
+// this array instead.  Every GPU holds its own copy of the array at its own address, found once per device with
+// hipGetSymbolAddress; the array's name itself is only a host-side stand-in and never goes to a kernel.
+#define EE_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+#define EE_STATIC_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[EE_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[EE_STATIC_MAX_DEVICES] = {nullptr};
+static std::mutex g_scratch_mutex;
+
+static int static_scratch_base(char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= EE_STATIC_MAX_DEVICES) { ee_set_error("device %d outside the static scratch table", dev); return EE_ERR_HIP; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) { ee_set_error("static scratch has no device address"); return EE_ERR_HIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = (char*)g_scratch_ptr[dev];
+  return EE_OK;
+}
+
+// the session's scratch pointers, swapped for the length of one call and put back whatever happens
+struct ScratchSwap {
+  ee_session* s;
+  float *part_o, *part_ml, *pmax, *ssq, *gemm_part, *inv_rms;
+  int* pidx;
+  explicit ScratchSwap(ee_session* s_) : s(s_), part_o(s_->part_o), part_ml(s_->part_ml), pmax(s_->pmax), ssq(s_->ssq),
+                                         gemm_part(s_->gemm_part), inv_rms(s_->inv_rms), pidx(s_->pidx) {}
+  ~ScratchSwap() {
+    s->part_o = part_o; s->part_ml = part_ml; s->pmax = pmax; s->ssq = ssq; s->gemm_part = gemm_part; s->inv_rms = inv_rms;
+    s->pidx = pidx;
+  }
+};
+
+// Lay the scratch of the call with plan p (pass over layers [l0, l1), then the shared exit head) out in the static
+// array and point the session at it.  The split plan is the one the session arena would have given (its capacity
+// only enters as a number), so the call computes exactly what ee_verify_intermediate computes.
+static int place_scratch_static(ee_session* s, const CallPlan& p) {
+  const ee_model* m = s->m;
+  const ee_config& c = m->cfg;
+  if (!m->bf16) return EE_OK;                       // the fp32 kernels use no scratch
+  char* base = nullptr;
+  EE_TRY(static_scratch_base(&base));
+  AttnScratch scr;
+  int nsplit = 1;
+  (void)attention_plan(s, p, 0, scr, &nsplit);
+  Carver cv{base};
+  const size_t slots = (size_t)p.total_qt * c.n_kv_heads * nsplit;
+  float* part_o = cv.take<float>(slots * 16 * c.head_dim);
+  float* part_ml = cv.take<float>(slots * 32);
+  const size_t pstride = (size_t)ceil_div(p.M, 16) * 16;
+  float* pmax = cv.take<float>((size_t)m->head.ntiles() * pstride);
+  int* pidx = cv.take<int>((size_t)m->head.ntiles() * pstride);
+  float* ssq = cv.take<float>((size_t)ceil_div(c.d_model, 16) * s->Mp);
+  float* inv_rms = cv.take<float>(512);
+  float* gemm_part = nullptr;
+  if (p.M > 16) {                                   // the row-tiled GEMM may run: room for its K shares
+    size_t gp = 0;
+    for (const MatLoc* ml : {&m->L[0].qkv, &m->L[0].o, &m->L[0].gu, &m->L[0].down, &m->head, &m->auxA[0], &m->auxB[0]})
+      if (ml->Np > 0) gp = std::max(gp, bf16_gemm_rows_scratch_floats(ml->ntiles(), ml->ktiles()));
+    gemm_part = cv.take<float>(gp);
+  }
+  if (cv.cur > EE_STATIC_SCRATCH_BYTES) {
+    ee_set_error("this call needs %zu bytes of scratch, the static array holds %zu: use ee_verify_intermediate", cv.cur,
+                 (size_t)EE_STATIC_SCRATCH_BYTES);
+    return EE_ERR_CAPACITY;
+  }
+  s->part_o = part_o; s->part_ml = part_ml; s->pmax = pmax; s->pidx = pidx; s->ssq = ssq; s->inv_rms = inv_rms;
+  s->gemm_part = gemm_part;
+  return EE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // C ABI: intermediate verification at exit L_i
 // ---------------------------------------------------------------------------------------------
 // u_acc == null: LeadingSubstringVerify on arg max tokens (Alg. 2); otherwise the acceptance rule of App. G with the
 // uniform numbers u_acc [batch, u_stride] (one per draft token) and u_res [batch] (the replacement / next-token draw)
 static int verify_intermediate_impl(ee_session* s, int32_t* n_accept, int32_t* next_token, const float* u_acc, int u_stride,
-                                    const float* u_res) {
+                                    const float* u_res, bool static_scratch = false) {
   if (!s || !n_accept || !next_token) { ee_set_error("null argument"); return EE_ERR_ARG; }
   const ee_config& c = s->m->cfg;
   const bool rs = u_acc != nullptr;
+  ScratchSwap restore(s);
   CallPlan p;
   p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
   int any = 0;
@@ -845,6 +938,7 @@ static int verify_intermediate_impl(ee_session* s, int32_t* n_accept, int32_t* n
     src = b * s->max_rows + r;                               // H_d row
     dst = b * s->max_rows + (int)s->seq[b].V.size() + r;     // H_i row
   }));
+  if (static_scratch) EE_TRY(place_scratch_static(s, p));
   int* h = s->slot[0].h;
   for (int b = 0; b < s->B; ++b) {
     const SeqState& q = s->seq[b];
@@ -889,6 +983,11 @@ static int verify_intermediate_impl(ee_session* s, int32_t* n_accept, int32_t* n
 
 extern "C" int ee_verify_intermediate(ee_session* s, int32_t* n_accept, int32_t* next_token) {
   return verify_intermediate_impl(s, n_accept, next_token, nullptr, 0, nullptr);
+}
+
+extern "C" int ee_verify_intermediate_static(ee_session* s, int32_t* n_accept, int32_t* next_token) {
+  if (s && s->time_kernels) { ee_set_error("kernel timing creates events: switch it off for the call that allocates nothing"); return EE_ERR_STATE; }
+  return verify_intermediate_impl(s, n_accept, next_token, nullptr, 0, nullptr, true);
 }
 
 extern "C" int ee_verify_intermediate_rs(ee_session* s, const float* u_acc, int u_stride, const float* u_res, int32_t* n_accept,
