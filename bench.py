@@ -33,11 +33,15 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0        # dense bf16
 MODEL_SEED = 20251001
 
-# HBM traffic of one gate/up GEMM launch (8b_b1_ctx2048_k8) measured with two rocprofv3 --pmc runs
-# (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the calibration copy
-# below; the figures and the commands are in profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = 236_569_000
+# HBM traffic of one gate/up GEMM launch, measured with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE),
+# each scaled by what the same counter reads for the calibration copy below.  Hardware counters cannot be read from
+# inside this script, so the line carries the figure of the committed profile of the same workload, named beside
+# it (`traffic_source`); a workload without such a profile reports null.
+MEASURED_TRAFFIC = {
+    "8b_b1_ctx2048_k8": (236_569_000, "profiles/hbm_traffic__8b_b1_ctx2048_k8.md"),
+}
 CALIBRATION_COPY_BYTES = 1 << 30
+MFMA_TARGET_FRAC = 0.50          # the goal stated for the FFN / LM-head GEMMs at their compute-bound shapes
 
 def _ragged16():
     return [int(c) for c in synth.gen_context_lengths(16, 5)]     # lognormal(ln 1024, 0.7) clipped to [128, 4096]
@@ -257,7 +261,8 @@ def context_build(w):
     tflops = flop / (gu_ms * 1e-3) / 1e12
     return {"tokens": tokens, "ms": 1e3 * wall, "tokens_per_s": tokens / wall,
             "gate_up_gemm": {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                             "frac": tflops / MFMA_PEAK_TFLOPS, "launches": gu_n, "avg_launch_us": 1e3 * gu_ms / gu_n}}
+                             "frac": tflops / MFMA_PEAK_TFLOPS, "target_frac": MFMA_TARGET_FRAC,
+                             "launches": gu_n, "avg_launch_us": 1e3 * gu_ms / gu_n}}
 
 
 def one_step(w, collect=None, wall=None):
@@ -292,50 +297,80 @@ def one_step(w, collect=None, wall=None):
     return a, f
 
 
+class _OneLayerStore:
+    """Weights for the CPU baseline: every layer answers with the tensors of one generated layer.  The oracle's
+    time does not depend on the values, and 32 distinct layers of the 8B shape are 28 GB of fp32 to generate."""
+
+    def __init__(self, cfg, seed, layer):
+        self.store, self.layer = synth.WeightStore(cfg, seed, cache=True), layer
+
+    def get(self, name, layer=0):
+        return self.store.get(name, self.layer if name in synth.model.LAYER_TENSORS else layer)
+
+
+def _oracle_step(orc, seqs, blocks, ctxs):
+    """One whole step of the workload in the oracle, through its own calls, sequence by sequence."""
+    for seq, ctx in zip(seqs, ctxs):
+        for drafts_b in blocks:
+            orc.draft_inject(seq, drafts_b)
+            orc.verify_intermediate(seq)
+        orc.verify_full(seq)
+        orc.rollback(seq, 0b111, ctx)
+
+
 def cpu_baseline(w):
-    """The oracle as it stands, on a bounded sample: ONE layer of the verify pass (k+1 rows against
-    a random KV context of the workload's length) plus ONE exit head, scaled to the layer and head
-    count of a full step."""
+    """The oracle as it stands on the host cores: ONE WHOLE STEP of the workload (block-parallel G1 pass, intermediate
+    verification, full verification with its catch-up row, prune), run through the oracle's own calls over a random KV
+    context of the workload's lengths, at all cores; and the same at one thread on a bounded sample (the first
+    sequence's G1 pass and intermediate verification, scaled by the layer passes of a whole step)."""
     from oracle import ee_oracle as eo
-    cfg, k, batch = w["cfg"], w["k"], w["batch"]
-    ctx = int(round(sum(w["ctxs"]) / batch))           # mean context: the sample times one sequence's layer pass
+    from threadpoolctl import threadpool_info, threadpool_limits
+    cfg, k, batch, ctxs = w["cfg"], w["k"], w["batch"], w["ctxs"]
     spec = eo.ModelSpec.from_config(cfg)
-    l = cfg.exit_draft                         # first layer of G2
-    store = synth.WeightStore(cfg, MODEL_SEED, cache=True)
-    for name in ("g1", "wq", "wk", "wv", "wo", "g2", "wgate", "wup", "wdown"):
-        store.get(name, l)
-    store.get("gfinal"); store.get("head")
-    model = eo.EEModel(spec, store)
+    store = _OneLayerStore(cfg, MODEL_SEED, cfg.exit_draft)
+    orc = eo.HiSpecOracle(eo.EEModel(spec, store), bool(1), bool(w["bonus_full"]), poison=False)
     rng = np.random.default_rng(0)
-    rows = k + 1
-    cache = eo.KVCache(spec, ctx + rows)
-    cache.K[l, :ctx] = eo.round_bf16(rng.normal(size=(ctx, cfg.n_kv_heads, cfg.head_dim)))
-    cache.V[l, :ctx] = eo.round_bf16(rng.normal(size=(ctx, cfg.n_kv_heads, cfg.head_dim)))
-    x = rng.normal(size=(rows, cfg.d_model))
-    # repeated until about ten seconds of layer passes and five of exit heads have been timed
-    reps_l, t0 = 0, time.perf_counter()
-    while reps_l < 3 or time.perf_counter() - t0 < 10.0:
-        for _ in range(batch):
-            y = model.layer(l, x, ctx + np.arange(rows), cache)
-        reps_l += 1
-    t_layer = (time.perf_counter() - t0) / reps_l
-    reps_h, t0 = 0, time.perf_counter()
-    while reps_h < 3 or time.perf_counter() - t0 < 5.0:
-        for _ in range(batch):
-            eo.argmax_rows(model.exit_logits(y))
-        reps_h += 1
-    t_head = (time.perf_counter() - t0) / reps_h
-    layers = cfg.n_layers + cfg.exit_inter      # G1 + G2 + G3 + catch-up row through G1+G2
-    t_step = layers * t_layer + 2 * t_head
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    return {"value": batch * k / t_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"1 of {layers} layer passes ({rows} rows, KV context {ctx}, random KV) timed {reps_l} times at "
-                      f"{t_layer:.2f} s each + 1 of 2 exit heads {reps_h} times at {t_head:.2f} s each, scaled to a full "
-                      f"step ({t_step:.1f} s); float64 numpy"}
+    seqs = []
+    for b, ctx in enumerate(ctxs):
+        seq = eo.Sequence_(spec, ctx + 4 * (k + 2))
+        # one random page of KV repeated over the context (float64 caches of 32 layers: filling them with fresh
+        # normals would take longer than the step)
+        tileK = eo.round_bf16(rng.normal(size=(64, cfg.n_kv_heads, cfg.head_dim)))
+        reps = -(-ctx // 64)
+        seq.cache.K[:, :ctx] = np.tile(tileK, (reps, 1, 1))[:ctx]
+        seq.cache.V[:, :ctx] = np.tile(tileK[::-1], (reps, 1, 1))[:ctx]
+        seq.C = [int(t) for t in w["prompts"][b]] + [1]
+        seq.len, seq.prompt_len = [ctx, ctx, ctx], ctx
+        seqs.append(seq)
+    blocks = [[w["blocks"][r][b] for r in range(w["rounds"])] for b in range(batch)]
+
+    def step_all():
+        for b in range(batch):
+            _oracle_step(orc, [seqs[b]], blocks[b], [ctxs[b]])
+
+    cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    for name in synth.model.LAYER_TENSORS + ("gfinal", "head"):     # untimed: generate the weights
+        store.get(name, cfg.exit_draft)
+    t0 = time.perf_counter()
+    step_all()
+    t_step = time.perf_counter() - t0
+    # one thread: the first sequence's block-parallel G1 pass (exit_draft layer passes of k+1 rows), scaled by layer
+    # passes to the whole step (the exit heads, about a tenth of the step, are left out of this figure)
+    passes_step = batch * (w["rounds"] * cfg.exit_inter + (cfg.n_layers - cfg.exit_inter) + (cfg.exit_inter if w["bonus_full"] else 0))
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        orc.draft_inject(seqs[0], blocks[0][0])
+        t_1 = time.perf_counter() - t0
+        orc.rollback(seqs[0], 0b111, ctxs[0])
+    t_step_1 = t_1 * passes_step / cfg.exit_draft
+    return {"value": batch * k * w["rounds"] / t_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one whole step of the workload ({passes_step} layer passes and {batch * (w['rounds'] + 1)} exit heads through "
+                      f"the oracle's own draft_inject / verify_intermediate / verify_full / rollback, random KV context, "
+                      f"one generated layer's weights serving every layer) timed once: {t_step:.1f} s; float64 numpy",
+            "one_thread": {"value": batch * k * w["rounds"] / t_step_1, "unit": "tokens/s", "cores": 1,
+                           "sample": f"first sequence's block-parallel G1 pass ({cfg.exit_draft} layer passes) timed once at one "
+                                     f"thread: {t_1:.1f} s, scaled by layer passes to a whole step ({t_step_1:.0f} s, exit "
+                                     f"heads left out)"}}
 
 
 def calibration_copy(stream_ptr):
@@ -419,8 +454,9 @@ def main():
     gu_kernel = "gemm_skinny_kernel<1,SWIGLU>" if rows <= 16 else "gemm_rows_kernel<.,SWIGLU> / gemm_skinny_kernel<1,SWIGLU>, mean over the step's launches;"
     roofline = {"bound": "hbm", "kernel": gu_kernel + " (gate/up projection + SiLU*mul)",
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": MEASURED_TRAFFIC_BYTES, "bytes_per_launch": gu_bytes, "avg_launch_us": gu_avg_s * 1e6,
-                "launches": gu_n}
+                "traffic": MEASURED_TRAFFIC.get(args.workload, (None, None))[0],
+                "traffic_source": MEASURED_TRAFFIC.get(args.workload, (None, None))[1],
+                "bytes_per_launch": gu_bytes, "avg_launch_us": gu_avg_s * 1e6, "launches": gu_n}
     sb = step_bytes(cfg, w["ctxs"], w["k"], bool(w["bonus_full"]), w["rounds"])
     kernel_ms = {k2: round(v[0] / args.steps, 4) for k2, v in acc.items()}
 
