@@ -276,7 +276,10 @@ int ee_debug_kernel_times(ee_session* s, int32_t* n_families, const char** names
  * projections (O, down, QKV, adapters) either with K shares and a reduction pass or with blocks of row_tiles*16
  * rows and no K shares; row_tiles = 4, 8 or 16 forces the second form for every such call (104 and 108: blocks of 4
  * and 8 row tiles with eight instead of four weight tiles per workgroup), 0 the first, -1 restores the built-in
- * choice.  Results agree to rounding order.  EE_ERR_ARG for any other value. */
+ * choice.  Two more values choose the form of the wide projections (gate/up, exit head) at 257..512 rows: 1016 (the
+ * default) sixteen weight tiles per workgroup with the rows in two blocks, 1000 eight weight tiles and one block;
+ * these two give bit-identical results.  Results of the forms of the narrow projections agree to rounding order.
+ * EE_ERR_ARG for any other value. */
 int ee_debug_gemm_row_blocks(int row_tiles);
 
 /* Test support, process-wide: the attention kernel cuts every sequence's cached context into KV splits of equal

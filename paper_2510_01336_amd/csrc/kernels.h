@@ -76,6 +76,7 @@ void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kti
 struct LaunchEvents { hipEvent_t start, stop; bool used; };
 extern LaunchEvents* g_launch_events;
 extern int g_attn_pages_override;   // <= 0: pages per KV split chosen from the call's shape; else that many (test hook: batch and solo runs then cut their contexts alike)
+extern int g_rows_wide;              // 1: gate/up and exit head at 257..512 rows run sixteen weight tiles per workgroup in two row blocks; 0: eight in one
 extern int g_rows_blocks_override;   // -1: built-in choice between K shares and row blocks; else 0, or row tiles per block (+100: eight weight tiles per workgroup)
 size_t bf16_gemm_rows_scratch_floats(int ntiles, int ktiles);
 void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,

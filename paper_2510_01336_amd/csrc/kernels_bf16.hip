@@ -405,14 +405,21 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   // TMT*16 rows that blockIdx.z names; the deferred-norm factors and the K-share partials are indexed from row0,
   // everything the epilogue touches by the row itself
   constexpr int NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
-  static_assert(TN == 2 || TN == 4, "weight tiles per wave");
-  const int rbase = blockIdx.z * (TMT * 16), M = min(M_all - rbase, TMT * 16);
+  static_assert(TN == 2 || TN == 4 || TN == 8, "weight tiles per wave");
+  // TN = 8 (sixteen weight tiles per workgroup, rows in two blocks): the grid is one-dimensional and workgroups L and
+  // L + 8 are the two row blocks of one column group -- dispatched together and on the same XCD (L mod 8), so the
+  // weights cross HBM once and the second reader finds them in that XCD's L2
+  const int bx = TN == 8 ? (int)(((blockIdx.x >> 4) << 3) | (blockIdx.x & 7)) : (int)blockIdx.x;
+  const int bz = TN == 8 ? (int)((blockIdx.x >> 3) & 1) : (int)blockIdx.z;
+  if (TN == 8 && (bx * (2 * TN) >= ntiles || bz * (TMT * 16) >= M_all)) return;       // whole workgroup
+  const int rbase = bz * (TMT * 16), M = min(M_all - rbase, TMT * 16);
   constexpr int TMW = TMT / 4;                      // row tiles per wave
   static_assert(TMT % 4 == 0 && TMT >= 4 && TMT <= 32, "row tiles split four ways");
   constexpr int STAGE = (2 * TN + TMT) * 64;        // 16-byte units: weight tiles first, then row tiles
   constexpr int S = (160 / (2 * TN + TMT)) & ~1;    // stages in the ring: what 160 KiB of LDS holds (even: fragments alternate between two register sets)
   constexpr int XHI = (TMT + 7) / 8;                // row tiles a wave requests per stage at most: wave, wave+8, ...
-  constexpr int LHI = 1 + XHI;                      // requests per stage at most: a weight tile and XHI row tiles
+  constexpr int WHI = TN == 8 ? 2 : 1;              // weight tiles a wave requests per stage: wave (and wave+8)
+  constexpr int LHI = WHI + XHI;                    // requests per stage at most
   static_assert((S - 1) * LHI < 64, "the load counter has six bits");
   __shared__ u32x4 ring[S][STAGE];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -420,7 +427,7 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   const int rq = wave_s >> 1, nh = wave_s & 1;
   const int rqv = wave >> 1, nhv = wave & 1;                    // the same again from the vector register: one address register
                                                                 // serves all LDS reads, the slots being constant offsets from it
-  const int nt0 = blockIdx.x * (2 * TN) + nh * TN;              // first weight tile of this wave
+  const int nt0 = bx * (2 * TN) + nh * TN;                      // first weight tile of this wave
   // Row tiles of this wave: TMW in a row when all of them hold rows (FULL: the guards below fold away), else
   // rq, rq+4, ..., so that the tiles past the last row, which are neither requested nor multiplied, are spread
   // over the four wave pairs.  The launcher picks the smallest TMT that holds the rows, so the unused tiles are
@@ -446,17 +453,20 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
   // this wave's last row tile holds rows: XHI requests per stage, else one less; with four weight tiles per
   // workgroup (TN = 2) only the first four waves request one
   const bool hi = (FULL && TMT % 8 == 0) || wave_s + 8 * (XHI - 1) < mt_used;
-  const bool wreq = TN == 4 || wave_s < 2 * TN;
+  const bool wreq = TN >= 4 || wave_s < 2 * TN;
   // LDS byte address of this wave's weight tile in stage 0 as a scalar: every request's LDS address is this plus a
   // constant, so none of them occupies a vector register (measured: 3-4 % at 24 and 32 row tiles)
   const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)&ring[0][0]) + 1024u * wave_s;
 #define ROWS_LDS(slot_, tile_) ((lptr_t)(size_t)(lds0 + 16u * ((slot_) * STAGE + (tile_) * 64)))
-  const u32x4* wsrc = (const u32x4*)W + (size_t)min(blockIdx.x * (2 * TN) + wave, ntiles - 1) * ktiles * 64 + lane;
+  const u32x4* wsrc = (const u32x4*)W + (size_t)min(bx * (2 * TN) + wave, ntiles - 1) * ktiles * 64 + lane;
+  const u32x4* wsrc2 = (const u32x4*)W + (size_t)min(bx * (2 * TN) + wave + 8, ntiles - 1) * ktiles * 64 + lane;   // (TN = 8)
   const u32x4* xsrc = (const u32x4*)A + (size_t)(((row0 + rbase) >> 4) + wave) * ktiles * 64 + lane;
+  // (weights: streaming hint, except where a second workgroup is to find them in L2)
 #define ROWS_REQUEST(slot_, kt_)                                                                              \
   do {                                                                                                        \
     const size_t k_ = (size_t)min(kt_, last) * 64;                                                            \
     if (wreq) __builtin_amdgcn_global_load_lds((gptr_t)(wsrc + k_), ROWS_LDS(slot_, 0), 16, 0, 2);                \
+    if (TN == 8) __builtin_amdgcn_global_load_lds((gptr_t)(wsrc2 + k_), ROWS_LDS(slot_, 8), 16, 0, 2);        \
     _Pragma("unroll") for (int j = 0; j < XHI - 1; ++j)                                                       \
       __builtin_amdgcn_global_load_lds((gptr_t)(xsrc + (size_t)(8 * j) * ktiles * 64 + k_),                   \
                                        ROWS_LDS(slot_, 2 * TN + 8 * j), 16, 0, 0);                            \
@@ -467,8 +477,9 @@ __global__ __launch_bounds__(512) void gemm_rows_kernel(const uint4* __restrict_
 #define ROWS_WAIT(stages_)                                                                                    \
   do {                                                                                                        \
     if (wreq && hi) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * LHI));                            \
-    else if (wreq || hi) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * (LHI - 1)));                 \
-    else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * (LHI - 2)));                                 \
+    else if (wreq) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * (LHI - 1)));                       \
+    else if (hi) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * XHI));                               \
+    else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((stages_) * (XHI - 1)));                                 \
   } while (0)
 #define ROWS_READ(buf_, slot_)                                                                               \
   do {                                                                                                        \
@@ -688,6 +699,23 @@ static bool launch_gemm_rows_blocks(hipStream_t st, int epi, const uint4* W, int
   return true;
 }
 
+// Wide matrices (gate/up, exit head) at 257..512 rows: sixteen weight tiles per workgroup and the rows in two blocks of
+// up to 256.  Per k-tile a workgroup then moves 16 + 16 KiB through its address path for 256 MFMAs where the
+// one-block form (8 weight tiles x 32 row tiles) moves 8 + 32 KiB for the same 256: a fifth less request time per
+// MFMA, which is what bounds these shapes.  The two blocks of a column group run side by side on one XCD (see the
+// kernel), so the weights still cross HBM once.
+template <int EPI>
+static void launch_gemm_rows_wide(hipStream_t st, const uint4* W, int ntiles, int ktiles, const uint4* A, int row0, int M, int N,
+                                  const GemmOut& out) {
+  const int groups = ceil_div(ntiles, 16);
+  dim3 grid(16 * ceil_div(groups, 8)), blk(512);
+  LaunchEvents* ev = g_launch_events;
+  g_launch_events = nullptr;
+  if (M == 512) launch_timed(ev, gemm_rows_kernel<16, EPI, true, 8>, grid, blk, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, (float*)nullptr);
+  else launch_timed(ev, gemm_rows_kernel<16, EPI, false, 8>, grid, blk, st, W, ktiles, ntiles, A, row0, M, N, out, ktiles, (float*)nullptr);
+}
+int g_rows_wide = 1;               // test and tuning hook: 0 keeps the one-block form for wide matrices
+
 // Form of the launch above for a call of M rows: row tiles per block, plus 100 with eight weight tiles per workgroup
 // (TN = 4) instead of four; 0: use the K-share kernel (wide matrices, and shapes where it measured faster).
 LaunchEvents* g_launch_events = nullptr;
@@ -720,6 +748,11 @@ void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kt
       hipLaunchKernelGGL(norm_factor_kernel, dim3(ceil_div(mc, 4)), dim3(256), 0, st, out.nin.ssq + m0, out.nin.n_part, out.nin.stride,
                          out.nin.inv_d, out.nin.eps, inv_rms, mc);
       out.nin.inv_rms = inv_rms;
+    }
+    if (g_rows_wide && mc > 256 && ntiles >= 1536 && (epi == EPI_SWIGLU || epi == EPI_ARGMAX)) {
+      if (epi == EPI_SWIGLU) launch_gemm_rows_wide<EPI_SWIGLU>(st, Wc, ntiles, ktiles, Ac, m0, mc, N, out);
+      else launch_gemm_rows_wide<EPI_ARGMAX>(st, Wc, ntiles, ktiles, Ac, m0, mc, N, out);
+      continue;
     }
     const int bt = rows_blocks_form(ntiles, ktiles, mc);
     if (bt == 4 && launch_gemm_rows_blocks<4, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out)) continue;

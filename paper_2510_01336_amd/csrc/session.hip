@@ -1328,10 +1328,15 @@ extern "C" int ee_debug_poison_dead_kv(ee_session* s, int seq) {
   return EE_OK;
 }
 extern "C" int ee_debug_gemm_row_blocks(int row_tiles) {
+  if (row_tiles == 1000 || row_tiles == 1016) {      // wide matrices at 257..512 rows: one block of 32 row tiles / two of 16
+    g_rows_wide = row_tiles == 1016;
+    return EE_OK;
+  }
   if (row_tiles != -1 && row_tiles != 0 && row_tiles != 4 && row_tiles != 8 && row_tiles != 16 && row_tiles != 104 && row_tiles != 108) {
-    ee_set_error("row_tiles must be -1, 0, 4, 8, 16, 104 or 108");
+    ee_set_error("row_tiles must be -1, 0, 4, 8, 16, 104, 108, 1000 or 1016");
     return EE_ERR_ARG;
   }
+  if (row_tiles == -1) g_rows_wide = 1;
   g_rows_blocks_override = row_tiles;
   return EE_OK;
 }

@@ -95,7 +95,7 @@ def test_gemm_form_selector_checks_its_argument(lib):
     lib.ee_last_error.restype = ctypes.c_char_p
     for ok in (0, 4, 8, 16, 104, 108, -1):
         assert lib.ee_debug_gemm_row_blocks(ok) == 0, ok
-    for bad in (1, 12, 32, 100, -2):
+    for bad in (1, 12, 32, 100, -2, 1001):
         assert lib.ee_debug_gemm_row_blocks(bad) == -1, bad
         assert b"row_tiles" in lib.ee_last_error()
     assert lib.ee_debug_gemm_row_blocks(-1) == 0
