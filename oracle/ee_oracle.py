@@ -11,7 +11,7 @@ the paper's decoding algorithms, written from the paper:
 * per-sequence acceptance in a batch           -- Sec. "HiSpec Supports Batched Inference"
 * rejection-sampling acceptance                -- App. G (rejection_verify and the rs arguments)
 * low-rank exit heads                          -- App. I (EEModel.exit_logits, ModelSpec.head_rank)
-* a chain of intermediate verifiers            -- Future Work section (MultiLevelOracle)
+* a chain of intermediate verifiers            -- Future Work section (MultiLevelOracle; with App. G's rule: its rs arguments)
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import
 this module; the product path never does.  It shares no code with the HIP
@@ -589,6 +589,9 @@ class MultiSequence:
         self.V: List[List[int]] = [[] for _ in range(n)]         # V[0] unused
         self.S: List[int] = []
         self.H: List[List[np.ndarray]] = [[] for _ in range(n)]
+        # rejection sampling only: P[0] the distributions the draft tokens were drawn from, P[j] the exit-e_j
+        # distributions of the tokens in V[j] (the law they follow, by the lemma of App. G applied level by level)
+        self.P: List[List[np.ndarray]] = [[] for _ in range(n)]
         self.len = [0] * (n + 1)
         self.prompt_len = 0
 
@@ -610,13 +613,21 @@ class MultiLevelOracle:
     LeadingSubstringVerify against exit e_j's arg max keeps the matching prefix and e_j's own next
     token.  What is kept moves to V[j] (to C at the last level); everything below is dropped and
     the KV lengths of the groups up to j are pruned to the kept prefix (Sec. 3.2).  A level runs
-    only when every buffer below the one it checks is empty."""
+    only when every buffer below the one it checks is empty.
+
+    With uniform numbers (the `u` / `rs` arguments) the same chain runs under the acceptance rule of App. G instead
+    of arg max comparison: draft tokens are drawn from p_{L_d}; level j accepts a token of the buffer below with
+    probability min(1, p_{e_j} / p_{e_{j-1}}), replaces the first rejected one from the normalised positive part of
+    p_{e_j} - p_{e_{j-1}}, and after a fully accepted buffer draws the next token from its extra row.  By the
+    appendix's lemma the tokens a level keeps follow that level's distribution, which makes them a valid draft for
+    the next level: applied n times, what is committed follows p_{L_f}."""
 
     def __init__(self, model: EEModel):
         self.m, self.spec = model, model.spec
         self.exits = model.spec.exits
         self.n = len(self.exits) - 1
         self.last_logits: Optional[np.ndarray] = None
+        self.last_margin: float = np.inf     # rejection sampling: smallest decision margin of the last call
 
     def group(self, g: int) -> range:
         return range(self.exits[g - 1] if g else 0, self.exits[g])
@@ -646,22 +657,33 @@ class MultiLevelOracle:
         seq.S = [int(t) for t in S]
         self._draft_rows(seq, [seq.T[-1]] + seq.S)
 
-    def draft(self, seq: MultiSequence, k: int) -> List[int]:
-        """Generate(L_d, T, k): k sequential shallow passes, then the last draft token's own row."""
+    def draft(self, seq: MultiSequence, k: int, u: Optional[Sequence[float]] = None) -> List[int]:
+        """Generate(L_d, T, k): k sequential shallow passes, then the last draft token's own row.  With uniform
+        numbers u[0..k-1] the tokens are drawn from p_{L_d} and the distributions kept (App. G)."""
         assert not seq.S and not seq.H[0]
         p0 = len(seq.T) - 1
         tok, rows, S = seq.T[-1], [], []
+        seq.P[0] = []
         for j in range(k + 1):
             x = self.m.run_layers(self.group(0), self.m.embed([tok]), np.array([p0 + j]), seq.cache)
             rows.append(x[0])
             if j < k:
-                tok = int(argmax_rows(self._head(x, 0))[0])
+                lg = self._head(x, 0)
+                if u is None:
+                    tok = int(argmax_rows(lg)[0])
+                else:
+                    pd = softmax_rows(lg)[0]
+                    tok, mg = sample_inverse_cdf(pd, float(u[j]))
+                    seq.P[0].append(pd)
+                    self.last_margin = min(self.last_margin, mg) if j else mg
                 S.append(tok)
         seq.S, seq.H[0], seq.len[0] = S, rows, p0 + k + 1
         return S
 
-    def verify_level(self, seq: MultiSequence, j: int) -> Tuple[int, int, List[int]]:
-        """Returns (a, next token, the tokens that moved up: accepted prefix + next token)."""
+    def verify_level(self, seq: MultiSequence, j: int,
+                     rs: Optional[Tuple[Sequence[float], float]] = None) -> Tuple[int, int, List[int]]:
+        """Returns (a, next token, the tokens that moved up: accepted prefix + next token).  rs = (u_acc, u_res):
+        the acceptance rule of App. G with the stored distributions of the buffer below as the draft law."""
         n = self.n
         assert 1 <= j <= n
         src = seq.S if j == 1 else seq.V[j - 1]
@@ -679,7 +701,12 @@ class MultiLevelOracle:
         assert len(rows) == len(src) + 1
         Y = self.m.run_layers(self.group(j), np.stack(rows), p0 + np.arange(len(rows)), seq.cache)
         self.last_logits = self._head(Y, j)
-        a, out = leading_substring_verify(src, argmax_rows(self.last_logits))
+        if rs is None:
+            a, out = leading_substring_verify(src, argmax_rows(self.last_logits))
+        else:
+            assert len(seq.P[j - 1]) == len(src), "the buffer below was not produced by the sampling calls"
+            Pt = softmax_rows(self.last_logits)
+            a, out, self.last_margin = rejection_verify(src, np.stack(seq.P[j - 1]), Pt, rs[0], rs[1])
         moved = [int(t) for t in out]                 # accepted prefix and the verifier's own next token
         keep = len(moved)
         if j == n:
@@ -687,9 +714,12 @@ class MultiLevelOracle:
         else:
             seq.V[j] += moved
             seq.H[j] += [r for r in Y[:keep]]
+            if rs is not None:
+                seq.P[j] += [Pt[r] for r in range(keep)]
         seq.S = []
         for i in range(j):
             seq.H[i] = []
+            seq.P[i] = []
             if i >= 1:
                 seq.V[i] = []
         for g in range(j + 1):
@@ -711,8 +741,9 @@ class MultiLevelOracle:
             take = min(room, len(seq.V[j]))
             seq.V[j] = seq.V[j][:take]
             seq.H[j] = seq.H[j][:take]
+            seq.P[j] = seq.P[j][:take]
             room -= take
-        seq.S, seq.H[0] = [], []
+        seq.S, seq.H[0], seq.P[0] = [], [], []
         seq.len[0] = seq.len[1] = new_len
         for g in range(2, n + 1):
             seq.len[g] = min(seq.len[g], new_len)

@@ -113,3 +113,86 @@ def test_lemma_two_stages_composed_output_follows_final_target():
     assert _chi2_ok(counts, pf, trials)
     # a planted mistake is seen: testing against the intermediate distribution instead must fail
     assert not _chi2_ok(counts, pi, trials)
+
+
+def test_lemma_three_stages_composed_output_follows_final_target():
+    """A chain of verifiers (the hierarchy of the Future Work section under App. G's rule): draft ~ p_0, then three
+    accept-or-replace stages against p_1, p_2, p_3, each using the previous stage's law as its draft law: the emitted
+    token ~ p_3, and not ~ p_2."""
+    rng = np.random.default_rng(6)
+    n, trials = 9, 40000
+    p = [_dist(rng, n, zeros=z) for z in (1, 2, 1, 2)]
+    counts = np.zeros(n)
+    for _ in range(trials):
+        tok = [eo.sample_inverse_cdf(p[0], rng.random())[0]]
+        for j in (1, 2, 3):
+            _, tok, _ = eo.rejection_verify(tok, p[j - 1][None], p[j][None], [rng.random()], rng.random())
+        counts[tok[0]] += 1
+    assert _chi2_ok(counts, p[3], trials)
+    assert not _chi2_ok(counts, p[2], trials)
+
+
+def _chain_model(exit_extra, seed=5):
+    import synth
+    cfg = synth.tiny_config(n_layers=6, exit_draft=1, exit_inter=2, exit_extra=exit_extra, gamma=(1.0, 0.3, 0.3), vocab=64,
+                            d_model=64, n_q_heads=2, n_kv_heads=2, head_dim=32, d_ffn=96)
+    return cfg, eo.EEModel(eo.ModelSpec.from_config(cfg), synth.WeightStore(cfg, seed))
+
+
+def test_chain_sampling_with_one_verifier_is_alg2_sampling_call_for_call():
+    """MultiLevelOracle under App. G's rule with exits (L_d, L_i, L_f) takes, on the same uniform numbers, exactly
+    the steps of HiSpecOracle's sampling calls: tokens, accept counts, committed streams, lengths, decision margins."""
+    import synth
+    cfg, model = _chain_model(())
+    H, M = eo.HiSpecOracle(model), eo.MultiLevelOracle(model)
+    prompt = synth.gen_prompt(cfg.vocab, 12, 3)
+    hs_, ms = eo.Sequence_(model.spec, 200), eo.MultiSequence(model.spec, 200)
+    assert H.prefill(hs_, prompt) == M.prefill(ms, prompt)
+    rng = np.random.default_rng(8)
+    k = 3
+    for rnd in range(6):
+        u_d, u_a, u_r = rng.random(k), rng.random(k), float(rng.random())
+        assert H.draft(hs_, k, u_d) == M.draft(ms, k, u_d)
+        a, nxt = H.verify_intermediate(hs_, (u_a, u_r))
+        a2, nxt2, moved = M.verify_level(ms, 1, (u_a, u_r))
+        assert (a, nxt) == (a2, nxt2) and H.last_margin == M.last_margin
+        if rnd % 2:
+            uf_a, uf_r = rng.random(len(hs_.V)), float(rng.random())
+            f, fn, F = H.verify_full(hs_, (uf_a, uf_r))
+            f2, fn2, F2 = M.verify_level(ms, 2, (uf_a, uf_r))
+            assert (f, fn, F) == (f2, fn2, F2)
+        assert hs_.T == ms.T and hs_.len == ms.len
+    assert len(ms.C) > 13
+
+
+def test_chain_sampling_keeps_the_law_of_each_level():
+    """Two intermediate verifiers under App. G's rule: every buffer holds as many stored distributions as tokens,
+    the stored rows are the level's own softmax of the rows that predicted those tokens, an explicit prune cuts
+    tokens, rows and distributions alike, and a level refuses a buffer that the arg max calls produced."""
+    import synth
+    cfg, model = _chain_model((4,))
+    M = eo.MultiLevelOracle(model)
+    s = eo.MultiSequence(model.spec, 200)
+    M.prefill(s, synth.gen_prompt(cfg.vocab, 10, 4))
+    rng = np.random.default_rng(2)
+    k = 4
+    for rnd in range(5):
+        M.draft(s, k, rng.random(k))
+        assert len(s.P[0]) == k and all(abs(p.sum() - 1) < 1e-12 for p in s.P[0])
+        M.verify_level(s, 1, (rng.random(k), float(rng.random())))
+        assert len(s.P[1]) == len(s.V[1]) and not s.P[0]
+        if rnd % 2:
+            n1 = len(s.V[1])
+            a, nxt, moved = M.verify_level(s, 2, (rng.random(n1), float(rng.random())))
+            assert len(s.P[2]) == len(s.V[2]) == len(s.H[2]) and not s.P[1] and not s.V[1]
+            # the stored law of the last moved token is the level's softmax of the row that predicted it
+            assert np.allclose(s.P[2][-1], eo.softmax_rows(M.last_logits)[len(moved) - 1])
+    assert len(s.V[2]) >= 2
+    M.rollback(s, len(s.C) + len(s.V[2]) - 2)
+    assert len(s.P[2]) == len(s.V[2]) == len(s.H[2])
+    n2 = len(s.V[2])
+    M.verify_level(s, 3, (rng.random(n2), float(rng.random())))
+    assert not s.V[2] and not s.P[2] and s.len == [len(s.C) - 1] * 4
+    M.draft(s, k)                                   # an arg max block has no distributions to test against
+    with pytest.raises(AssertionError):
+        M.verify_level(s, 1, (rng.random(k), 0.5))
