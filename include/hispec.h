@@ -228,8 +228,9 @@ int kv_rollback(ee_session* s, int seq, int group_mask, int new_len);
  * extra row (if the block has one) supplies the next token, drawn from p.  The full verification applies the
  * rule again with V as the draft and its stored p_{L_i} rows as q.  All uniform numbers are inputs: host
  * arrays of floats in [0, 1) (EE_ERR_ARG otherwise).  Draws are by inverse CDF over the token ids in order.
- * The distributions are kept in a caller-owned device arena of ee_sampling_bytes() bytes (2 * batch *
- * max_rows * vocab floats and the uniform numbers), attached once per session; 256-byte aligned.
+ * The distributions are kept in a caller-owned device arena of ee_sampling_bytes() bytes (one store of batch *
+ * max_rows * vocab floats per exit below L_f -- two for Alg. 2 -- and the uniform numbers), attached once per session;
+ * 256-byte aligned.
  * The sampling calls and the arg max calls may not be mixed within one round (EE_ERR_STATE). */
 size_t ee_sampling_bytes(const ee_session* s);
 int ee_sampling_attach(ee_session* s, void* dev_arena, size_t arena_bytes);
@@ -244,6 +245,15 @@ int ee_verify_intermediate_rs(ee_session* s, const float* u_acc, int u_stride, c
  * Otherwise as ee_verify_full. */
 int ee_verify_full_rs(ee_session* s, const uint8_t* active, const float* u_acc, int u_stride, const float* u_res,
                       int32_t* n_accept, int32_t* next_token, int32_t* committed, int32_t* n_committed);
+/* The same rule at a further verifier exit (models with n_extra_exits > 0; level in 2..ee_n_levels(), the last being
+ * ee_verify_full_rs): the tokens waiting below the level, distributed as the exit below it (their stored
+ * distributions), are the draft, exit `level`'s distribution the target; what is kept follows exit `level`'s
+ * distribution and waits for the next level with that law stored.  By the appendix's lemma applied level by level the
+ * committed tokens follow p_{L_f}.  u_acc: host [batch, u_stride] (u_stride >= the longest buffer taking part), u_res:
+ * host [batch].  EE_ERR_STATE if the waiting tokens were not produced by the sampling calls.  Otherwise as
+ * ee_verify_level. */
+int ee_verify_level_rs(ee_session* s, int level, const uint8_t* active, const float* u_acc, int u_stride, const float* u_res,
+                       int32_t* n_accept, int32_t* next_token, int32_t* moved, int32_t* n_moved);
 /* Test support: n rows from row0 of one sequence's stored distributions (which = 0: the draft distributions of
  * the pending block, 1: the L_i distributions of the tentative tokens), host out [n, vocab].  After a sampling
  * verify call ee_debug_last_logits returns that call's target distributions instead of logits. */

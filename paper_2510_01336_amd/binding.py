@@ -16,7 +16,7 @@ __all__ = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_seq_release", "ee_free_pages", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_intermediate_static", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
-    "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
+    "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_verify_level_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_gemm_row_blocks", "ee_debug_attention_split_pages", "ee_debug_stream_copy", "ee_last_error",
     "EE_F32", "EE_BF16", "TENSOR_IDS", "EXPORTED_SYMBOLS",
@@ -31,7 +31,7 @@ EXPORTED_SYMBOLS = [
     "ee_model_bytes", "ee_model_load", "ee_model_set_tensor", "ee_model_get_tensor_rows", "ee_model_free",
     "ee_session_bytes", "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_seq", "ee_seq_release", "ee_free_pages", "ee_decode_ar", "ee_draft", "ee_draft_inject",
     "ee_verify_intermediate", "ee_verify_intermediate_static", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
-    "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
+    "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_verify_level_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
     "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_gemm_row_blocks", "ee_debug_attention_split_pages", "ee_debug_stream_copy", "ee_last_error",
 ]
@@ -93,6 +93,7 @@ def _load():
         "ee_debug_read_dist": (C.c_int, [vp, C.c_int, C.c_int, C.c_int, C.c_int, f32p]),
         "ee_verify_intermediate_rs": (C.c_int, [vp, f32p, C.c_int, f32p, i32p, i32p]),
         "ee_verify_full_rs": (C.c_int, [vp, C.POINTER(C.c_uint8), f32p, C.c_int, f32p, i32p, i32p, i32p, i32p]),
+        "ee_verify_level_rs": (C.c_int, [vp, C.c_int, C.POINTER(C.c_uint8), f32p, C.c_int, f32p, i32p, i32p, i32p, i32p]),
         "ee_get_lengths": (C.c_int, [vp, i32p]),
         "ee_get_counts": (C.c_int, [vp, i32p, i32p]),
         "ee_get_tokens": (C.c_int, [vp, C.c_int, i32p, C.c_int, i32p]),
@@ -344,6 +345,20 @@ def ee_verify_full_rs(session: int, batch: int, max_rows: int, u_acc: np.ndarray
     return a, n, [com[b, :nc[b]].tolist() for b in range(batch)]
 
 
+def ee_verify_level_rs(session: int, level: int, batch: int, max_rows: int, u_acc: np.ndarray, u_res: np.ndarray,
+                       active: Optional[Sequence[int]] = None):
+    u_acc, u_res = _f32c(u_acc).reshape(batch, -1), _f32c(u_res).reshape(batch)
+    a, n, nc = np.empty(batch, np.int32), np.empty(batch, np.int32), np.empty(batch, np.int32)
+    com = np.zeros((batch, max_rows + 1), np.int32)
+    act = None
+    if active is not None:
+        act_arr = np.ascontiguousarray(active, dtype=np.uint8)
+        act = act_arr.ctypes.data_as(C.POINTER(C.c_uint8))
+    _chk(lib.ee_verify_level_rs(session, level, act, _p_f32(u_acc), u_acc.shape[1], _p_f32(u_res), _p_i32(a), _p_i32(n),
+                                _p_i32(com), _p_i32(nc)))
+    return a, n, [com[b, :nc[b]].tolist() for b in range(batch)]
+
+
 def kv_rollback(session: int, seq: int, group_mask: int, new_len: int) -> None:
     _chk(lib.kv_rollback(session, seq, group_mask, new_len))
 
@@ -516,6 +531,9 @@ class Session:
 
     def verify_full_rs(self, u_acc: np.ndarray, u_res: np.ndarray, active=None):
         return ee_verify_full_rs(self.handle, self.batch, self.max_rows, u_acc, u_res, active)
+
+    def verify_level_rs(self, level: int, u_acc: np.ndarray, u_res: np.ndarray, active=None):
+        return ee_verify_level_rs(self.handle, level, self.batch, self.max_rows, u_acc, u_res, active)
 
     def rollback(self, seq: int, group_mask: int, new_len: int) -> None:
         kv_rollback(self.handle, seq, group_mask, new_len)

@@ -16,6 +16,7 @@ struct SeqState {
   int len[EE_MAX_GROUPS] = {0, 0, 0, 0, 0, 0, 0};     // KV length per layer group
   int n_hd = 0;               // buffered L_d hidden rows (pending draft block incl. bonus row)
   int n_pi = 0;               // rejection sampling: tokens of V whose L_i distribution is stored
+  int n_pu[4] = {0, 0, 0, 0}; // ... and tokens of the buffers at the further verifier exits (levels 2..n-1) whose distribution is stored
   bool sampled = false;       // the pending draft block was drawn from p_{L_d} (its distributions are stored)
   std::vector<int> pages;     // block table
   bool started = false;
@@ -47,6 +48,7 @@ struct ee_session {
   // rejection-sampling acceptance (attached separately): the distributions the draft tokens were drawn from,
   // the L_i distributions of the tokens in V (rows [batch][max_rows][vocab]), and the call's uniform numbers
   float *Pd = nullptr, *Pi = nullptr, *u_dev = nullptr;
+  float* Pup[4] = {nullptr, nullptr, nullptr, nullptr};   // the same for the buffers of levels 2..n-1
   bool need_logits = false;
   float *part_o = nullptr, *part_ml = nullptr, *pmax = nullptr, *ssq = nullptr, *gemm_part = nullptr, *inv_rms = nullptr;
   // auxiliary exit heads: adapter output rows z [maxM][d], its rank-r intermediate (fp32 rows and, for bf16
@@ -1001,6 +1003,8 @@ extern "C" int ee_verify_intermediate_rs(ee_session* s, const float* u_acc, int 
 // verifier exits, the levels in between (the hierarchy of the paper's Future Work section)
 // ---------------------------------------------------------------------------------------------
 static float* level_rows(const ee_session* s, int j) { return j == 0 ? s->Hd : (j == 1 ? s->Hi : s->Hup[j - 2]); }
+// stored distributions of the tokens in level j's buffer (0: the draft block's)
+static float* level_dist(const ee_session* s, int j) { return j == 0 ? s->Pd : (j == 1 ? s->Pi : s->Pup[j - 2]); }
 
 // Level j (2 <= j <= n) takes the buffer of level j-1 as its draft: V for j = 2, else the tail C[cut[j]..) (every
 // buffer below it must be empty).  The buffered rows of exit j-1 plus, in bonus mode, one row for the buffer's
@@ -1016,7 +1020,6 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
   const std::vector<int>& ex = s->m->exits;
   const int bonus = c.bonus_full ? 1 : 0;
   const bool rs = u_acc != nullptr;
-  if (rs && n != 2) { ee_set_error("the sampling calls support one intermediate verifier"); return EE_ERR_STATE; }
   std::vector<int> act(s->B, 0), m_src(s->B, 0), base(s->B, 0);
   int any = 0;
   for (int b = 0; b < s->B; ++b) {
@@ -1030,8 +1033,8 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
     if (j > 2 && (!q.V.empty() || q.cut[j - 1] != (int)q.C.size())) {
       ee_set_error("sequence %d: the buffers below level %d must be verified first", b, j - 1); return EE_ERR_STATE;
     }
-    if (rs && q.n_pi != (int)q.V.size()) {
-      ee_set_error("sequence %d: the tentative tokens were not produced by the sampling calls", b);
+    if (rs && (j == 2 ? q.n_pi : q.n_pu[j - 3]) != m_src[b]) {
+      ee_set_error("sequence %d: the tokens waiting below level %d were not produced by the sampling calls", b, j);
       return EE_ERR_STATE;
     }
     // level j's buffer is level j+1's draft: its rows sit in a [max_rows] slab per sequence together with the
@@ -1101,11 +1104,14 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
   exit_head(s, p.M, j);
   s->need_logits = false;
   if (j < n) KF(KF_COPY, k_copy_rows(s->st, level_rows(s, j), mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));   // keep exit j's rows
-  if (rs) {      // second stage of App. G: V, distributed as p_{L_i}, is the draft; p_{L_f} the target
+  if (rs) {      // a further stage of App. G: the buffer below, distributed as exit j-1's p, is the draft; exit j's p the target
+    const float* q_below = level_dist(s, j - 1);
     KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->LOGITS, nullptr, 0, p.M, c.vocab));
-    KF(KF_ACCEPT, k_rs_accept(s->st, s->LOGITS, s->Pi, s->max_rows, c.vocab, mt, s->cand_stride, s->B, s->u_dev, s->max_rows, s->out_dev));
-    KF(KF_ACCEPT, k_rs_draw(s->st, s->LOGITS, s->Pi, s->max_rows, c.vocab, mt, s->B, s->out_dev, s->u_dev + (size_t)s->B * s->max_rows,
+    KF(KF_ACCEPT, k_rs_accept(s->st, s->LOGITS, q_below, s->max_rows, c.vocab, mt, s->cand_stride, s->B, s->u_dev, s->max_rows, s->out_dev));
+    KF(KF_ACCEPT, k_rs_draw(s->st, s->LOGITS, q_below, s->max_rows, c.vocab, mt, s->B, s->out_dev, s->u_dev + (size_t)s->B * s->max_rows,
                             s->out_dev + s->B));
+    // exit j's distributions of the rows that may stay: the law of the tokens that wait for exit j+1
+    if (j < n) KF(KF_COPY, k_copy_rows(s->st, level_dist(s, j), mt.row_dst, 0, s->LOGITS, nullptr, p.M, c.vocab));
   } else {
     KF(KF_ACCEPT, k_accept(s->st, s->vtok, mt, s->cand_stride, s->B, s->out_dev, s->out_dev + s->B));
   }
@@ -1123,8 +1129,11 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
     if (f < p.m[b]) out[cnt++] = next_token[b];
     n_committed[b] = cnt;
     if (j > 2) q.C.resize(q.cut[j]);
+    const int held = j < n ? q.cut[j] - q.cut[j + 1] : 0;      // tokens level j's buffer held before this call
     q.C.insert(q.C.end(), out, out + cnt);
     q.V.clear(); q.n_pi = 0;
+    for (int i = 2; i < j; ++i) q.n_pu[i - 2] = 0;
+    if (j < n) q.n_pu[j - 2] = (rs && q.n_pu[j - 2] == held) ? held + cnt : -1;   // -1: holds tokens without a stored law
     for (int g = 2; g <= j; ++g) q.cut[g] = (int)q.C.size();
     for (int g = 0; g <= j; ++g) q.len[g] = (int)q.C.size() - 1;
     trim_pages(s, b);
@@ -1143,6 +1152,12 @@ extern "C" int ee_verify_level(ee_session* s, int level, const uint8_t* active, 
   return verify_upper_impl(s, level, active, n_accept, next_token, moved, n_moved, nullptr, 0, nullptr);
 }
 
+extern "C" int ee_verify_level_rs(ee_session* s, int level, const uint8_t* active, const float* u_acc, int u_stride, const float* u_res,
+                                  int32_t* n_accept, int32_t* next_token, int32_t* moved, int32_t* n_moved) {
+  if (!s || !u_acc || !u_res) { ee_set_error("null argument"); return EE_ERR_ARG; }
+  return verify_upper_impl(s, level, active, n_accept, next_token, moved, n_moved, u_acc, u_stride, u_res);
+}
+
 extern "C" int ee_n_levels(const ee_session* s) { return s ? s->n_levels : -1; }
 
 extern "C" int ee_verify_full_rs(ee_session* s, const uint8_t* active, const float* u_acc, int u_stride, const float* u_res,
@@ -1156,7 +1171,7 @@ extern "C" int ee_verify_full_rs(ee_session* s, const uint8_t* active, const flo
 // ---------------------------------------------------------------------------------------------
 static size_t sampling_floats(const ee_session* s) {
   const size_t rows = (size_t)s->B * s->max_rows;
-  return 2 * rows * s->m->cfg.vocab + rows + s->B + 64;
+  return (size_t)s->n_levels * rows * s->m->cfg.vocab + rows + s->B + 64;     // one store per level below L_f, and the uniform numbers
 }
 extern "C" size_t ee_sampling_bytes(const ee_session* s) { return s ? sampling_floats(s) * sizeof(float) : 0; }
 
@@ -1165,7 +1180,10 @@ extern "C" int ee_sampling_attach(ee_session* s, void* dev_arena, size_t arena_b
   if (arena_bytes < sampling_floats(s) * sizeof(float)) { ee_set_error("sampling arena too small"); return EE_ERR_ARG; }
   const size_t rows = (size_t)s->B * s->max_rows;
   float* f = (float*)dev_arena;
-  s->Pd = f; s->Pi = f + rows * s->m->cfg.vocab; s->u_dev = s->Pi + rows * s->m->cfg.vocab;
+  const size_t store = rows * s->m->cfg.vocab;
+  s->Pd = f; s->Pi = f + store;
+  for (int j = 2; j < s->n_levels; ++j) s->Pup[j - 2] = f + (size_t)j * store;
+  s->u_dev = f + (size_t)s->n_levels * store;
   return EE_OK;
 }
 
@@ -1200,6 +1218,7 @@ extern "C" int kv_rollback(ee_session* s, int seq, int group_mask, int new_len) 
     q.V.resize(nT - q.C.size());
   }
   q.n_pi = std::min(q.n_pi, (int)q.V.size());
+  for (int g = 2; g < n; ++g) q.n_pu[g - 2] = std::min(q.n_pu[g - 2], q.cut[g] - q.cut[g + 1]);
   q.n_hd = 0; q.S.clear(); q.sampled = false;
   q.len[0] = q.len[1] = new_len;
   trim_pages(s, seq);

@@ -185,3 +185,78 @@ def test_bf16_distributions_and_decisions():
                 r0 += n
     assert checked > 10 * max(1, skipped)
     sess.close(); model.close()
+
+
+def test_chain_of_verifiers_under_the_sampling_rule_matches_oracle():
+    """App. G's acceptance at every exit of a chain (L_d, L_i, one further verifier, L_f): drafting by sampling, then
+    levels 1, 2 and 3 with the stochastic rule, in lockstep with the oracle's MultiLevelOracle on the same uniform
+    numbers; decisions equal wherever the oracle's decision margin clears what fp32 summation order can move."""
+    import paper_2510_01336_amd as hs
+    cfg = synth.EEConfig(n_layers=8, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_ffn=688, vocab=1024,
+                         exit_draft=2, exit_inter=4, exit_extra=(6,), rope_theta=10000.0, dtype="f32", gamma=(1.0, 0.3, 0.3))
+    k, ctxs = 4, [40, 23]
+    B, rows, margin = len(ctxs), 4 * (k + 2), RS_MARGIN["f32"]
+    W = synth.WeightStore(cfg, 77)
+    M = eo.MultiLevelOracle(eo.EEModel(eo.ModelSpec.from_config(cfg), W))
+    prompts = [synth.gen_prompt(cfg.vocab, n, 300 + b) for b, n in enumerate(ctxs)]
+    model, sess = gpu_side(cfg, 77, B, max(ctxs) + 16 * rows, rows)
+    assert sess.n_levels() == 3
+    sess.enable_sampling()
+    first = sess.prefill(prompts)
+    seqs = []
+    for b, p in enumerate(prompts):
+        s = eo.MultiSequence(M.spec, max(ctxs) + 16 * rows)
+        M.prefill(s, p)
+        s.C[-1] = int(first[b])
+        seqs.append(s)
+    rng = np.random.default_rng(9)
+    plan = [[1], [1, 2], [1, 2, 3], [1, 2], [1], [1, 2, 3]]
+
+    def trial(s, levels, u):
+        t, worst = copy.deepcopy(s), np.inf
+        M.draft(t, k, u["d"])
+        worst = min(worst, M.last_margin)
+        for lv in levels:
+            M.verify_level(t, lv, (u[lv][0], u[lv][1]))
+            worst = min(worst, M.last_margin)
+        return worst
+
+    accepted = rejected = 0
+    for levels in plan:
+        for _ in range(60):      # redraw the round's uniform numbers until every decision clears the margin
+            us = [{"d": rng.random(k, np.float32), **{lv: (rng.random(rows, np.float32), float(rng.random(dtype=np.float32))) for lv in levels}}
+                  for _b in range(B)]
+            if all(trial(s, levels, us[b]) > margin for b, s in enumerate(seqs)):
+                break
+        else:
+            pytest.fail("no draw cleared the margin")
+        gS = sess.draft_sample(k, np.stack([u["d"] for u in us]))
+        for b, s in enumerate(seqs):
+            assert gS[b].tolist() == M.draft(s, k, us[b]["d"])
+        for lv in levels:
+            u_a = np.stack([us[b][lv][0] for b in range(B)])
+            u_r = np.array([us[b][lv][1] for b in range(B)], np.float32)
+            if lv == 1:
+                ga, gn = sess.verify_intermediate_rs(u_a[:, :k], u_r)
+            elif lv < 3:
+                ga, gn, gm = sess.verify_level_rs(lv, u_a, u_r)
+            else:
+                ga, gn, gm = sess.verify_full_rs(u_a, u_r)
+            for b, s in enumerate(seqs):
+                n_src = len(s.S) if lv == 1 else len(s.V[lv - 1])
+                a, nxt, moved = M.verify_level(s, lv, (us[b][lv][0], us[b][lv][1]))
+                assert (int(ga[b]), int(gn[b])) == (a, nxt), (levels, lv, b)
+                if lv > 1:
+                    assert gm[b] == moved
+                accepted += a; rejected += n_src - a
+            lens = sess.lengths()
+            for b, s in enumerate(seqs):
+                assert list(lens[b]) == s.len and sess.tokens(b).tolist() == s.T
+    assert accepted > 0 and rejected > 0
+    # a buffer filled by the arg max calls has no stored law: the sampling call of the level above refuses it
+    sess.draft(k); sess.verify_intermediate(); sess.verify_level(2)
+    with pytest.raises(hs.EEError) as e:
+        sess.verify_full_rs(rng.random((B, rows), np.float32), rng.random(B, np.float32))
+    assert e.value.code == -2
+    sess.verify_full()
+    sess.close(); model.close()
