@@ -344,16 +344,23 @@ def cpu_baseline(w):
         seqs.append(seq)
     blocks = [[w["blocks"][r][b] for r in range(w["rounds"])] for b in range(batch)]
 
-    def step_all():
+    timed_seqs = [0]
+
+    def step_all(budget_s=25.0):
+        """The step, sequence by sequence; stops early (and says so) once the time budget is spent."""
+        t_begin = time.perf_counter()
         for b in range(batch):
             _oracle_step(orc, [seqs[b]], blocks[b], [ctxs[b]])
+            timed_seqs[0] = b + 1
+            if time.perf_counter() - t_begin > budget_s:
+                break
 
     cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     for name in synth.model.LAYER_TENSORS + ("gfinal", "head"):     # untimed: generate the weights
         store.get(name, cfg.exit_draft)
     t0 = time.perf_counter()
     step_all()
-    t_step = time.perf_counter() - t0
+    t_step = (time.perf_counter() - t0) * batch / timed_seqs[0]      # (scaled when the budget cut the batch short)
     # one thread: the first sequence's block-parallel G1 pass (exit_draft layer passes of k+1 rows), scaled by layer
     # passes to the whole step (the exit heads, about a tenth of the step, are left out of this figure)
     passes_step = batch * (w["rounds"] * cfg.exit_inter + (cfg.n_layers - cfg.exit_inter) + (cfg.exit_inter if w["bonus_full"] else 0))
@@ -366,7 +373,9 @@ def cpu_baseline(w):
     return {"value": batch * k * w["rounds"] / t_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"one whole step of the workload ({passes_step} layer passes and {batch * (w['rounds'] + 1)} exit heads through "
                       f"the oracle's own draft_inject / verify_intermediate / verify_full / rollback, random KV context, "
-                      f"one generated layer's weights serving every layer) timed once: {t_step:.1f} s; float64 numpy",
+                      f"one generated layer's weights serving every layer) timed once"
+                      + (f" for {timed_seqs[0]} of {batch} sequences and scaled" if timed_seqs[0] < batch else "")
+                      + f": {t_step:.1f} s; float64 numpy",
             "one_thread": {"value": batch * k * w["rounds"] / t_step_1, "unit": "tokens/s", "cores": 1,
                            "sample": f"first sequence's block-parallel G1 pass ({cfg.exit_draft} layer passes) timed once at one "
                                      f"thread: {t_1:.1f} s, scaled by layer passes to a whole step ({t_step_1:.0f} s, exit "
