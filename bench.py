@@ -382,6 +382,35 @@ def cpu_baseline(w):
                                      f"heads left out)"}}
 
 
+def read_floor(w, acc, steps):
+    """What a kernel that only fetches the same bytes takes: plain reads of each projection's weight bytes, back to
+    back on the library's stream in a layer's order, each launch timed by events attached to its dispatch
+    (ee_debug_read_floor).  A dependent launch of tens of MB runs well under the peak rate whatever its arithmetic, so
+    this -- not bytes / 8 TB/s -- is what the projections can be held against; their own mean launch times of the
+    instrumented pass stand beside it."""
+    import torch
+    import paper_2510_01336_amd as hs
+    cfg = w["cfg"]
+    es = 2 if cfg.dtype == "bf16" else 4
+    d, dh = cfg.d_model, cfg.head_dim
+    sizes = {"gemm_qkv": (cfg.n_q_heads + 2 * cfg.n_kv_heads) * dh * d * es, "gemm_o": cfg.n_q_heads * dh * d * es,
+             "gemm_gate_up": 2 * cfg.d_ffn * d * es, "gemm_down": cfg.d_ffn * d * es, "gemm_head": cfg.vocab * d * es}
+    if cfg.head_rank:
+        del sizes["gemm_head"]               # (low-rank exit heads: two small products, not one stream of this size)
+    names = list(sizes)
+    buf = torch.full((sum(sizes.values()),), 3, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    us = hs.ee_debug_read_floor(buf.data_ptr(), [sizes[n] for n in names], 20, w["model"].stream)
+    del buf
+    out = {}
+    for n, t in zip(names, us):
+        k_ms, k_n = acc.get(n, (0.0, 0))
+        out[n] = {"weight_bytes": sizes[n], "plain_read_us": t, "plain_read_GBs": sizes[n] / t / 1e3,
+                  "kernel_us": 1e3 * k_ms / k_n if k_n else None,
+                  "plain_read_over_kernel": t / (1e3 * k_ms / k_n) if k_n else None}
+    return out
+
+
 def calibration_copy(stream_ptr):
     """One plain device-to-device copy of known size (reads and writes CALIBRATION_COPY_BYTES each): the
     reference dispatch for scaling hardware byte counters when this script runs under rocprofv3 --pmc."""
@@ -489,6 +518,7 @@ def main():
         "step_bytes": sb, "step_hbm_frac": sb / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms_per_step": kernel_ms,
     }
+    out["read_floor"] = read_floor(w, acc, args.steps)
     out["context_build"] = context_build(w)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

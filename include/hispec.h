@@ -306,6 +306,15 @@ int ee_debug_attention_split_pages(int pages);
  * calibrate hardware byte counters when the HBM traffic of the other kernels is measured. */
 int ee_debug_stream_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
 
+/* Plain streaming reads of known size, timed: buf_dev holds sum(sizes) bytes (16-byte aligned, sizes multiples of
+ * 16, 1 <= n <= 16); per round the n regions are read back to back on `stream` by a kernel that only fetches them
+ * (behind one untimed read), each launch timed by events attached to its dispatch; us_out[i] (host) = mean
+ * microseconds of region i over `reps` rounds after two untimed ones.  Blocks until done.  This is the measured
+ * floor for a weight-streaming projection of that size launched behind another kernel -- the rate a dependent launch
+ * of tens of MB can reach on the chip, which is below the peak rate -- and is what the measurement script prints
+ * beside each projection's own time.  EE_ERR_ARG for bad arguments, EE_ERR_HIP if a launch or an event fails. */
+int ee_debug_read_floor(const void* buf_dev, const size_t* sizes, int n, int reps, float* us_out, void* stream);
+
 const char* ee_last_error(void);
 
 #ifdef __cplusplus

@@ -18,7 +18,7 @@ __all__ = [
     "ee_verify_intermediate", "ee_verify_intermediate_static", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_verify_level_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
-    "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_gemm_row_blocks", "ee_debug_attention_split_pages", "ee_debug_stream_copy", "ee_last_error",
+    "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_gemm_row_blocks", "ee_debug_attention_split_pages", "ee_debug_stream_copy", "ee_debug_read_floor", "ee_last_error",
     "EE_F32", "EE_BF16", "TENSOR_IDS", "EXPORTED_SYMBOLS",
 ]
 
@@ -33,7 +33,7 @@ EXPORTED_SYMBOLS = [
     "ee_verify_intermediate", "ee_verify_intermediate_static", "ee_verify_full", "ee_verify_level", "ee_n_levels", "kv_rollback", "ee_sampling_bytes", "ee_sampling_attach",
     "ee_draft_sample", "ee_verify_intermediate_rs", "ee_verify_full_rs", "ee_verify_level_rs", "ee_debug_read_dist", "ee_get_lengths", "ee_get_counts", "ee_get_tokens",
     "ee_debug_enable_logits", "ee_debug_last_logits", "ee_debug_last_hidden", "ee_debug_read_kv", "ee_debug_write_kv",
-    "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_gemm_row_blocks", "ee_debug_attention_split_pages", "ee_debug_stream_copy", "ee_last_error",
+    "ee_debug_poison_dead_kv", "ee_debug_time_kernels", "ee_debug_kernel_times", "ee_debug_gemm_row_blocks", "ee_debug_attention_split_pages", "ee_debug_stream_copy", "ee_debug_read_floor", "ee_last_error",
 ]
 
 
@@ -108,6 +108,7 @@ def _load():
         "ee_debug_attention_split_pages": (C.c_int, [C.c_int]),
         "ee_debug_kernel_times": (C.c_int, [vp, i32p, C.POINTER(C.c_char_p), f32p, i32p]),
         "ee_debug_stream_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
+        "ee_debug_read_floor": (C.c_int, [vp, C.POINTER(C.c_size_t), C.c_int, C.c_int, C.POINTER(C.c_float), vp]),
         "ee_last_error": (C.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -435,6 +436,15 @@ def ee_debug_kernel_times(session: int) -> dict:
 
 def ee_debug_stream_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream_ptr: int) -> None:
     _chk(lib.ee_debug_stream_copy(dst_ptr, src_ptr, nbytes, stream_ptr))
+
+
+def ee_debug_read_floor(buf_ptr: int, sizes, reps: int, stream_ptr: int) -> list:
+    """Mean microseconds of a plain read of each region (sizes in bytes, laid out one after another from buf_ptr)."""
+    n = len(sizes)
+    arr = (C.c_size_t * n)(*[int(x) for x in sizes])
+    out = (C.c_float * n)()
+    _chk(lib.ee_debug_read_floor(buf_ptr, arr, n, int(reps), out, stream_ptr))
+    return [float(x) for x in out]
 
 
 # ---- arena owners ---------------------------------------------------------------------------------

@@ -13,7 +13,8 @@ void k_accept(hipStream_t st, const int* v, const CallMeta& meta, int cand_strid
 // sequential drafting, one row per sequence: tok_next[r] = v[r]; draft_out[row_seq[r]*stride + j] = v[r]
 void k_take_token(hipStream_t st, const int* v, const int* row_seq, int M, int* tok_next, int* draft_out, int stride, int j);
 // cos/sin table for the rows of this call: cs[r][i] = (cos, sin)(pos_r * inv_freq[i]), evaluated in double
-void k_rope_table(hipStream_t st, const int* row_pos, int pos_add, const double* inv_freq, float2* cs, int M, int half);
+void k_rope_table(hipStream_t st, const CallMeta& mt, int pos_add, const double* inv_freq, float2* cs, int M, int half, int pps,
+                  int4* rowinfo);   // rowinfo[r] = (first q-tile of the row's sequence, row inside the sequence, KV page, slot in page)
 void k_fill_nan_dead_kv(hipStream_t st, bool bf16, void* kv, const int* pages, int n_owned_pages, int len,
                         int layer0, int layer1, int n_pages, int n_kv, int D);
 void k_read_kv(hipStream_t st, bool bf16, const void* kv, const int* pages, int layer, int pos0, int n,
@@ -51,8 +52,8 @@ struct NormOut {
 // their cache pages.
 struct RopeOut {
   const float2* cs = nullptr;   // [rows][D/2] (cos, sin) of every row's position
-  const int *row_seq = nullptr, *row_pos = nullptr, *seq_row0 = nullptr, *seq_qt0 = nullptr, *block_table = nullptr;
-  int pos_add = 0, Hq = 0, Hkv = 0, D = 0, layer = 0, n_pages = 0, pps = 0, total_qt = 0;
+  const int4* rowinfo = nullptr;   // [rows] (first q-tile of the row's sequence, row inside the sequence, KV page, slot in page)
+  int Hq = 0, Hkv = 0, D = 0, layer = 0, n_pages = 0, total_qt = 0;
   bf16_t *Q = nullptr, *kv = nullptr;
 };
 struct GemmOut {

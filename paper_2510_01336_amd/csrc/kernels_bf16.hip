@@ -114,17 +114,16 @@ __device__ inline void epi_prefetch(EpiPre& p, const GemmOut& out, int task, int
     const RopeOut& R = out.rope;
     const int half = R.D >> 1, tph = R.D >> 5;
     const int h = task / tph, f = (task % tph) * 16 + 4 * g;
-    const int sq = R.row_seq[row];
+    const int4 ri = R.rowinfo[row];              // (every operand here is indexed by the row alone: no dependent loads)
     if (h < R.Hq + R.Hkv) {
       const float4* c4 = (const float4*)(R.cs + (size_t)row * half + f);
       p.rc01 = c4[0]; p.rc23 = c4[1];
     }
     if (h < R.Hq) {
-      const int q = (row - R.seq_row0[sq]) * (R.Hq / R.Hkv) + h % (R.Hq / R.Hkv);
-      p.r_a = R.seq_qt0[sq] + (q >> 4); p.r_b = q & 15;
+      const int q = ri.y * (R.Hq / R.Hkv) + h % (R.Hq / R.Hkv);
+      p.r_a = ri.x + (q >> 4); p.r_b = q & 15;
     } else {
-      const int pos = R.row_pos[row] + R.pos_add;
-      p.r_a = R.block_table[sq * R.pps + pos / EE_PAGE]; p.r_b = pos % EE_PAGE;
+      p.r_a = ri.z; p.r_b = ri.w;
     }
   }
 }
@@ -230,18 +229,31 @@ struct Frags {
   u32x4 x[MT][U];
 };
 
+// Requests the fragments of k-tiles kt .. kt+U-1 (indices past `last` repeat the last k-tile: valid memory; the
+// caller leaves those out of the product).  Nothing here touches a loaded value, so the wave does not wait.
 template <int MT, int NB, int U>
-__device__ inline void load_frags(Frags<MT, NB, U>& f, const u32x4* const (&wp)[NB], const u32x4* ap, int ktiles, int kt, int kt1) {
-  const u32x4 z = {0u, 0u, 0u, 0u};
+__device__ inline void load_frags(Frags<MT, NB, U>& f, const u32x4* const (&wp)[NB], const u32x4* ap, int ktiles, int kt, int last) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    bool ok = kt + u < kt1;
-    int k = ok ? kt + u : kt1 - 1;
+    const int k = min(kt + u, last);
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) { u32x4 t = __builtin_nontemporal_load(&wp[nb][(size_t)k * 64]); f.w[nb][u] = ok ? t : z; }
+    for (int nb = 0; nb < NB; ++nb) f.w[nb][u] = __builtin_nontemporal_load(&wp[nb][(size_t)k * 64]);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) f.x[mt][u] = ap[((size_t)mt * ktiles + k) * 64];
   }
+}
+// acc += the product over the k-tiles kt .. kt+U-1 held in f; GUARD: only those below kt1 (kt and kt1 must be
+// uniform in a way the compiler can see, see the kernel)
+template <int MT, int NB, int U, bool GUARD>
+__device__ inline void mma_frags(f32x4 (&acc)[NB][MT], const Frags<MT, NB, U>& f, int kt, int kt1) {
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (!GUARD || kt + u < kt1) {         // (uniform)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = mfma16(f.w[nb][u], f.x[mt][u], acc[nb][mt]);
+    }
 }
 
 template <int MT, int EPI, int U>
@@ -251,7 +263,11 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
   constexpr int NB = (EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? 2 : 1;
   __shared__ float4 red[EE_MAX_WAVES - 1][NB * MT][64];
   __shared__ float ssq_red[EE_MAX_WAVES][MT * 16];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  // The wave's number is taken through a scalar register: the compiler then knows that everything derived from it (the
+  // task, the K share and above all the conditions around the MFMAs of a short last group) is uniform and branches
+  // on it.  A condition it takes for divergent it may turn into an EXEC mask without a branch -- and the matrix
+  // instructions ignore EXEC, so a masked-off MFMA would still add its product.
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
   const int task = blockIdx.x * (nw / ksplit) + wave / ksplit, kpart = wave % ksplit;
   const bool active = task < ntasks;
   const int per = (ktiles + ksplit - 1) / ksplit;
@@ -270,68 +286,90 @@ __global__ __launch_bounds__(64 * EE_MAX_WAVES) void gemm_skinny_kernel(const ui
   const u32x4* ap = (const u32x4*)A + (size_t)(row0 >> 4) * ktiles * 64 + lane;
   Frags<MT, NB, U> cur;
 
-  // Epilogue operands that do not depend on the product (residual rows and gains; rotary table and page
-  // lookups) are requested by the epilogue wave now, so their latency is not paid after the reduction.
+  // Order of the requests: the partial sums of squares of the deferred RMSNorm (small, mostly L2), then the first
+  // weight fragments, then the epilogue's operands; the sums are formed once their loads are back, which frees their
+  // registers for the second set of fragments.  The load counter is in order, so nothing here waits for the weights.
+  constexpr int SB = 16 / MT;   // 16-byte loads per lane and m-tile in one batch (64 registers in all)
+  const bool normed = out.nin.ssq != nullptr && active;
   const int mc = lane & 15;
   const bool epi_wave = active && kpart == 0;
   EpiPre pre[MT];
-  if (epi_wave) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) epi_prefetch<EPI>(pre[mt], out, task, row0 + mt * 16 + mc, mt * 16 + mc < M, lane);
-  }
-
-  // Deferred RMSNorm: sum of squares of row mt*16 + lane%16 from the producer's per-tile partials, in a
-  // fixed order.  The ksplit waves of a task each sum a contiguous share of the partials (lane group g
-  // takes every 4th); the first batch is requested before the first weight fragments and added once
-  // those are in flight, so its (L2) latency hides under the first HBM fetch.
-  constexpr int SB = 64 / MT;   // partials per lane, m-tile and batch: d_model 4096 is one batch at 16 rows
-  const bool normed = out.nin.ssq != nullptr && active;
   float ssl[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) ssl[mt] = 0.f;
-  if (normed) {
-    const int np = out.nin.n_part, cp = (np + ksplit - 1) / ksplit;
-    const int c0 = kpart * cp + (lane >> 4), c1 = min(np, (kpart + 1) * cp);
-    const float* p = out.nin.ssq + row0 + (lane & 15);
-    float t[MT][SB];
+  {
+    // Deferred RMSNorm: sum of squares of row mt*16 + lane%16 from the producer's per-tile partials [partial][row], in
+    // a fixed order.  The ksplit waves of a task each sum a contiguous share of the partials; a lane loads four rows
+    // (lane % 4) of every 16th partial (lane / 4) at a time, the lanes' sums then meet in a butterfly.
+    const int np = normed ? out.nin.n_part : 0, cp = (np + ksplit - 1) / ksplit;
+    const int c0 = kpart * cp + (lane >> 2), c1 = min(np, (kpart + 1) * cp);
+    const float* p = out.nin.ssq + row0 + 4 * (lane & 3);
+    float4 t[MT][SB];
+    if (normed) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int j = 0; j < SB; ++j) { const int i = c0 + 4 * j; t[mt][j] = i < c1 ? p[(size_t)i * out.nin.stride + mt * 16] : 0.f; }
-    if (stream) load_frags<MT, NB, U>(cur, wp, ap, ktiles, kt0, kt1);
+        for (int j = 0; j < SB; ++j) t[mt][j] = *(const float4*)(p + (size_t)min(c0 + 16 * j, np - 1) * out.nin.stride + mt * 16);
+    }
+    if (stream) load_frags<MT, NB, U>(cur, wp, ap, ktiles, kt0, kt1 - 1);
+    if (epi_wave) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < MT; ++mt) epi_prefetch<EPI>(pre[mt], out, task, row0 + mt * 16 + mc, mt * 16 + mc < M, lane);
+    }
+    if (normed) {
+      float4 sv[MT];
 #pragma unroll
-      for (int j = 0; j < SB; ++j) ssl[mt] += t[mt][j];
-    for (int b0 = c0 + 4 * SB; b0 < c1; b0 += 4 * SB)
+      for (int mt = 0; mt < MT; ++mt) {
+        sv[mt] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int j = 0; j < SB; ++j)
+          if (c0 + 16 * j < c1) { sv[mt].x += t[mt][j].x; sv[mt].y += t[mt][j].y; sv[mt].z += t[mt][j].z; sv[mt].w += t[mt][j].w; }
+      }
+      for (int b0 = c0 + 16 * SB; b0 < c1; b0 += 16 * SB)      // (more partials than one batch: wide models, several row tiles)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+          for (int j = 0; j < SB; ++j) t[mt][j] = *(const float4*)(p + (size_t)min(b0 + 16 * j, np - 1) * out.nin.stride + mt * 16);
+#pragma unroll
+          for (int j = 0; j < SB; ++j)
+            if (b0 + 16 * j < c1) { sv[mt].x += t[mt][j].x; sv[mt].y += t[mt][j].y; sv[mt].z += t[mt][j].z; sv[mt].w += t[mt][j].w; }
+        }
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-        for (int j = 0; j < SB; ++j) { const int i = b0 + 4 * j; t[mt][j] = i < c1 ? p[(size_t)i * out.nin.stride + mt * 16] : 0.f; }
-#pragma unroll
-        for (int j = 0; j < SB; ++j) ssl[mt] += t[mt][j];
+        for (int sh = 4; sh < 64; sh <<= 1) {
+          sv[mt].x += __shfl_xor(sv[mt].x, sh, 64); sv[mt].y += __shfl_xor(sv[mt].y, sh, 64);
+          sv[mt].z += __shfl_xor(sv[mt].z, sh, 64); sv[mt].w += __shfl_xor(sv[mt].w, sh, 64);
+        }
+        // lanes with lane % 4 == q now hold rows 4q .. 4q+3; this lane wants row mc
+        const float a = __shfl(sv[mt].x, mc >> 2, 64), b = __shfl(sv[mt].y, mc >> 2, 64);
+        const float c = __shfl(sv[mt].z, mc >> 2, 64), e = __shfl(sv[mt].w, mc >> 2, 64);
+        ssl[mt] = (mc & 2) ? ((mc & 1) ? e : c) : ((mc & 1) ? b : a);
       }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      ssl[mt] += __shfl_xor(ssl[mt], 16, 64);
-      ssl[mt] += __shfl_xor(ssl[mt], 32, 64);
     }
-  } else if (stream) {
-    load_frags<MT, NB, U>(cur, wp, ap, ktiles, kt0, kt1);
   }
 
+  // Two register sets of fragments take turns: while one is multiplied the other is in flight, and the next request
+  // for a set goes out as soon as its MFMAs are issued.
   if (stream) {
-    Frags<MT, NB, U> nxt;
-    for (int kt = kt0; kt < kt1; kt += U) {
-      const bool more = kt + U < kt1;
-      if (more) load_frags<MT, NB, U>(nxt, wp, ap, ktiles, kt + U, kt1);
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[nb][mt] = mfma16(cur.w[nb][u], cur.x[mt][u], acc[nb][mt]);
-      if (more) cur = nxt;
+    // Groups of U k-tiles; only the last one can be short.  In the loop every fragment requested is multiplied, with
+    // no condition in between -- a request whose data might go unused would make the compiler drain the load counter
+    // before the registers are requested again, and with it the set in flight.
+    Frags<MT, NB, U> oth;
+    const int last = kt1 - 1;
+    int kt = kt0;
+    for (; kt + 2 * U < kt1; kt += 2 * U) {
+      load_frags<MT, NB, U>(oth, wp, ap, ktiles, kt + U, last);
+      mma_frags<MT, NB, U, false>(acc, cur, kt, kt1);
+      load_frags<MT, NB, U>(cur, wp, ap, ktiles, kt + 2 * U, last);
+      mma_frags<MT, NB, U, false>(acc, oth, kt + U, kt1);
+    }
+    if (kt + U < kt1) {                  // two groups left
+      load_frags<MT, NB, U>(oth, wp, ap, ktiles, kt + U, last);
+      mma_frags<MT, NB, U, false>(acc, cur, kt, kt1);
+      mma_frags<MT, NB, U, true>(acc, oth, kt + U, kt1);
+    } else {
+      mma_frags<MT, NB, U, true>(acc, cur, kt, kt1);
     }
   }
 
@@ -823,9 +861,9 @@ void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kti
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out) {
   const int ntasks = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? ntiles / 2 : ntiles;
   // launch shape by task count, from sweeps over the 8B and 70B matrix shapes at 9 rows
-  int ksplit = ntasks >= 4096 ? 4 : (ntasks >= 768 ? 1 : (ntasks >= 320 ? 4 : (ntasks >= 200 ? 8 : 4)));
-  int U = (ntasks >= 768 || ntasks < 200) ? 8 : 4;
+  int ksplit = ntasks >= 768 ? 1 : (ntasks >= 320 ? 4 : (ntasks >= 200 ? 8 : 4));
   while (ksplit > 1 && ktiles / ksplit < 4) ksplit >>= 1;
+  const int U = (ntasks >= 768 || ntasks < 200 || ktiles / ksplit >= 32) ? 8 : 4;
   const int nw = ksplit > 4 ? ksplit : 4;
   bf16_gemm_cfg(st, epi, W, ntiles, ktiles, A, M, N, out, nw, ksplit, U);
 }

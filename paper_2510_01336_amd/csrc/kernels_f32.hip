@@ -2,6 +2,7 @@
 // The fp32 kernels favour clarity over speed: EE_F32 exists for the small reference-precision
 // configuration; the bandwidth-critical work is in kernels_bf16.hip.
 #include "kernels.h"
+#include <hip/hip_ext.h>
 #include <algorithm>
 #include <cmath>
 
@@ -68,17 +69,29 @@ void k_take_token(hipStream_t st, const int* v, const int* row_seq, int M, int* 
 }
 
 // Rotary angles are formed in double: at position 32768 an fp32 product pos*freq is off by ~2e-3 rad.
-__global__ void rope_table_kernel(const int* row_pos, int pos_add, const double* inv_freq, float2* cs, int M, int half) {
+// The thread of a row's first pair also resolves the row's lookups once for all layers of the call -- first q-tile of
+// its sequence, row index inside the sequence, KV page and slot of its position -- so that the QKV epilogue of every
+// layer finds them with one row-indexed load instead of a chain of dependent ones.
+__global__ void rope_table_kernel(const int* row_pos, int pos_add, const double* inv_freq, float2* cs, int M, int half,
+                                  const int* row_seq, const int* seq_row0, const int* seq_qt0, const int* block_table, int pps,
+                                  int4* rowinfo) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= M * half) return;
   int r = i / half, f = i % half;
-  double ang = (double)(row_pos[r] + pos_add) * inv_freq[f];
+  const int pos = row_pos[r] + pos_add;
+  double ang = (double)pos * inv_freq[f];
   double s, c;
   sincos(ang, &s, &c);
   cs[i] = make_float2((float)c, (float)s);
+  if (f == 0 && rowinfo) {
+    const int sq = row_seq[r];
+    rowinfo[r] = make_int4(seq_qt0[sq], r - seq_row0[sq], block_table[sq * pps + pos / EE_PAGE], pos % EE_PAGE);
+  }
 }
-void k_rope_table(hipStream_t st, const int* row_pos, int pos_add, const double* inv_freq, float2* cs, int M, int half) {
-  hipLaunchKernelGGL(rope_table_kernel, dim3(ceil_div(M * half, 256)), dim3(256), 0, st, row_pos, pos_add, inv_freq, cs, M, half);
+void k_rope_table(hipStream_t st, const CallMeta& mt, int pos_add, const double* inv_freq, float2* cs, int M, int half, int pps,
+                  int4* rowinfo) {
+  hipLaunchKernelGGL(rope_table_kernel, dim3(ceil_div(M * half, 256)), dim3(256), 0, st, mt.row_pos, pos_add, inv_freq, cs, M, half,
+                     mt.row_seq, mt.seq_row0, mt.seq_qt0, mt.block_table, pps, rowinfo);
 }
 
 __global__ void fill_nan_dead_kv_kernel(void* kv, int bf16, const int* pages, int n_owned, int len, int layer0, int layer1,
@@ -155,6 +168,67 @@ extern "C" int ee_debug_stream_copy(void* dst_dev, const void* src_dev, size_t b
   const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
   hipLaunchKernelGGL(stream_copy_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)dst_dev, (const uint4*)src_dev, n16);
   HIP_TRY(hipGetLastError());
+  return EE_OK;
+}
+
+// Plain streaming read (16 bytes per lane, four requests in flight per lane, streaming hint, grid-stride): what the
+// chip delivers to a kernel that does nothing but fetch `bytes` once, launched after another kernel on the same
+// stream.  The floor against which the weight-streaming projections are read: a dependent launch of a few tens of MB
+// never reaches the peak rate, whatever its arithmetic.
+__device__ unsigned g_read_sink;
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src0, size_t n16) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4* src = (const u32x4*)src0;
+  const size_t stride = (size_t)gridDim.x * 1024;
+  unsigned acc = 0;
+  size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+  for (; i + 768 < n16; i += stride) {
+    const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + 256);
+    const u32x4 c = __builtin_nontemporal_load(src + i + 512), d = __builtin_nontemporal_load(src + i + 768);
+    acc ^= a.x ^ b.y ^ c.z ^ d.w;
+  }
+  for (; i < n16; i += 256) acc ^= __builtin_nontemporal_load(src + i).x;
+  if (acc == 0x9e3779b9u) g_read_sink = acc;       // (keeps the loads alive; practically never taken)
+}
+extern "C" int ee_debug_read_floor(const void* buf_dev, const size_t* sizes, int n, int reps, float* us_out, void* stream) {
+  if (!buf_dev || !sizes || !us_out || n < 1 || n > 16 || reps < 1 || ((uintptr_t)buf_dev & 15)) {
+    ee_set_error("read floor needs a 16-byte aligned buffer, 1..16 sizes and at least one repetition");
+    return EE_ERR_ARG;
+  }
+  for (int i = 0; i < n; ++i)
+    if (!sizes[i] || (sizes[i] & 15)) { ee_set_error("read floor: every size must be a positive multiple of 16"); return EE_ERR_ARG; }
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<hipEvent_t> ev(2 * n, nullptr);
+  int rc = EE_OK;
+  for (auto& e : ev)
+    if (rc == EE_OK && hipEventCreate(&e) != hipSuccess) { ee_set_error("read floor: no event"); rc = EE_ERR_HIP; }
+  std::vector<double> sum(n, 0.0);
+  auto launch = [&](const char* p, size_t bytes, hipEvent_t a, hipEvent_t b) {
+    const size_t n16 = bytes / 16;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 1023) / 1024, 2048);
+    if (a) hipExtLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, st, a, b, 0, (const uint4*)p, n16);
+    else hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, st, (const uint4*)p, n16);
+  };
+  // one round = the n reads back to back on the stream, behind an untimed one, as the projections of a layer follow
+  // each other; the events are attached to the dispatches and hold each kernel's own start and end
+  for (int r = 0; r < reps + 2 && rc == EE_OK; ++r) {           // (two untimed rounds first)
+    const char* p = (const char*)buf_dev;
+    launch(p, sizes[0], nullptr, nullptr);
+    for (int i = 0; i < n; ++i) {
+      launch(p, sizes[i], ev[2 * i], ev[2 * i + 1]);
+      p += sizes[i];
+    }
+    if (hipStreamSynchronize(st) != hipSuccess) { ee_set_error("read floor: a launch failed"); rc = EE_ERR_HIP; break; }
+    for (int i = 0; i < n && r >= 2; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) != hipSuccess) { ee_set_error("read floor: timing a launch failed"); rc = EE_ERR_HIP; break; }
+      sum[i] += 1e3 * ms;
+    }
+  }
+  for (auto e : ev)
+    if (e) (void)hipEventDestroy(e);
+  if (rc != EE_OK) return rc;
+  for (int i = 0; i < n; ++i) us_out[i] = (float)(sum[i] / reps);
   return EE_OK;
 }
 

@@ -44,6 +44,7 @@ struct ee_session {
   int n_levels = 2;             // verifier levels: exits after L_d (2 = Alg. 2: L_i and L_f)
   void *XN = nullptr, *Qb = nullptr, *AO = nullptr, *H = nullptr;
   float2* cs = nullptr;
+  int4* rowinfo = nullptr;    // [maxM] per-row lookups of the QKV epilogue, resolved once per call
   int *vtok = nullptr, *tok_next = nullptr, *draft_dev = nullptr, *out_dev = nullptr, *page_scratch = nullptr;
   // rejection-sampling acceptance (attached separately): the distributions the draft tokens were drawn from,
   // the L_i distributions of the tokens in V (rows [batch][max_rows][vocab]), and the call's uniform numbers
@@ -135,6 +136,7 @@ static size_t carve(ee_session* s, char* base) {
   s->Hi = cv.take<float>((size_t)s->B * s->max_rows * d);
   for (int j = 2; j < s->n_levels; ++j) s->Hup[j - 2] = cv.take<float>((size_t)s->B * s->max_rows * d);
   s->cs = cv.take<float2>((size_t)s->maxM * (D / 2));
+  s->rowinfo = cv.take<int4>((size_t)s->maxM);
   s->vtok = cv.take<int>(s->maxM);
   s->tok_next = cv.take<int>(s->maxM);
   s->draft_dev = cv.take<int>((size_t)s->B * s->max_rows);
@@ -411,7 +413,7 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
   const ee_config& c = m->cfg;
   const int d = c.d_model, D = c.head_dim, Hq = c.n_q_heads, Hkv = c.n_kv_heads, M = p.M;
   hipStream_t st = s->st;
-  KF(KF_ROPE, k_rope_table(st, mt.row_pos, pos_add, m->inv_freq, s->cs, M, D / 2));
+  KF(KF_ROPE, k_rope_table(st, mt, pos_add, m->inv_freq, s->cs, M, D / 2, s->pps, s->rowinfo));
   AttnScratch scr;
   const int per = attention_plan(s, p, pos_add, scr, nullptr);
   for (int l = l0; l < l1; ++l) {
@@ -429,9 +431,8 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
       if (l == l0) KF(KF_NORM, bf16_rmsnorm(st, s->X, g1, c.rms_eps, (bf16_t*)s->XN, L.qkv.ktiles(), M, d));
       else o.nin = nin;
       RopeOut& R = o.rope;
-      R.cs = s->cs; R.row_seq = mt.row_seq; R.row_pos = mt.row_pos; R.seq_row0 = mt.seq_row0; R.seq_qt0 = mt.seq_qt0;
-      R.block_table = mt.block_table; R.pos_add = pos_add; R.Hq = Hq; R.Hkv = Hkv; R.D = D; R.layer = l;
-      R.n_pages = s->n_pages; R.pps = s->pps; R.total_qt = p.total_qt; R.Q = (bf16_t*)s->Qb; R.kv = (bf16_t*)s->kv;
+      R.cs = s->cs; R.rowinfo = s->rowinfo; R.Hq = Hq; R.Hkv = Hkv; R.D = D; R.layer = l;
+      R.n_pages = s->n_pages; R.total_qt = p.total_qt; R.Q = (bf16_t*)s->Qb; R.kv = (bf16_t*)s->kv;
       KF(KF_GEMM_QKV, gemm(s, EPI_ROPE, L.qkv, (const bf16_t*)s->XN, M, o));
       KF(KF_ATTN, bf16_attention(st, (const bf16_t*)s->Qb, (const bf16_t*)s->kv, mt, pos_add, s->B, p.max_m, p.total_qt,
                                  p.max_kv_end + pos_add, Hq, Hkv, D, l, s->n_pages, s->pps, scr, (bf16_t*)s->AO, L.o.ktiles(), per));
