@@ -107,3 +107,21 @@ def test_attention_split_selector_checks_its_argument(lib):
         assert lib.ee_debug_attention_split_pages(ok) == 0, ok
     assert lib.ee_debug_attention_split_pages(-3) == -1 and b"pages per split" in lib.ee_last_error()
     assert lib.ee_debug_attention_split_pages(0) == 0
+
+
+def test_read_floor_checks_its_arguments(lib):
+    """Bad arguments are refused before any device call."""
+    lib.ee_last_error.restype = ctypes.c_char_p
+    f = lib.ee_debug_read_floor
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t), ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float),
+                  ctypes.c_void_p]
+    sizes = (ctypes.c_size_t * 2)(4096, 4096)
+    out = (ctypes.c_float * 2)()
+    assert f(None, sizes, 2, 1, out, None) == -1 and b"read floor" in lib.ee_last_error()
+    assert f(ctypes.c_void_p(256), sizes, 0, 1, out, None) == -1
+    assert f(ctypes.c_void_p(256), sizes, 17, 1, out, None) == -1
+    assert f(ctypes.c_void_p(256), sizes, 2, 0, out, None) == -1
+    assert f(ctypes.c_void_p(264), sizes, 2, 1, out, None) == -1          # not 16-byte aligned
+    odd = (ctypes.c_size_t * 2)(4096, 100)
+    assert f(ctypes.c_void_p(256), odd, 2, 1, out, None) == -1 and b"multiple of 16" in lib.ee_last_error()

@@ -526,3 +526,19 @@ def test_released_slot_idles_while_the_batch_goes_on():
     with pytest.raises(hs.EEError):
         sess.decode_ar(1)
     sess.close(); model.close()
+
+
+@pytest.mark.gpu
+def test_read_floor_times_plain_reads():
+    """The measurement entry point behind bench.py's read_floor: every region gets a positive time, a region sixteen times
+    the size takes longer, and the implied rate stays below the chip's 8 TB/s."""
+    import torch
+    import paper_2510_01336_amd as hs
+    sizes = [8 << 20, 128 << 20]
+    buf = torch.full((sum(sizes),), 5, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    us = hs.ee_debug_read_floor(buf.data_ptr(), sizes, 5, 0)
+    assert len(us) == 2 and 0.5 < us[0] < us[1] < 1e4
+    assert sizes[1] / (us[1] * 1e-6) < 8.0e12
+    with pytest.raises(hs.EEError):
+        hs.ee_debug_read_floor(buf.data_ptr() + 4, sizes, 5, 0)
