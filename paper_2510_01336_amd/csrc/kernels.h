@@ -83,6 +83,11 @@ size_t bf16_gemm_rows_scratch_floats(int ntiles, int ktiles);
 void bf16_gemm_rows(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                     const GemmOut& out, float* scratch, float* inv_rms);
 void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf16_t* out, int ktiles, int M, int d);
+// Opens a pass over layers in one launch: row r of X <- embedding of tok[r] (emb set), rows[row_idx[r]] (rows set) or
+// itself; out <- its RMSNorm with gain g as a GEMM operand; cs / rowinfo as k_rope_table fills them.
+void bf16_begin_pass(hipStream_t st, const bf16_t* emb, const int* tok, const float* rows, const int* row_idx, float* X,
+                     const float* g, float eps, bf16_t* out, int ktiles, int M, int d, const CallMeta& mt, int pos_add,
+                     const double* inv_freq, float2* cs, int half, int pps, int4* rowinfo);
 struct AttnScratch { float* part_o; float* part_ml; int max_splits; };
 // pages each KV split takes, chosen from the call's sequence ends (kv_end[b] = first position past the
 // block, 0 for a sequence not taking part) so that a ragged batch is cut into equal workgroups

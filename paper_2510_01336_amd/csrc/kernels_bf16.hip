@@ -71,6 +71,91 @@ void bf16_rmsnorm(hipStream_t st, const float* X, const float* g, float eps, bf1
   else hipLaunchKernelGGL((bf16_rmsnorm_kernel<16>), dim3(M), dim3(256), 0, st, X, g, eps, out, ktiles, d);
 }
 
+// The first kernel of a pass over layers, one workgroup per row: brings the row into the residual stream X -- from the
+// embedding table by token, from a buffer of kept hidden rows by index, or leaves it where it is --, writes its
+// RMSNorm as the first projection's operand, and fills the row's rotary table and epilogue lookups (what
+// rope_table_kernel does) on the side.  One launch where the pass used to open with three.
+template <int CH>
+__global__ __launch_bounds__(256) void bf16_begin_pass_kernel(const bf16_t* __restrict__ emb, const int* __restrict__ tok,
+                                                              const float* __restrict__ rows, const int* __restrict__ row_idx,
+                                                              float* __restrict__ X, const float* __restrict__ g, float eps,
+                                                              bf16_t* __restrict__ out, int ktiles, int d, const int* row_pos,
+                                                              int pos_add, const double* inv_freq, float2* cs, int half,
+                                                              const int* row_seq, const int* seq_row0, const int* seq_qt0,
+                                                              const int* block_table, int pps, int4* rowinfo) {
+  __shared__ float part[4];
+  const int r = blockIdx.x, nch = d >> 2;
+  const float4* g4 = (const float4*)g;
+  float4 xv[CH], gv[CH];
+  if (emb) {
+    const uint2* e2 = (const uint2*)(emb + (size_t)tok[r] * d);          // four bf16 per chunk
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int c = threadIdx.x + i * 256;
+      const uint2 e = c < nch ? e2[c] : make_uint2(0u, 0u);
+      xv[i] = make_float4(__uint_as_float(e.x << 16), __uint_as_float(e.x & 0xffff0000u), __uint_as_float(e.y << 16),
+                          __uint_as_float(e.y & 0xffff0000u));
+    }
+  } else {
+    const float4* x4 = (const float4*)((rows ? rows : X) + (size_t)(row_idx ? row_idx[r] : r) * d);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int c = threadIdx.x + i * 256;
+      xv[i] = c < nch ? x4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = threadIdx.x + i * 256;
+    gv[i] = c < nch ? g4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const int pos = row_pos[r] + pos_add;
+  for (int f = threadIdx.x; f < half; f += 256) {     // rotary angles in double, as in rope_table_kernel
+    double sn, cn;
+    sincos((double)pos * inv_freq[f], &sn, &cn);
+    cs[(size_t)r * half + f] = make_float2((float)cn, (float)sn);
+  }
+  if (threadIdx.x == 0) {
+    const int sq = row_seq[r];
+    rowinfo[r] = make_int4(seq_qt0[sq], r - seq_row0[sq], block_table[sq * pps + pos / EE_PAGE], pos % EE_PAGE);
+  }
+  if (emb || rows) {
+    float4* xo = (float4*)(X + (size_t)r * d);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int c = threadIdx.x + i * 256;
+      if (c < nch) xo[c] = xv[i];
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < CH; ++i) ss += xv[i].x * xv[i].x + xv[i].y * xv[i].y + xv[i].z * xv[i].z + xv[i].w * xv[i].w;
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_down(ss, o, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float inv = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = threadIdx.x + i * 256;
+    if (c < nch) {
+      uint2 pk = make_uint2(pack2(xv[i].x * inv * gv[i].x, xv[i].y * inv * gv[i].y),
+                            pack2(xv[i].z * inv * gv[i].z, xv[i].w * inv * gv[i].w));
+      *(uint2*)(out + frag_offset(r, c * 4, ktiles)) = pk;
+    }
+  }
+}
+void bf16_begin_pass(hipStream_t st, const bf16_t* emb, const int* tok, const float* rows, const int* row_idx, float* X,
+                     const float* g, float eps, bf16_t* out, int ktiles, int M, int d, const CallMeta& mt, int pos_add,
+                     const double* inv_freq, float2* cs, int half, int pps, int4* rowinfo) {
+#define BEGIN_PASS(CH_)                                                                                                       \
+  hipLaunchKernelGGL((bf16_begin_pass_kernel<CH_>), dim3(M), dim3(256), 0, st, emb, tok, rows, row_idx, X, g, eps, out, ktiles, d,  \
+                     mt.row_pos, pos_add, inv_freq, cs, half, mt.row_seq, mt.seq_row0, mt.seq_qt0, mt.block_table, pps, rowinfo)
+  if (d <= 1024) BEGIN_PASS(1);
+  else if (d <= 4096) BEGIN_PASS(4);
+  else BEGIN_PASS(16);
+#undef BEGIN_PASS
+}
+
 // ---------------------------------------------------------------------------------------------
 // Skinny GEMM  Y[m][n] = sum_k X[m][k] W[n][k],  M <= 16*MT rows per launch, weights streamed once.
 // A task is one 16-row weight tile strip over the whole K, or two adjacent strips (NB = 2) when the

@@ -408,12 +408,28 @@ static int attention_plan(const ee_session* s, const CallPlan& p, int pos_add, A
   return per;
 }
 
-static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const CallMeta& mt, int pos_add) {
+// where the rows of a pass come from: the embedding of tokens (a1 of a pass that starts at layer 0), kept hidden rows
+// gathered by index (hidden-state reuse of Alg. 2), or the residual stream as it stands
+struct PassSource {
+  const int* tok = nullptr;
+  const float* rows = nullptr; const int* row_idx = nullptr;
+};
+
+static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const CallMeta& mt, int pos_add, const PassSource& src = PassSource()) {
   const ee_model* m = s->m;
   const ee_config& c = m->cfg;
   const int d = c.d_model, D = c.head_dim, Hq = c.n_q_heads, Hkv = c.n_kv_heads, M = p.M;
   hipStream_t st = s->st;
-  KF(KF_ROPE, k_rope_table(st, mt, pos_add, m->inv_freq, s->cs, M, D / 2, s->pps, s->rowinfo));
+  if (m->bf16 && l0 < l1) {
+    // one launch: rows into the stream, the first layer's operand, the rotary table and the epilogue lookups
+    KF(KF_NORM, bf16_begin_pass(st, src.tok ? (const bf16_t*)(m->base + m->emb) : nullptr, src.tok, src.rows, src.row_idx, s->X,
+                                (const float*)(m->base + m->L[l0].g1), c.rms_eps, (bf16_t*)s->XN, m->L[l0].qkv.ktiles(), M, d, mt,
+                                pos_add, m->inv_freq, s->cs, D / 2, s->pps, s->rowinfo));
+  } else {
+    if (src.tok) KF(KF_EMBED, k_embed(st, m->bf16, m->base + m->emb, src.tok, s->X, M, d));
+    else if (src.rows) KF(KF_COPY, k_copy_rows(st, s->X, nullptr, 0, src.rows, src.row_idx, M, d));
+    KF(KF_ROPE, k_rope_table(st, mt, pos_add, m->inv_freq, s->cs, M, D / 2, s->pps, s->rowinfo));
+  }
   AttnScratch scr;
   const int per = attention_plan(s, p, pos_add, scr, nullptr);
   for (int l = l0; l < l1; ++l) {
@@ -428,8 +444,7 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
       NormOut nout;
       nout.xn = (bf16_t*)s->XN; nout.ktiles = ceil_div(d, 32); nout.ssq = s->ssq; nout.stride = Mp;
       GemmOut o;
-      if (l == l0) KF(KF_NORM, bf16_rmsnorm(st, s->X, g1, c.rms_eps, (bf16_t*)s->XN, L.qkv.ktiles(), M, d));
-      else o.nin = nin;
+      if (l != l0) o.nin = nin;            // (the first layer's operand was normalised when the pass was opened)
       RopeOut& R = o.rope;
       R.cs = s->cs; R.rowinfo = s->rowinfo; R.Hq = Hq; R.Hkv = Hkv; R.D = D; R.layer = l;
       R.n_pages = s->n_pages; R.total_qt = p.total_qt; R.Q = (bf16_t*)s->Qb; R.kv = (bf16_t*)s->kv;
@@ -587,8 +602,8 @@ static int prefill_impl(ee_session* s, const int32_t* tokens, const int32_t* len
     EE_TRY(build_meta(s, si, p, [&](int b, int r, int& tok, int&, int&) { tok = tokens[off0[b] + done[b] + r]; }));
     EE_TRY(upload_meta(s, si));
     CallMeta mt = meta_ptrs(s, s->slot[si].d);
-    KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
-    run_layers(s, 0, c.n_layers, p, mt, 0);
+    PassSource from_tokens; from_tokens.tok = mt.row_tok;
+    run_layers(s, 0, c.n_layers, p, mt, 0, from_tokens);
     bool head_done = false;
     for (int b = 0, row = 0; b < s->B; row += p.m[b], ++b) {
       if (!p.m[b] || done[b] + p.m[b] < lens[b]) continue;
@@ -672,8 +687,8 @@ extern "C" int ee_decode_ar(ee_session* s, int n, int32_t* out) {
   EE_TRY(upload_meta(s, 0));
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
   for (int j = 0; j < n; ++j) {       // the next token stays on the device; positions advance through pos_add
-    KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, j == 0 ? mt.row_tok : s->tok_next, s->X, p.M, c.d_model));
-    run_layers(s, 0, c.n_layers, p, mt, j);
+    PassSource from_tokens; from_tokens.tok = j == 0 ? mt.row_tok : s->tok_next;
+    run_layers(s, 0, c.n_layers, p, mt, j, from_tokens);
     exit_head(s, p.M, s->n_levels);
     KF(KF_MISC, k_take_token(s->st, s->vtok, mt.row_seq, p.M, s->tok_next, s->draft_dev, s->max_rows, j));
   }
@@ -746,8 +761,8 @@ static int draft_impl(ee_session* s, int k, int32_t* draft, const float* u) {
   EE_TRY(upload_meta(s, 0));
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
   for (int j = 0; j < rows; ++j) {
-    KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, j == 0 ? mt.row_tok : s->tok_next, s->X, p.M, c.d_model));
-    run_layers(s, 0, c.exit_draft, p, mt, j);
+    PassSource from_tokens; from_tokens.tok = j == 0 ? mt.row_tok : s->tok_next;
+    run_layers(s, 0, c.exit_draft, p, mt, j, from_tokens);
     KF(KF_COPY, k_copy_rows(s->st, s->Hd, mt.row_dst, j, s->X, nullptr, p.M, c.d_model));
     if (j < k) {
       exit_head(s, p.M, 0);
@@ -806,8 +821,8 @@ extern "C" int ee_draft_inject(ee_session* s, int k, const int32_t* draft) {
   }));
   EE_TRY(upload_meta(s, 0));
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
-  KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
-  run_layers(s, 0, c.exit_draft, p, mt, 0);
+  PassSource from_tokens; from_tokens.tok = mt.row_tok;
+  run_layers(s, 0, c.exit_draft, p, mt, 0, from_tokens);
   KF(KF_COPY, k_copy_rows(s->st, s->Hd, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));
   HIP_TRY(hipGetLastError());
   for (int b = 0; b < s->B; ++b) {
@@ -951,8 +966,8 @@ static int verify_intermediate_impl(ee_session* s, int32_t* n_accept, int32_t* n
   }
   EE_TRY(upload_meta(s, 0));
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
-  KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, s->Hd, mt.row_src, p.M, c.d_model));       // a1: consume buffered H_d
-  run_layers(s, c.exit_draft, c.exit_inter, p, mt, 0);
+  PassSource kept; kept.rows = s->Hd; kept.row_idx = mt.row_src;       // a1: consume buffered H_d
+  run_layers(s, c.exit_draft, c.exit_inter, p, mt, 0, kept);
   s->need_logits = rs;
   exit_head(s, p.M, 1);
   s->need_logits = false;
@@ -1077,8 +1092,8 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
     }));
     EE_TRY(upload_meta(s, 1));
     CallMeta mt = meta_ptrs(s, s->slot[1].d);
-    KF(KF_EMBED, k_embed(s->st, s->m->bf16, s->m->base + s->m->emb, mt.row_tok, s->X, p.M, c.d_model));
-    run_layers(s, 0, ex[j - 1], p, mt, 0);
+    PassSource from_tokens; from_tokens.tok = mt.row_tok;
+    run_layers(s, 0, ex[j - 1], p, mt, 0, from_tokens);
     KF(KF_COPY, k_copy_rows(s->st, rows_below, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));
   }
   CallPlan p;
@@ -1099,8 +1114,8 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
   }
   EE_TRY(upload_meta(s, 0));
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
-  KF(KF_COPY, k_copy_rows(s->st, s->X, nullptr, 0, rows_below, mt.row_src, p.M, c.d_model));  // consume the buffered rows
-  run_layers(s, ex[j - 1], ex[j], p, mt, 0);
+  PassSource kept; kept.rows = rows_below; kept.row_idx = mt.row_src;  // consume the buffered rows
+  run_layers(s, ex[j - 1], ex[j], p, mt, 0, kept);
   s->need_logits = rs;
   exit_head(s, p.M, j);
   s->need_logits = false;
