@@ -59,7 +59,7 @@ struct RopeOut {
 struct GemmOut {
   float* Y = nullptr; int ldy = 0;        // EPI_ADD: residual stream, Y += product (row-major fp32); EPI_ARGMAX: optional logits
   bf16_t* H = nullptr; int h_ktiles = 0;  // EPI_SWIGLU target (fragment layout)
-  float* pmax = nullptr; int* pidx = nullptr; int pstride = 0;   // EPI_ARGMAX partials [ntiles][pstride]
+  float* pmax = nullptr; int* pidx = nullptr; int pstride = 0;   // EPI_ARGMAX partials [row][pstride >= ntiles]
   NormIn nin;
   NormOut nout;
   RopeOut rope;

@@ -302,8 +302,8 @@ __device__ inline void epi_apply(const f32x4& acc0, const f32x4& acc1, float sc,
       if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
     }
     if (g == 0 && ok) {
-      out.pmax[(size_t)task * out.pstride + row] = best;
-      out.pidx[(size_t)task * out.pstride + row] = bi;
+      out.pmax[(size_t)row * out.pstride + task] = best;
+      out.pidx[(size_t)row * out.pstride + task] = bi;
     }
   }
 }
@@ -953,12 +953,12 @@ void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles,
   bf16_gemm_cfg(st, epi, W, ntiles, ktiles, A, M, N, out, nw, ksplit, U);
 }
 
-// one workgroup of 1024 threads per row; eight independent partials per thread are requested at once (the
-// partials of a row lie a row-stride apart, one cache line each, so the kernel is a chain of load latencies)
+// one workgroup of 1024 threads per row; the row's partials lie side by side ([row][tile]), so a wave's load is one
+// contiguous 256 bytes; eight independent partials per thread are requested at once
 __global__ __launch_bounds__(1024) void bf16_argmax_reduce_kernel(const float* __restrict__ pmax, const int* __restrict__ pidx,
                                                                    int ntiles, int pstride, int* v) {
-  __shared__ float bv[1024];
-  __shared__ int bi[1024];
+  __shared__ float bv[16];
+  __shared__ int bi[16];
   const int m = blockIdx.x;
   float best = -INFINITY; int idx = 0x7fffffff;
   for (int t0 = threadIdx.x; t0 < ntiles; t0 += 8 * 1024) {
@@ -966,22 +966,27 @@ __global__ __launch_bounds__(1024) void bf16_argmax_reduce_kernel(const float* _
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int t = min(t0 + j * 1024, ntiles - 1);
-      x[j] = pmax[(size_t)t * pstride + m]; xi[j] = pidx[(size_t)t * pstride + m];
+      x[j] = pmax[(size_t)m * pstride + t]; xi[j] = pidx[(size_t)m * pstride + t];
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j)      // a clamped duplicate carries the same (value, index): harmless
       if (x[j] > best || (x[j] == best && xi[j] < idx)) { best = x[j]; idx = xi[j]; }
   }
-  bv[threadIdx.x] = best; bi[threadIdx.x] = idx;
-  __syncthreads();
-  for (int s = 512; s > 0; s >>= 1) {
-    if (threadIdx.x < s) {
-      float o = bv[threadIdx.x + s]; int oi = bi[threadIdx.x + s];
-      if (o > bv[threadIdx.x] || (o == bv[threadIdx.x] && oi < bi[threadIdx.x])) { bv[threadIdx.x] = o; bi[threadIdx.x] = oi; }
-    }
-    __syncthreads();
+  // within the wave by shuffles, then the sixteen waves' results through LDS (one barrier)
+  for (int sh = 32; sh > 0; sh >>= 1) {
+    const float o = __shfl_xor(best, sh, 64); const int oi = __shfl_xor(idx, sh, 64);
+    if (o > best || (o == best && oi < idx)) { best = o; idx = oi; }
   }
-  if (threadIdx.x == 0) v[m] = bi[0];
+  if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = idx; }
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    best = threadIdx.x < 16 ? bv[threadIdx.x] : -INFINITY; idx = threadIdx.x < 16 ? bi[threadIdx.x] : 0x7fffffff;
+    for (int sh = 8; sh > 0; sh >>= 1) {
+      const float o = __shfl_xor(best, sh, 64); const int oi = __shfl_xor(idx, sh, 64);
+      if (o > best || (o == best && oi < idx)) { best = o; idx = oi; }
+    }
+    if (threadIdx.x == 0) v[m] = idx;
+  }
 }
 void bf16_argmax_reduce(hipStream_t st, const float* pmax, const int* pidx, int ntiles, int pstride, int M, int* v) {
   hipLaunchKernelGGL(bf16_argmax_reduce_kernel, dim3(M), dim3(1024), 0, st, pmax, pidx, ntiles, pstride, v);

@@ -509,9 +509,8 @@ static void exit_head(ee_session* s, int M, int which) {
     }
     GemmOut o;
     o.nin = nin;
-    // (max, arg max) partials [tile][row] with the rows packed to the call's row tiles: the reduction then walks
-    // a compact array instead of one memory page per tile
-    const int pstride = ceil_div(M, 16) * 16;
+    // (max, arg max) partials [row][tile]: the reduction of a row then reads one contiguous strip
+    const int pstride = m->head.ntiles();
     o.pmax = s->pmax; o.pidx = s->pidx; o.pstride = pstride;
     if (s->debug_logits || s->need_logits) { o.Y = s->LOGITS; o.ldy = c.vocab; }
     KF(KF_GEMM_HEAD, gemm(s, EPI_ARGMAX, m->head, (const bf16_t*)s->XN, M, o));
