@@ -64,7 +64,7 @@ struct GemmOut {
   NormOut nout;
   RopeOut rope;
 };
-// Y^T tile = W tile (A operand) x X^T (B operand); W, A in fragment layout.  Rows go in passes of 64.
+// Y^T tile = W tile (A operand) x X^T (B operand); W, A in fragment layout.  Rows go in passes of 32.
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out);
 void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                    const GemmOut& out, int nw, int ksplit, int U);

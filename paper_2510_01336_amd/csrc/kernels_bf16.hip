@@ -161,9 +161,10 @@ void bf16_begin_pass(hipStream_t st, const bf16_t* emb, const int* tok, const fl
 // A task is one 16-row weight tile strip over the whole K, or two adjacent strips (NB = 2) when the
 // epilogue needs both at once: gate and up of the same features (SwiGLU), or the two rotary halves of
 // a head (RoPE).  A workgroup of nw waves runs nw/ksplit tasks; the ksplit waves of a task split K
-// into contiguous chunks, each wave streaming its chunk (1 KiB per MFMA step) through a two-stage
-// register pipeline of depth U; the partial 16x16 tiles are then summed through LDS in a fixed
-// order (deterministic) and the task's first wave runs the epilogue.
+// into contiguous chunks, each wave streaming its chunk (1 KiB per MFMA step) through two register
+// sets of U k-tiles that take turns (one in flight while the other is multiplied); the partial 16x16
+// tiles are then summed through LDS in a fixed order (deterministic) and the task's first wave runs
+// the epilogue.
 // The MFMA computes Y^T = W X^T so that a lane ends up with 4 consecutive n of one row m.
 //
 // Epilogues (everything between two projections is fused here, so a layer is five launches):
@@ -920,29 +921,26 @@ static void launch_gemm_mt(hipStream_t st, int epi, const uint4* W, int ntiles, 
 #undef SKINNY_LAUNCH
 }
 
-// launch shape: nw waves per workgroup, ksplit of them per task, register pipeline depth U (2, 4 or 8)
+// launch shape: nw waves per workgroup, ksplit of them per task, k-tiles per register set U (4 or 8; 4 at 17..32 rows)
 void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N,
                    const GemmOut& out, int nw, int ksplit, int U) {
   const uint4* Wc = (const uint4*)W;
   const uint4* Ac = (const uint4*)A;
-  for (int m0 = 0; m0 < M; m0 += 64) {
-    const int mc = min(64, M - m0);
+  // (the session sends calls of more than 32 rows to the row-tiled kernel; should one arrive here it goes in passes of 32)
+  for (int m0 = 0; m0 < M; m0 += 32) {
+    const int mc = min(32, M - m0);
     if (mc <= 16) {
       if (U >= 8) launch_gemm_mt<1, 8>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
-      else if (U >= 4) launch_gemm_mt<1, 4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
-      else launch_gemm_mt<1, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
-    } else if (mc <= 32) {
-      if (U >= 4) launch_gemm_mt<2, 4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
-      else launch_gemm_mt<2, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
+      else launch_gemm_mt<1, 4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
     } else {
-      launch_gemm_mt<4, 2>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
+      launch_gemm_mt<2, 4>(st, epi, Wc, ntiles, ktiles, Ac, m0, mc, N, out, nw, ksplit);
     }
   }
 }
 
 // Launch shape by task count (measured on MI355X at M <= 16): many tasks -> one wave streams a whole
 // strip (no reduction, deepest pipeline); few tasks -> split K over the waves of a workgroup so that
-// about two thousand waves are in flight.  M may exceed 64: rows go in passes of 64 (weights re-streamed).
+// about two thousand waves are in flight.  M may exceed 32: rows then go in passes of 32 (weights re-streamed).
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out) {
   const int ntasks = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? ntiles / 2 : ntiles;
   // launch shape by task count, from sweeps over the 8B and 70B matrix shapes at 9 rows
