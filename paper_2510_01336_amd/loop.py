@@ -96,23 +96,34 @@ def hispec_generate(sess, n_new: int, k: int, *, n_i: Optional[int] = None, ever
     return np.array([o[:n_new] for o in out], np.int32), st
 
 
-def hispec_generate_levels(sess, n_new: int, k: int, windows: Sequence[int]):
+def hispec_generate_levels(sess, n_new: int, k: int, windows: Sequence[int], rng: Optional[np.random.Generator] = None):
     """The decoding loop over a chain of verifier exits (models with extra exits; ee_verify_level).
 
     Every iteration drafts k tokens and checks them at level 1 (L_i).  A sequence then climbs: level j runs
     for it when level j-1 has just run for it and the tokens waiting below level j number at least
     windows[j-2] (the per-stage windows N_{i,1}, N_{i,2}, ... of the paper's Future Work section), or when the
-    sequence already holds enough tokens and is being flushed.  The last level commits.  Returns (tokens
-    [batch, n_new], {"calls", "checked", "accepted"}: per level, index 0 unused).
+    sequence already holds enough tokens and is being flushed.  The last level commits.  With rng the calls are the
+    ones of the rejection-sampling acceptance of App. G (ee_draft_sample, ee_verify_intermediate_rs,
+    ee_verify_level_rs, ee_verify_full_rs; the session's sampling buffers must be attached) and rng supplies their
+    uniform numbers; without it the greedy ones.  Returns (tokens [batch, n_new], {"calls", "checked", "accepted"}:
+    per level, index 0 unused).
     """
     n = sess.n_levels()
     assert len(windows) == n - 1 and all(w >= 1 for w in windows)
     B = sess.batch
     out: List[List[int]] = [[] for _ in range(B)]
     stats = {"calls": [0] * (n + 1), "checked": [0] * (n + 1), "accepted": [0] * (n + 1)}
+
+    def uniforms():
+        return rng.random((B, sess.max_rows), np.float32), rng.random(B, np.float32)
+
     while min(len(o) for o in out) < n_new:
-        sess.draft(k)
-        a, _ = sess.verify_intermediate()
+        if rng is None:
+            sess.draft(k)
+            a, _ = sess.verify_intermediate()
+        else:
+            sess.draft_sample(k, rng.random((B, k), np.float32))
+            a, _ = sess.verify_intermediate_rs(rng.random((B, k), np.float32), rng.random(B, np.float32))
         stats["calls"][1] += 1
         stats["checked"][1] += B * k
         stats["accepted"][1] += int(a.sum())
@@ -125,7 +136,10 @@ def hispec_generate_levels(sess, n_new: int, k: int, windows: Sequence[int]):
             if not act.any():
                 break
             mask = act.astype(np.uint8)
-            f, _, moved = sess.verify_level(j, mask) if j < n else sess.verify_full(mask)
+            if rng is None:
+                f, _, moved = sess.verify_level(j, mask) if j < n else sess.verify_full(mask)
+            else:
+                f, _, moved = sess.verify_level_rs(j, *uniforms(), mask) if j < n else sess.verify_full_rs(*uniforms(), mask)
             stats["calls"][j] += 1
             stats["checked"][j] += int(waiting[act].sum())
             stats["accepted"][j] += int(np.minimum(f, waiting)[act].sum())

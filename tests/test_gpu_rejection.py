@@ -260,3 +260,30 @@ def test_chain_of_verifiers_under_the_sampling_rule_matches_oracle():
     assert e.value.code == -2
     sess.verify_full()
     sess.close(); model.close()
+
+
+@pytest.mark.gpu
+def test_chain_loop_under_the_sampling_rule_runs_on_the_gpu():
+    """The host loop over a chain of exits with App. G's acceptance at each (loop.hispec_generate_levels with rng):
+    every call succeeds, each sequence gets its tokens, what the loop returns is what the session committed, and the
+    same uniform numbers give the same stream again."""
+    from paper_2510_01336_amd.loop import hispec_generate_levels
+    cfg = synth.EEConfig(n_layers=8, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_ffn=688, vocab=1024,
+                         exit_draft=2, exit_inter=4, exit_extra=(6,), rope_theta=10000.0, dtype="f32", gamma=(1.0, 0.3, 0.3))
+    k, n_new, ctxs = 4, 20, [40, 23]
+    prompts = [synth.gen_prompt(cfg.vocab, n, 300 + b) for b, n in enumerate(ctxs)]
+    streams = []
+    for rep in range(2):
+        model, sess = gpu_side(cfg, 77, len(ctxs), max(ctxs) + n_new + 16 * (k + 2), 4 * (k + 2))
+        sess.enable_sampling()
+        sess.prefill(prompts)
+        toks, stats = hispec_generate_levels(sess, n_new, k, [3, 4], rng=np.random.default_rng(21))
+        assert toks.shape == (len(ctxs), n_new) and all(c > 0 for c in stats["calls"][1:])
+        assert all(0 <= a <= c for a, c in zip(stats["accepted"][1:], stats["checked"][1:]))
+        nc, _ = sess.counts()
+        for b in range(len(ctxs)):
+            committed = sess.tokens(b)[ctxs[b] + 1:int(nc[b])].tolist()
+            assert committed[:n_new] == toks[b].tolist()
+        streams.append(toks)
+        sess.close(); model.close()
+    assert np.array_equal(streams[0], streams[1])
