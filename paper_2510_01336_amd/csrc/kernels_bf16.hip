@@ -167,7 +167,7 @@ void bf16_begin_pass(hipStream_t st, const bf16_t* emb, const int* tok, const fl
 // the epilogue.
 // The MFMA computes Y^T = W X^T so that a lane ends up with 4 consecutive n of one row m.
 //
-// Epilogues (everything between two projections is fused here, so a layer is five launches):
+// Epilogues (everything between two projections is fused here, so a layer is five launches, six when the attention is split over the KV axis and merged):
 //   EPI_ADD     residual add into the fp32 stream; optionally emits the next projection's operand
 //               bf16(x_new * gain) and this tile's partial sum of squares per row (deferred RMSNorm)
 //   EPI_SWIGLU  silu(gate) * up  -> bf16 operand of the down projection

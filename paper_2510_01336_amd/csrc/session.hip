@@ -437,7 +437,7 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
     const float* g1 = (const float*)(m->base + L.g1);
     const float* g2 = (const float*)(m->base + L.g2);
     if (m->bf16) {
-      // five launches per layer; RMSNorm is deferred into the projections (see NormIn / NormOut)
+      // five launches per layer (six with the merge of a split attention); RMSNorm is deferred into the projections (see NormIn / NormOut)
       const int Mp = s->Mp;
       NormIn nin;         // operand left by the previous EPI_ADD launch
       nin.ssq = s->ssq; nin.n_part = d / 16; nin.stride = Mp; nin.inv_d = 1.0f / (float)d; nin.eps = c.rms_eps;
