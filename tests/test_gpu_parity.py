@@ -77,6 +77,12 @@ CASES = [
     ("tiny_f32_heads", synth.tiny_config(gamma=(1.0, 0.3, 0.3), head_rank=24), [32, 70], 4, (True, True)),
     ("bf16_small_heads", bf16_small(head_rank=64), [150, 40], 8, (True, True)),
     ("bf16_d128_heads_batch16", bf16_d128(head_rank=96), [100, 260, 31, 64, 65, 7, 190, 128, 40, 77, 300, 12, 55, 201, 99, 160], 8, (True, True)),
+    # K shares of the weight-streaming GEMM that end in every way its pipeline distinguishes: d_ffn 3584 = 4 shares
+    # of 28 k-tiles (a pair of full groups of 8, then a full and a short one), d_ffn 2560 = 4 x 20 (a pair, then one short
+    # group); 9 rows (one row tile, 8 k-tiles per register set) and 18 rows (two row tiles, 4 per set)
+    ("bf16_k_tail_28", bf16_small(d_ffn=3584), [90], 8, (True, True)),
+    ("bf16_k_tail_28_rows18", bf16_small(d_ffn=3584), [90, 41], 8, (True, True)),
+    ("bf16_k_tail_20", bf16_small(d_ffn=2560), [70, 33], 8, (True, True)),
 ]
 
 
