@@ -383,8 +383,8 @@ def cpu_baseline(w):
 
 
 def read_floor(w, acc, steps):
-    """What a kernel that only fetches the same bytes takes: plain reads of each projection's weight bytes, back to
-    back on the library's stream in a layer's order, each launch timed by events attached to its dispatch
+    """What a kernel that only fetches the same bytes takes: plain reads of each projection's weight bytes (and of the
+    cached K and V that one attention launch streams), back to back on the library's stream in a layer's order, each launch timed by events attached to its dispatch
     (ee_debug_read_floor).  A dependent launch of tens of MB runs well under the peak rate whatever its arithmetic, so
     this -- not bytes / 8 TB/s -- is what the projections can be held against; their own mean launch times of the
     instrumented pass stand beside it."""
@@ -397,6 +397,9 @@ def read_floor(w, acc, steps):
              "gemm_gate_up": 2 * cfg.d_ffn * d * es, "gemm_down": cfg.d_ffn * d * es, "gemm_head": cfg.vocab * d * es}
     if cfg.head_rank:
         del sizes["gemm_head"]               # (low-rank exit heads: two small products, not one stream of this size)
+    # attention (kernel + merge of the KV splits): the cached K and V of every sequence, once per layer
+    kv = sum(c + w["k"] + 1 for c in w["ctxs"]) * cfg.n_kv_heads * dh * 2 * es
+    sizes["attention"] = (kv + 15) // 16 * 16
     names = list(sizes)
     buf = torch.full((sum(sizes.values()),), 3, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
@@ -405,7 +408,7 @@ def read_floor(w, acc, steps):
     out = {}
     for n, t in zip(names, us):
         k_ms, k_n = acc.get(n, (0.0, 0))
-        out[n] = {"weight_bytes": sizes[n], "plain_read_us": t, "plain_read_GBs": sizes[n] / t / 1e3,
+        out[n] = {"bytes": sizes[n], "plain_read_us": t, "plain_read_GBs": sizes[n] / t / 1e3,
                   "kernel_us": 1e3 * k_ms / k_n if k_n else None,
                   "plain_read_over_kernel": t / (1e3 * k_ms / k_n) if k_n else None}
     return out
