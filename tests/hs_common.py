@@ -28,14 +28,17 @@ STATS = {}    # name -> largest value seen in this test session (printed by conf
 
 
 def progress(msg):
-    """One line per finished step of a long test into gpurun_out/ (when that folder exists): the full-width
-    oracle passes take minutes of host time during which pytest itself prints nothing."""
+    """One line per finished step of a long test, flushed to stderr and -- when HISPEC_PROGRESS_LOG names a file --
+    appended there: the full-width oracle passes take a while of host time during which pytest itself prints nothing."""
     import os
+    import sys
     import time
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
-        with open(os.path.join(d, "pytest_progress.log"), "a") as f:
-            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+    line = f"{time.strftime('%H:%M:%S')} {msg}"
+    print(line, file=sys.stderr, flush=True)
+    path = os.environ.get("HISPEC_PROGRESS_LOG")
+    if path:
+        with open(path, "a") as f:
+            f.write(line + "\n")
 
 
 def note(name, value):
