@@ -58,6 +58,7 @@ struct RopeOut {
 };
 struct GemmOut {
   float* Y = nullptr; int ldy = 0;        // EPI_ADD: residual stream, Y += product (row-major fp32); EPI_ARGMAX: optional logits
+  float* Y2 = nullptr; const int* y2_idx = nullptr; int y2_add = 0;   // EPI_ADD: the new rows also go to Y2[y2_idx[row] + y2_add] (kept hidden rows of an exit)
   bf16_t* H = nullptr; int h_ktiles = 0;  // EPI_SWIGLU target (fragment layout)
   float* pmax = nullptr; int* pidx = nullptr; int pstride = 0;   // EPI_ARGMAX partials [row][pstride >= ntiles]
   NormIn nin;

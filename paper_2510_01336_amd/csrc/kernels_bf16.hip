@@ -183,6 +183,7 @@ struct EpiPre {            // operands of the epilogue that do not depend on the
   float4 res, gnext;       // EPI_ADD: residual row slice, gains of the next operand
   float4 rc01, rc23;       // EPI_ROPE: (cos, sin) of the lane's four rotary pairs
   int r_a, r_b;            // EPI_ROPE: Q heads: (global q-tile, row in tile); K/V heads: (page, position in page)
+                           // EPI_ADD: r_a = row of the second destination
 };
 
 template <int EPI>
@@ -195,6 +196,7 @@ __device__ inline void epi_prefetch(EpiPre& p, const GemmOut& out, int task, int
     const int n = task * 16 + 4 * g;
     if (ok) p.res = *(const float4*)(out.Y + (size_t)row * out.ldy + n);
     if (out.nout.xn) p.gnext = *(const float4*)(out.nout.g + n);
+    if (out.Y2 && ok) p.r_a = out.y2_idx[row] + out.y2_add;
   }
   if (EPI == EPI_ROPE && ok) {
     const RopeOut& R = out.rope;
@@ -224,6 +226,7 @@ __device__ inline void epi_apply(const f32x4& acc0, const f32x4& acc1, float sc,
     float4 r = make_float4(acc0[0] * sc, acc0[1] * sc, acc0[2] * sc, acc0[3] * sc);
     r.x += p.res.x; r.y += p.res.y; r.z += p.res.z; r.w += p.res.w;
     if (ok) *(float4*)(out.Y + (size_t)row * out.ldy + n) = r;
+    if (out.Y2 && ok) *(float4*)(out.Y2 + (size_t)p.r_a * out.ldy + n) = r;
     if (out.nout.xn) {
       const float4 gn = p.gnext;
       if (ok) *(uint2*)(out.nout.xn + frag_offset(row, n, out.nout.ktiles)) = make_uint2(pack2(r.x * gn.x, r.y * gn.y), pack2(r.z * gn.z, r.w * gn.w));

@@ -414,8 +414,14 @@ struct PassSource {
   const int* tok = nullptr;
   const float* rows = nullptr; const int* row_idx = nullptr;
 };
+// where the hidden rows behind the last layer of a pass are kept besides the stream (H_d, H_i, a level's rows): row r
+// goes to rows[row_idx[r] + add]; the last down projection's epilogue writes them
+struct PassSink {
+  float* rows = nullptr; const int* row_idx = nullptr; int add = 0;
+};
 
-static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const CallMeta& mt, int pos_add, const PassSource& src = PassSource()) {
+static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const CallMeta& mt, int pos_add, const PassSource& src = PassSource(),
+                       const PassSink& sink = PassSink()) {
   const ee_model* m = s->m;
   const ee_config& c = m->cfg;
   const int d = c.d_model, D = c.head_dim, Hq = c.n_q_heads, Hkv = c.n_kv_heads, M = p.M;
@@ -459,6 +465,7 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
       // projection, or the shared exit head behind the last layer of the pass
       o = GemmOut(); o.Y = s->X; o.ldy = d; o.nout = nout;
       o.nout.g = l + 1 < l1 ? (const float*)(m->base + m->L[l + 1].g1) : (const float*)(m->base + closing_gain(m, l1));
+      if (l + 1 == l1) { o.Y2 = sink.rows; o.y2_idx = sink.row_idx; o.y2_add = sink.add; }
       KF(KF_GEMM_DOWN, gemm(s, EPI_ADD, L.down, (const bf16_t*)s->H, M, o));
     } else {
       const float* Wqkv = (const float*)(m->base + L.qkv.off);
@@ -477,6 +484,7 @@ static void run_layers(ee_session* s, int l0, int l1, const CallPlan& p, const C
       KF(KF_GEMM_DOWN, f32_gemm(st, (const float*)s->H, c.d_ffn, Wd, s->X, d, M, d, c.d_ffn, true));
     }
   }
+  if (sink.rows && (!m->bf16 || l0 >= l1)) KF(KF_COPY, k_copy_rows(st, sink.rows, sink.row_idx, sink.add, s->X, nullptr, M, d));
 }
 
 // Prediction head of exit `which` (0 = L_d, 1 = L_i, ..., n_levels = L_f) + arg max for rows 0..M-1 of X -> vtok.
@@ -761,8 +769,8 @@ static int draft_impl(ee_session* s, int k, int32_t* draft, const float* u) {
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
   for (int j = 0; j < rows; ++j) {
     PassSource from_tokens; from_tokens.tok = j == 0 ? mt.row_tok : s->tok_next;
-    run_layers(s, 0, c.exit_draft, p, mt, j, from_tokens);
-    KF(KF_COPY, k_copy_rows(s->st, s->Hd, mt.row_dst, j, s->X, nullptr, p.M, c.d_model));
+    PassSink keep; keep.rows = s->Hd; keep.row_idx = mt.row_dst; keep.add = j;
+    run_layers(s, 0, c.exit_draft, p, mt, j, from_tokens, keep);
     if (j < k) {
       exit_head(s, p.M, 0);
       if (u) {      // p_{L_d} of this position into the draft-distribution store, then the draw
@@ -821,8 +829,8 @@ extern "C" int ee_draft_inject(ee_session* s, int k, const int32_t* draft) {
   EE_TRY(upload_meta(s, 0));
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
   PassSource from_tokens; from_tokens.tok = mt.row_tok;
-  run_layers(s, 0, c.exit_draft, p, mt, 0, from_tokens);
-  KF(KF_COPY, k_copy_rows(s->st, s->Hd, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));
+  PassSink keep; keep.rows = s->Hd; keep.row_idx = mt.row_dst;
+  run_layers(s, 0, c.exit_draft, p, mt, 0, from_tokens, keep);
   HIP_TRY(hipGetLastError());
   for (int b = 0; b < s->B; ++b) {
     SeqState& q = s->seq[b];
@@ -966,11 +974,11 @@ static int verify_intermediate_impl(ee_session* s, int32_t* n_accept, int32_t* n
   EE_TRY(upload_meta(s, 0));
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
   PassSource kept; kept.rows = s->Hd; kept.row_idx = mt.row_src;       // a1: consume buffered H_d
-  run_layers(s, c.exit_draft, c.exit_inter, p, mt, 0, kept);
+  PassSink keep; keep.rows = s->Hi; keep.row_idx = mt.row_dst;          // keep L_i hidden rows
+  run_layers(s, c.exit_draft, c.exit_inter, p, mt, 0, kept, keep);
   s->need_logits = rs;
   exit_head(s, p.M, 1);
   s->need_logits = false;
-  KF(KF_COPY, k_copy_rows(s->st, s->Hi, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));       // keep L_i hidden rows
   if (rs) {
     KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->LOGITS, nullptr, 0, p.M, c.vocab));          // p_{L_i}, in place
     KF(KF_ACCEPT, k_rs_accept(s->st, s->LOGITS, s->Pd, s->max_rows, c.vocab, mt, s->cand_stride, s->B, s->u_dev, s->max_rows, s->out_dev));
@@ -1092,8 +1100,8 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
     EE_TRY(upload_meta(s, 1));
     CallMeta mt = meta_ptrs(s, s->slot[1].d);
     PassSource from_tokens; from_tokens.tok = mt.row_tok;
-    run_layers(s, 0, ex[j - 1], p, mt, 0, from_tokens);
-    KF(KF_COPY, k_copy_rows(s->st, rows_below, mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));
+    PassSink keep; keep.rows = rows_below; keep.row_idx = mt.row_dst;
+    run_layers(s, 0, ex[j - 1], p, mt, 0, from_tokens, keep);
   }
   CallPlan p;
   p.m.assign(s->B, 0); p.p0.assign(s->B, 0);
@@ -1114,11 +1122,12 @@ static int verify_upper_impl(ee_session* s, int level, const uint8_t* active, in
   EE_TRY(upload_meta(s, 0));
   CallMeta mt = meta_ptrs(s, s->slot[0].d);
   PassSource kept; kept.rows = rows_below; kept.row_idx = mt.row_src;  // consume the buffered rows
-  run_layers(s, ex[j - 1], ex[j], p, mt, 0, kept);
+  PassSink keep;
+  if (j < n) { keep.rows = level_rows(s, j); keep.row_idx = mt.row_dst; }   // keep exit j's rows
+  run_layers(s, ex[j - 1], ex[j], p, mt, 0, kept, keep);
   s->need_logits = rs;
   exit_head(s, p.M, j);
   s->need_logits = false;
-  if (j < n) KF(KF_COPY, k_copy_rows(s->st, level_rows(s, j), mt.row_dst, 0, s->X, nullptr, p.M, c.d_model));   // keep exit j's rows
   if (rs) {      // a further stage of App. G: the buffer below, distributed as exit j-1's p, is the draft; exit j's p the target
     const float* q_below = level_dist(s, j - 1);
     KF(KF_MISC, k_softmax_rows(s->st, s->LOGITS, c.vocab, s->LOGITS, nullptr, 0, p.M, c.vocab));
