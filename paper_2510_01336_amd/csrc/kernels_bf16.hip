@@ -943,11 +943,11 @@ void bf16_gemm_cfg(hipStream_t st, int epi, const bf16_t* W, int ntiles, int kti
 
 // Launch shape by task count (measured on MI355X at M <= 16): many tasks -> one wave streams a whole
 // strip (no reduction, deepest pipeline); few tasks -> split K over the waves of a workgroup so that
-// about two thousand waves are in flight.  M may exceed 32: rows then go in passes of 32 (weights re-streamed).
+// one to two thousand waves are in flight (the 70B projections with 320-512 tasks: two waves per task).  M may exceed 32: rows then go in passes of 32 (weights re-streamed).
 void bf16_gemm(hipStream_t st, int epi, const bf16_t* W, int ntiles, int ktiles, const bf16_t* A, int M, int N, const GemmOut& out) {
   const int ntasks = (epi == EPI_SWIGLU || epi == EPI_ROPE) ? ntiles / 2 : ntiles;
   // launch shape by task count, from sweeps over the 8B and 70B matrix shapes at 9 rows
-  int ksplit = ntasks >= 768 ? 1 : (ntasks >= 320 ? 4 : (ntasks >= 200 ? 8 : 4));
+  int ksplit = ntasks >= 768 ? 1 : (ntasks >= 320 ? 2 : (ntasks >= 200 ? 8 : 4));
   while (ksplit > 1 && ktiles / ksplit < 4) ksplit >>= 1;
   const int U = (ntasks >= 768 || ntasks < 200 || ktiles / ksplit >= 32) ? 8 : 4;
   const int nw = ksplit > 4 ? ksplit : 4;
